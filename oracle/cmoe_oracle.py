@@ -1,0 +1,254 @@
+"""FP64 CPU oracle of the clustered, compressed MoE FFN layer forward.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this module;
+only tests, the smoke check and the bench's CPU-baseline leg do.  It shares no
+code with the HIP library and never receives a value computed by it.
+
+What it computes (every function names the passage it follows):
+
+  * the expert weights are a per-cluster shared base plus a rank-r product of two
+    factors, W_e = W_base(c) + U_e V_e                      (Sec. 3.2, Eq. 7);
+  * the factors are stored as INT4 codes with one FP16 scale per group of q
+    consecutive codes; bases and routers are FP16           (Sec. 3.4);
+  * routing is two-stage: cluster logits z_g = u_g . x, the cluster with the
+    largest softmax probability wins (Eq. 9); inside it, logits l_i = v_i . x,
+    softmax over the cluster (Eq. 10), the k most probable experts are kept
+    (Sec. 3.3);
+  * the layer output is the gate-weighted sum of the k selected experts'
+    two-matrix GELU FFNs.
+
+`forward_naive` is the plain definition: every expert matrix is materialised
+densely and each selected expert's FFN is evaluated on its own.  `ffn_rewrite`
+is the same function in the method's cheaper form (base product once per token,
+Sec. 3.2 after Eq. 7; second matrix by linearity) and also returns the
+intermediates the HIP path exposes.  All arithmetic is float64 on the exact
+values of the FP16 / INT4 inputs.  numpy's float64 `@` is used as the matrix
+product primitive; nothing is blocked, fused or reordered beyond that.
+
+Readings where the paper is silent (also listed in the design notes):
+  - FFN form: y_e = W2_e GELU(W1_e x), no biases, GELU(u) = u/2 (1 + erf(u/sqrt 2)).
+  - W is out x in, y = W x; U_e is out x r, V_e is r x in; both factors are
+    stored rank-major [r][long dimension].
+  - Gates: softmax over the k selected in-cluster logits (equivalently the Eq. 10
+    probabilities of the selected experts renormalised to sum to one); the cluster
+    probability does not scale the output.
+  - Ties: the lowest index wins; the k experts are listed by descending logit.
+  - INT4: symmetric two's-complement codes in [-8, 7], value = scale * code, no
+    zero point; element n in byte n // 2, even n in the low nibble.
+  - An optional per-cluster bias may be added to the cluster logits (used only to
+    skew cluster loads in one benchmark configuration; None = the paper's form).
+
+Parity pins: see tests/test_oracle_pins.py.  The end-to-end output on the large
+configurations has no external value to pin to (the paper prints none): it is
+pinned through the naive-vs-rewrite identity, brute-force scalar loops on tiny
+inputs, and special cases that reduce to a dense FFN written with math.erf.
+"""
+from __future__ import annotations
+
+import numpy as np
+from scipy.special import erf as _erf
+
+
+# ---------------------------------------------------------------- Sec. 3.4
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    """uint8 [..., L/2] -> integer codes [..., L] in [-8, 7] (float64)."""
+    lo = (packed & 0x0F).astype(np.int16)
+    hi = (packed >> 4).astype(np.int16)
+    lo = np.where(lo >= 8, lo - 16, lo)
+    hi = np.where(hi >= 8, hi - 16, hi)
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.float64)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    return out
+
+
+def dequant_int4(packed: np.ndarray, scales: np.ndarray, q: int) -> np.ndarray:
+    """Stored factor -> float64 [..., L]: value[n] = scale[n // q] * code[n]  (Sec. 3.4)."""
+    codes = unpack_int4(packed)
+    s = np.repeat(scales.astype(np.float64), q, axis=-1)
+    assert s.shape == codes.shape
+    return s * codes
+
+
+# ---------------------------------------------------------------- Sec. 3.3
+def route(x, router_cluster, router_expert, K, k, cluster_bias=None):
+    """Two-stage routing (Sec. 3.3, Eq. 9 and Eq. 10).
+
+    Returns cluster_id [T] int32, expert_idx [T][k] int32 (global slot c*K + j,
+    descending logit), gate [T][k] float64, and the logits (z [T][G], l [T][K]).
+    """
+    X = x.astype(np.float64)
+    U = router_cluster.astype(np.float64)
+    V = router_expert.astype(np.float64)
+    T = X.shape[0]
+    z = X @ U.T
+    if cluster_bias is not None:
+        z = z + cluster_bias.astype(np.float64)[None, :]
+    # Eq. 9: p_g = softmax(z)_g; the largest p_g is the largest z_g.  argmax
+    # returns the first maximum = lowest index on ties.
+    cluster_id = np.argmax(z, axis=1).astype(np.int32)
+    l = np.empty((T, K), dtype=np.float64)
+    for c in range(U.shape[0]):
+        rows = np.nonzero(cluster_id == c)[0]
+        if len(rows):
+            l[rows] = X[rows] @ V[c * K:(c + 1) * K].T
+    # Eq. 10 then top-k: stable sort of -l lists equal logits by ascending index
+    order = np.argsort(-l, axis=1, kind="stable")[:, :k]
+    lsel = np.take_along_axis(l, order, axis=1)
+    ex = np.exp(lsel - lsel[:, :1])
+    gate = ex / ex.sum(axis=1, keepdims=True)
+    expert_idx = (cluster_id[:, None].astype(np.int64) * K + order).astype(np.int32)
+    return cluster_id, expert_idx, gate, z, l
+
+
+def permute(cluster_id, G):
+    """Stable counting sort of token indices by cluster (the single-device part of
+    group-level dispatch, Sec. 3.3).  Returns offsets [G+1], perm [T], inv_perm [T]."""
+    T = len(cluster_id)
+    counts = [0] * G
+    for t in range(T):
+        counts[int(cluster_id[t])] += 1
+    offsets = [0] * (G + 1)
+    for c in range(G):
+        offsets[c + 1] = offsets[c] + counts[c]
+    cursor = list(offsets[:G])
+    perm = np.empty(T, dtype=np.int32)
+    inv_perm = np.empty(T, dtype=np.int32)
+    for t in range(T):
+        c = int(cluster_id[t])
+        perm[cursor[c]] = t
+        inv_perm[t] = cursor[c]
+        cursor[c] += 1
+    return np.asarray(offsets, dtype=np.int32), perm, inv_perm
+
+
+# ---------------------------------------------------------------- Sec. 3.2
+def gelu(u):
+    return 0.5 * u * (1.0 + _erf(u / np.sqrt(2.0)))
+
+
+def _factors(w, q):
+    return {n: dequant_int4(w[n + "_q"], w[n + "_s"], q) for n in ("v1", "u1", "v2", "u2")}
+
+
+def expert_weights(w, e, K, q, f=None):
+    """Dense W1_e [d_ff][d] and W2_e [d][d_ff] of expert slot e (Eq. 7):
+    W_e = W_base(c) + U_e V_e with U_e = u[e].T (out x r) and V_e = v[e] (r x in)."""
+    f = f if f is not None else _factors(w, q)
+    c = e // K
+    W1 = w["w1_base"][c].astype(np.float64) + f["u1"][e].T @ f["v1"][e]
+    W2 = w["w2_base"][c].astype(np.float64) + f["u2"][e].T @ f["v2"][e]
+    return W1, W2
+
+
+def ffn_naive(w, x, expert_idx, gate, K, q):
+    """y[t] = sum_j gate[t][j] * W2_e GELU(W1_e x[t]),  e = expert_idx[t][j].  Each
+    expert matrix is materialised (Eq. 7) and applied to the tokens that chose it."""
+    X = x.astype(np.float64)
+    T, d = X.shape
+    k = expert_idx.shape[1]
+    y = np.zeros((T, d), dtype=np.float64)
+    f = _factors(w, q)
+    for e in np.unique(expert_idx):
+        W1, W2 = expert_weights(w, int(e), K, q, f)
+        for j in range(k):
+            rows = np.nonzero(expert_idx[:, j] == e)[0]
+            if len(rows) == 0:
+                continue
+            h = X[rows] @ W1.T
+            y[rows] += gate[rows, j][:, None] * (gelu(h) @ W2.T)
+    return y
+
+
+def forward_naive(w, x, K, k, q):
+    """The layer by its definition: route, then the selected experts' dense FFNs."""
+    G = w["router_cluster"].shape[0]
+    cluster_id, expert_idx, gate, _, _ = route(x, w["router_cluster"], w["router_expert"], K, k, w.get("cluster_bias"))
+    y = ffn_naive(w, x, expert_idx, gate, K, q)
+    offsets, perm, inv_perm = permute(cluster_id, G)
+    return dict(cluster_id=cluster_id, expert_idx=expert_idx, gate=gate, offsets=offsets, perm=perm,
+                inv_perm=inv_perm, y=y)
+
+
+def ffn_rewrite(w, x, perm, offsets, expert_idx, gate, K, q):
+    """The same function in the method's form (Sec. 3.2: the base product is shared by
+    all experts of the cluster that see the token; by linearity of the second base
+    matrix the gate-weighted sum is taken before it):
+
+      Hb  = W1_base(c) x                    t1_j = V1_e x
+      a_j = GELU(Hb + U1_e t1_j)            A    = sum_j g_j a_j
+      s_j = V2_e a_j                        y    = W2_base(c) A + sum_j g_j U2_e s_j
+
+    Rows of Hb, A, y_base_sorted, y_sorted are in cluster-sorted order (row p is
+    token perm[p]); t1 and s are [T][k][r] in token order.
+    """
+    X = x.astype(np.float64)
+    T, d = X.shape
+    k = expert_idx.shape[1]
+    G = len(offsets) - 1
+    f = _factors(w, q)
+    r = f["v1"].shape[1]
+    d_ff = w["w1_base"].shape[1]
+    Hb = np.zeros((T, d_ff))
+    A = np.zeros((T, d_ff))
+    t1 = np.zeros((T, k, r))
+    s = np.zeros((T, k, r))
+    y_base_sorted = np.zeros((T, d))
+    y_sorted = np.zeros((T, d))
+    for c in range(G):
+        lo, hi = int(offsets[c]), int(offsets[c + 1])
+        if hi == lo:
+            continue
+        toks = perm[lo:hi]
+        Hb[lo:hi] = X[toks] @ w["w1_base"][c].astype(np.float64).T
+    for p in range(T):
+        t = int(perm[p])
+        for j in range(k):
+            e = int(expert_idx[t, j])
+            t1[t, j] = f["v1"][e] @ X[t]
+            a = gelu(Hb[p] + f["u1"][e].T @ t1[t, j])
+            A[p] += gate[t, j] * a
+            s[t, j] = f["v2"][e] @ a
+    for c in range(G):
+        lo, hi = int(offsets[c]), int(offsets[c + 1])
+        if hi == lo:
+            continue
+        y_base_sorted[lo:hi] = A[lo:hi] @ w["w2_base"][c].astype(np.float64).T
+    y = np.zeros((T, d))
+    for p in range(T):
+        t = int(perm[p])
+        acc = y_base_sorted[p].copy()
+        for j in range(k):
+            e = int(expert_idx[t, j])
+            acc += gate[t, j] * (f["u2"][e].T @ s[t, j])
+        y_sorted[p] = acc
+        y[t] = acc
+    return dict(Hb=Hb, t1=t1, A=A, s=s, y_base_sorted=y_base_sorted, y_sorted=y_sorted, y=y)
+
+
+# ---------------------------------------------------------------- closed forms
+def storage_elements_per_group(d_in, d_out, K, r):
+    """Stored elements of one cluster's weight matrix after compression (Sec. 3.2)."""
+    return d_in * d_out + K * r * (d_in + d_out)
+
+
+def compression_ratio(d_in, d_out, K, r):
+    """Eq. 8."""
+    return K * d_in * d_out / storage_elements_per_group(d_in, d_out, K, r)
+
+
+def routing_flops_per_token(d, G, K):
+    """Two dot products of length d per logit, G + K logits (Sec. 3.3)."""
+    return 2 * d * (G + K)
+
+
+# ---------------------------------------------------------------- error metrics
+def error_metrics(y, y_ref):
+    """max|y - y_ref| / RMS(y_ref) and sum|y - y_ref| / sum|y_ref| (the two bars)."""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    diff = np.abs(y - y_ref)
+    rms = np.sqrt(np.mean(y_ref ** 2))
+    return dict(max_over_rms=float(diff.max() / rms) if diff.size else 0.0,
+                mean_rel=float(diff.sum() / np.abs(y_ref).sum()) if diff.size else 0.0,
+                rms=float(rms))

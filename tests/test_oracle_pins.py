@@ -1,0 +1,350 @@
+"""Pins of the FP64 oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU.  Each pins one part of oracle/cmoe_oracle.py to
+something other than itself: hand-typed tables, brute-force scalar loops, library
+routines of a different implementation (math.erf, numpy stable argsort), closed
+forms the paper states, and invariants of the method.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import cmoe_inputs as ci
+from oracle import cmoe_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_closed_forms.txt")
+
+
+def _golden():
+    out = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split()
+            out[k] = float(v)
+    return out
+
+
+# ------------------------------------------------------------------ INT4 (Sec. 3.4)
+def test_int4_all_codes_both_nibbles():
+    # two's-complement table typed by hand
+    table = {0: 0, 1: 1, 2: 2, 3: 3, 4: 4, 5: 5, 6: 6, 7: 7, 8: -8, 9: -7, 10: -6, 11: -5, 12: -4, 13: -3, 14: -2, 15: -1}
+    for lo in range(16):
+        for hi in range(16):
+            b = np.array([[lo | (hi << 4)]], dtype=np.uint8)
+            codes = orc.unpack_int4(b)
+            assert codes.shape == (1, 2)
+            assert codes[0, 0] == table[lo] and codes[0, 1] == table[hi]
+    for scale in (0.0, 1.0, 0.0123, 6.1e-5, 1024.0):
+        s16 = np.array([[scale]], dtype=np.float16)
+        packed = np.arange(256, dtype=np.uint8).reshape(1, 256)
+        # one group covering all 512 elements
+        val = orc.dequant_int4(packed, s16, 512)
+        for byte in range(256):
+            assert val[0, 2 * byte] == float(s16[0, 0]) * table[byte & 15]
+            assert val[0, 2 * byte + 1] == float(s16[0, 0]) * table[byte >> 4]
+
+
+def test_int4_group_boundaries_and_roundtrip():
+    rng = np.random.default_rng(1)
+    w = rng.standard_normal((3, 2, 128)) * 0.02
+    q = 32
+    packed, scales = ci.quantize_int4(w, q)
+    assert packed.shape == (3, 2, 64) and scales.shape == (3, 2, 4)
+    val = orc.dequant_int4(packed, scales, q)
+    # element n uses scale n // q: check by a scalar loop
+    for e in range(3):
+        for rr in range(2):
+            for n in range(128):
+                byte = int(packed[e, rr, n // 2])
+                code = (byte >> 4) if (n & 1) else (byte & 15)
+                code = code - 16 if code >= 8 else code
+                assert val[e, rr, n] == float(scales[e, rr, n // q]) * code
+    # quantisation error at most half a step (plus the fp16 rounding of the scale)
+    step = np.repeat(scales.astype(np.float64), q, axis=-1)
+    assert np.all(np.abs(val - w) <= 0.5 * step * (1 + 2e-3) + 1e-12)
+    # an all-zero group decodes to exact zeros
+    w[0, 0, :32] = 0
+    packed, scales = ci.quantize_int4(w, q)
+    assert np.all(orc.dequant_int4(packed, scales, q)[0, 0, :32] == 0)
+
+
+# ------------------------------------------------------------------ routing (Sec. 3.3)
+def _brute_route(x, rc, re, K, k, bias):
+    T, d = x.shape
+    G = rc.shape[0]
+    cid, eidx, gates = [], [], []
+    for t in range(T):
+        z = [sum(float(rc[g, i]) * float(x[t, i]) for i in range(d)) + (float(bias[g]) if bias is not None else 0.0)
+             for g in range(G)]
+        # Eq. 9 softmax, then the most probable group
+        m = max(z)
+        p = [math.exp(v - m) for v in z]
+        sp = sum(p)
+        p = [v / sp for v in p]
+        c = max(range(G), key=lambda g: (p[g], -g))
+        l = [sum(float(re[c * K + j, i]) * float(x[t, i]) for i in range(d)) for j in range(K)]
+        m = max(l)
+        pe = [math.exp(v - m) for v in l]
+        spe = sum(pe)
+        pe = [v / spe for v in pe]                       # Eq. 10
+        order = sorted(range(K), key=lambda j: (-pe[j], j))[:k]
+        tot = sum(pe[j] for j in order)
+        cid.append(c)
+        eidx.append([c * K + j for j in order])
+        gates.append([pe[j] / tot for j in order])
+    return np.array(cid), np.array(eidx), np.array(gates)
+
+
+@pytest.mark.parametrize("G,K,k", [(2, 4, 1), (2, 4, 2), (4, 4, 2), (3, 5, 3), (1, 8, 2), (4, 2, 2)])
+def test_route_matches_bruteforce_softmax_argsort(G, K, k):
+    cfg = ci.small_config(T=48, d=24, d_ff=32, G=G, K=K, r=4, k=k, q=8, seed=100 + G * 10 + K)
+    w = ci.generate(cfg, with_weights=False)
+    bias = np.linspace(-0.3, 0.3, G).astype(np.float32)
+    for b in (None, bias):
+        cid, eidx, gate, z, l = orc.route(w["x"], w["router_cluster"], w["router_expert"], K, k, b)
+        bc, be, bg = _brute_route(w["x"], w["router_cluster"], w["router_expert"], K, k, b)
+        assert np.array_equal(cid, bc)
+        assert np.array_equal(eidx, be)
+        assert np.allclose(gate, bg, rtol=1e-12, atol=1e-15)
+        assert np.allclose(gate.sum(axis=1), 1.0, atol=1e-14)
+        assert cid.dtype == np.int32 and eidx.dtype == np.int32
+
+
+def test_route_special_cases():
+    cfg = ci.small_config(T=64, d=32, G=2, K=4, k=1, q=8)
+    w = ci.generate(cfg, with_weights=False)
+    _, eidx, gate, _, l = orc.route(w["x"], w["router_cluster"], w["router_expert"], 4, 1)
+    assert np.all(gate == 1.0)                         # k = 1: the gate is exactly one
+    # K = k: every expert of the cluster is selected, gates are the Eq. 10 probabilities
+    cid, eidx, gate, _, l = orc.route(w["x"], w["router_cluster"], w["router_expert"], 4, 4)
+    assert np.array_equal(np.sort(eidx - cid[:, None] * 4, axis=1), np.tile(np.arange(4), (64, 1)))
+    p = np.exp(l) / np.exp(l).sum(axis=1, keepdims=True)
+    assert np.allclose(np.sort(gate, axis=1), np.sort(p, axis=1), rtol=1e-12)
+    # G = 1: a flat top-k router over all experts
+    cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"][:1], w["router_expert"][:4], 4, 2)
+    assert np.all(cid == 0)
+    full = w["x"].astype(np.float64) @ w["router_expert"][:4].astype(np.float64).T
+    assert np.array_equal(eidx, np.argsort(-full, axis=1, kind="stable")[:, :2])
+
+
+def test_route_ties_lowest_index_wins():
+    x = np.ones((3, 8), dtype=np.float16)
+    rc = np.zeros((3, 8), dtype=np.float16)            # all cluster logits equal -> cluster 0
+    re = np.zeros((12, 8), dtype=np.float16)
+    re[1] = 1
+    re[2] = 1                                          # experts 1 and 2 tie for first
+    cid, eidx, gate, _, _ = orc.route(x, rc, re, 4, 3)
+    assert np.all(cid == 0)
+    assert np.array_equal(eidx[0], [1, 2, 0])
+    assert gate[0, 0] == gate[0, 1]
+
+
+def test_input_margin_is_enforced():
+    for cfg in (ci.config(0), ci.small_config(T=512, d=32, G=4, K=4, k=2, q=8)):
+        w = ci.generate(cfg, with_weights=False)
+        _, _, _, z, l = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
+        zs = np.sort(z, axis=1)
+        assert np.all(zs[:, -1] - zs[:, -2] >= ci.MARGIN)
+        ls = -np.sort(-l, axis=1)
+        for a in range(min(cfg.k + 1, cfg.K) - 1):
+            assert np.all(ls[:, a] - ls[:, a + 1] >= ci.MARGIN)
+
+
+# ------------------------------------------------------------------ permutation
+@pytest.mark.parametrize("T,G", [(0, 3), (1, 1), (257, 4), (1000, 8)])
+def test_permute_matches_stable_argsort(T, G):
+    rng = np.random.default_rng(T + G)
+    cid = rng.integers(0, G, size=T).astype(np.int32)
+    if T > 10:
+        cid[cid == 1] = 0                              # leave a cluster empty
+    offsets, perm, inv = orc.permute(cid, G)
+    assert np.array_equal(perm, np.argsort(cid, kind="stable"))
+    assert np.array_equal(offsets, np.concatenate([[0], np.cumsum(np.bincount(cid, minlength=G))]))
+    assert np.array_equal(inv[perm], np.arange(T))
+    assert np.array_equal(perm[inv], np.arange(T))
+    assert np.all(np.diff(cid[perm]) >= 0)
+
+
+# ------------------------------------------------------------------ FFN value
+def _gelu_scalar(u):
+    return 0.5 * u * (1.0 + math.erf(u / math.sqrt(2.0)))
+
+
+def test_gelu_spot_values_and_identities():
+    u = np.linspace(-6, 6, 241)
+    g = orc.gelu(u)
+    assert orc.gelu(np.array([0.0]))[0] == 0.0
+    assert np.allclose(g - orc.gelu(-u), u, atol=1e-15)             # GELU(u) - GELU(-u) = u
+    assert np.allclose(g, [_gelu_scalar(v) for v in u], rtol=1e-14, atol=1e-16)
+    assert abs(orc.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
+
+
+def _brute_forward(w, x, K, k, q):
+    """Every sum written out as scalar loops, straight from the definition."""
+    T, d = x.shape
+    G, d_ff, _ = w["w1_base"].shape
+    E = G * K
+    r = w["v1_q"].shape[1]
+
+    def deq(name, e, rho, n):
+        byte = int(w[name + "_q"][e, rho, n // 2])
+        code = (byte >> 4) if (n & 1) else (byte & 15)
+        code = code - 16 if code >= 8 else code
+        return float(w[name + "_s"][e, rho, n // q]) * code
+
+    cid, eidx, gate = _brute_route(x, w["router_cluster"], w["router_expert"], K, k, w.get("cluster_bias"))
+    y = np.zeros((T, d))
+    for t in range(T):
+        c = int(cid[t])
+        for jj in range(k):
+            e = int(eidx[t, jj])
+            h = []
+            for o in range(d_ff):
+                acc = 0.0
+                for i in range(d):
+                    wv = float(w["w1_base"][c, o, i]) + sum(deq("u1", e, rho, o) * deq("v1", e, rho, i) for rho in range(r))
+                    acc += wv * float(x[t, i])
+                h.append(_gelu_scalar(acc))
+            for o in range(d):
+                acc = 0.0
+                for i in range(d_ff):
+                    wv = float(w["w2_base"][c, o, i]) + sum(deq("u2", e, rho, o) * deq("v2", e, rho, i) for rho in range(r))
+                    acc += wv * h[i]
+                y[t, o] += gate[t, jj] * acc
+    return cid, eidx, gate, y
+
+
+def test_forward_matches_scalar_bruteforce():
+    cfg = ci.small_config(T=6, d=8, d_ff=12, G=2, K=3, r=2, k=2, q=4, factor_std=0.3, seed=7)
+    w = ci.generate(cfg)
+    out = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    cid, eidx, gate, y = _brute_forward(w, w["x"], cfg.K, cfg.k, cfg.q)
+    assert np.array_equal(out["cluster_id"], cid)
+    assert np.array_equal(out["expert_idx"], eidx)
+    assert np.allclose(out["gate"], gate, rtol=1e-12)
+    assert np.allclose(out["y"], y, rtol=1e-11, atol=1e-13)
+    # the factors are large enough here that dropping any residual term is visible
+    w0 = dict(w)
+    for n in ("u1", "u2"):
+        w0[n + "_s"] = np.zeros_like(w[n + "_s"])
+    y0 = orc.forward_naive(w0, w["x"], cfg.K, cfg.k, cfg.q)["y"]
+    assert np.abs(y0 - y).max() > 1e-2 * np.abs(y).max()
+
+
+def test_single_expert_zero_residual_is_dense_ffn():
+    # G = K = k = 1 and zero residuals: the layer is W2 GELU(W1 x)
+    cfg = ci.small_config(T=5, d=16, d_ff=24, G=1, K=1, r=2, k=1, q=8, seed=3)
+    w = ci.generate(cfg)
+    for n in ("v1", "u1", "v2", "u2"):
+        w[n + "_s"] = np.zeros_like(w[n + "_s"])
+    y = orc.forward_naive(w, w["x"], 1, 1, cfg.q)["y"]
+    W1 = w["w1_base"][0].astype(np.float64)
+    W2 = w["w2_base"][0].astype(np.float64)
+    X = w["x"].astype(np.float64)
+    ref = np.zeros_like(y)
+    for t in range(5):
+        h = [_gelu_scalar(v) for v in W1 @ X[t]]
+        ref[t] = W2 @ np.array(h)
+    assert np.allclose(y, ref, rtol=1e-13, atol=1e-15)
+
+
+def test_zero_residual_all_experts_equal_base():
+    # invariant (i): Eq. 6/7 with Delta W = 0: every expert of a cluster is the base
+    cfg = ci.small_config(T=40, d=16, d_ff=32, G=2, K=4, r=4, k=2, q=8, seed=11)
+    w = ci.generate(cfg)
+    for n in ("v1", "v2"):
+        w[n + "_s"] = np.zeros_like(w[n + "_s"])
+    out = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    cid = out["cluster_id"]
+    rng = np.random.default_rng(0)
+    other = (cid[:, None] * cfg.K + rng.integers(0, cfg.K, size=(cfg.T, cfg.k))).astype(np.int32)
+    y_other = orc.ffn_naive(w, w["x"], other, out["gate"], cfg.K, cfg.q)
+    assert np.allclose(out["y"], y_other, rtol=1e-12, atol=1e-14)
+    X = w["x"].astype(np.float64)
+    for t in range(cfg.T):
+        c = cid[t]
+        ref = w["w2_base"][c].astype(np.float64) @ orc.gelu(w["w1_base"][c].astype(np.float64) @ X[t])
+        assert np.allclose(out["y"][t], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_base_is_mean_of_materialised_experts():
+    # Eq. 6: if the residuals of a cluster sum to zero, the mean of its experts is the base
+    cfg = ci.small_config(T=4, d=16, d_ff=16, G=1, K=2, r=2, k=1, q=8, seed=5)
+    w = ci.generate(cfg)
+    for n in ("v1", "v2"):                           # expert 1 = mirror image of expert 0
+        w[n + "_q"][1] = w[n + "_q"][0]
+        w[n + "_s"][1] = w[n + "_s"][0]
+    for n in ("u1", "u2"):
+        codes = orc.unpack_int4(w[n + "_q"][0]).astype(np.int8)
+        w[n + "_q"][1] = ci.pack_int4(-codes)
+        w[n + "_s"][1] = w[n + "_s"][0]
+    W1a, W2a = orc.expert_weights(w, 0, 2, cfg.q)
+    W1b, W2b = orc.expert_weights(w, 1, 2, cfg.q)
+    assert np.allclose((W1a + W1b) / 2, w["w1_base"][0].astype(np.float64), atol=1e-15)
+    assert np.allclose((W2a + W2b) / 2, w["w2_base"][0].astype(np.float64), atol=1e-15)
+    assert np.abs(W1a - W1b).max() > 0
+
+
+@pytest.mark.parametrize("seed,k", [(21, 1), (22, 2), (23, 3)])
+def test_rewrite_equals_naive(seed, k):
+    # invariant (ii): base product shared + linearity of the second base matrix
+    cfg = ci.small_config(T=16, d=32, d_ff=48, G=3, K=4, r=4, k=k, q=8, factor_std=0.2, seed=seed)
+    w = ci.generate(cfg)
+    out = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    rw = orc.ffn_rewrite(w, w["x"], out["perm"], out["offsets"], out["expert_idx"], out["gate"], cfg.K, cfg.q)
+    scale = np.abs(out["y"]).max()
+    assert np.abs(rw["y"] - out["y"]).max() <= 1e-12 * scale
+    assert np.array_equal(rw["y_sorted"], rw["y"][out["perm"]])
+    # the residual terms matter at this factor size (a dropped term would show)
+    assert np.abs(rw["y_base_sorted"] - rw["y_sorted"]).max() > 1e-3 * scale
+
+
+def test_expert_weights_orientation():
+    # W1_e[o][i] = W1_base[o][i] + sum_rho U1[rho][o] V1[rho][i], checked on single entries
+    cfg = ci.small_config(T=2, d=8, d_ff=16, G=1, K=2, r=2, k=1, q=8, factor_std=0.5, seed=9)
+    w = ci.generate(cfg)
+    f = {n: orc.dequant_int4(w[n + "_q"], w[n + "_s"], cfg.q) for n in ("v1", "u1", "v2", "u2")}
+    W1, W2 = orc.expert_weights(w, 1, 2, cfg.q)
+    assert W1.shape == (16, 8) and W2.shape == (8, 16)
+    for (o, i) in ((0, 0), (15, 7), (3, 5)):
+        ref = float(w["w1_base"][0, o, i]) + sum(f["u1"][1, rho, o] * f["v1"][1, rho, i] for rho in range(2))
+        assert abs(W1[o, i] - ref) < 1e-15
+    for (o, i) in ((0, 0), (7, 15), (5, 3)):
+        ref = float(w["w2_base"][0, o, i]) + sum(f["u2"][1, rho, o] * f["v2"][1, rho, i] for rho in range(2))
+        assert abs(W2[o, i] - ref) < 1e-15
+
+
+# ------------------------------------------------------------------ closed forms the paper states
+def test_paper_closed_forms():
+    g = _golden()
+    assert orc.compression_ratio(4096, 4096, 8, 16) == pytest.approx(g["cr_square_d4096_K8_r16"], rel=1e-14)
+    assert 8 / (1 + 2 * 8 * 16 / 4096) == pytest.approx(g["cr_square_d4096_K8_r16"], rel=1e-14)
+    assert orc.storage_elements_per_group(4096, 4096, 8, 16) == int(g["storage_elements_d4096_K8_r16"])
+    E, G, K, d = 128, 16, 8, 768
+    assert (2 * d * E) / orc.routing_flops_per_token(d, G, K) == pytest.approx(g["routing_reduction_E128_G16_K8"], rel=1e-14)
+
+
+def test_generated_buffers_match_storage_closed_form():
+    cfg = ci.small_config(T=8, d=64, d_ff=128, G=2, K=4, r=4, k=2, q=32)
+    w = ci.generate(cfg)
+    per_group_w1 = w["w1_base"][0].size + (w["u1_q"][:cfg.K].size + w["v1_q"][:cfg.K].size) * 2
+    assert per_group_w1 == orc.storage_elements_per_group(cfg.d, cfg.d_ff, cfg.K, cfg.r)
+    per_group_w2 = w["w2_base"][0].size + (w["u2_q"][:cfg.K].size + w["v2_q"][:cfg.K].size) * 2
+    assert per_group_w2 == orc.storage_elements_per_group(cfg.d_ff, cfg.d, cfg.K, cfg.r)
+    fl = ci.flops_per_token(cfg)
+    assert fl["router"] == orc.routing_flops_per_token(cfg.d, cfg.G, cfg.K)
+
+
+def test_zipf_config_loads():
+    cfg = ci.scaled(ci.config(2), T=4096)
+    w = ci.generate(cfg, with_weights=False)
+    cid, *_ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
+    load = np.bincount(cid, minlength=cfg.G) / cfg.T
+    target = 1 / np.arange(1, cfg.G + 1)
+    target /= target.sum()
+    assert np.abs(load - target).max() < 0.01
