@@ -1,0 +1,153 @@
+/*
+ * cmoe.h -- C ABI of the clustered, compressed Mixture-of-Experts FFN layer (forward)
+ * for AMD MI355X (gfx950).
+ *
+ * The layer (notation of the paper, arXiv 2510.02345):
+ *   - E = G*K experts are organised in G clusters of uniform size K (Sec. 3.1).
+ *   - Every expert weight matrix is a per-cluster shared base plus a rank-r residual,
+ *     W_e = W_base(c) + U_e V_e (Sec. 3.2, Eq. 7).  Bases are FP16, the factors are
+ *     INT4 codes with one FP16 scale per group of q_group consecutive codes (Sec. 3.4).
+ *   - A token x in R^d is routed in two stages (Sec. 3.3): cluster logits z_g = u_g.x,
+ *     softmax (Eq. 9), the most probable cluster c wins; in-cluster logits l_i = v_i.x,
+ *     softmax over the cluster (Eq. 10), the top_k most probable experts are selected
+ *     and their probabilities renormalised to gates that sum to one.
+ *   - y = sum_j gate_j * W2_{e_j} GELU(W1_{e_j} x), evaluated with the base products
+ *     shared (Sec. 3.2, the sentence after Eq. 7): W1_base(c) x is computed once per
+ *     token, and by linearity W2_base(c) (sum_j gate_j a_j) once per token.
+ *
+ * Conventions
+ *   - Every pointer named in cmoe_weights and every tensor argument is a DEVICE
+ *     pointer owned by the caller, 16-byte aligned, valid until the stream has
+ *     finished the call.  cmoe_config / cmoe_weights structs themselves are HOST memory
+ *     and are read before the call returns.
+ *   - Calls only enqueue work on the given hipStream_t (passed as void*; NULL = the
+ *     default stream); they never synchronise, never read device memory from the host
+ *     and never allocate or free device memory.  Outputs are valid once the stream
+ *     has been synchronised.
+ *   - All matrices are row-major; "cmoe_f16" is the bit pattern of an IEEE binary16.
+ *   - Every function returns CMOE_OK (0) or a negative error code; argument checks are
+ *     done before any HIP call, so a rejected call has no side effect.  T = 0 is a
+ *     valid no-op.  Weights of a cluster that receives no token are never read.
+ *   - Indices are int32.  expert_idx holds global expert slots c*K + j.
+ *   - Tie-break everywhere: the lowest index wins; the top_k experts are listed by
+ *     descending logit.
+ */
+#ifndef CMOE_H
+#define CMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t cmoe_f16;
+
+enum {
+  CMOE_OK = 0,
+  CMOE_ERR_INVALID_ARG = -1, /* NULL / misaligned pointer, negative size, bad handle          */
+  CMOE_ERR_UNSUPPORTED = -2, /* a shape outside the supported set (see cmoe_create)           */
+  CMOE_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned or smaller than cmoe_workspace_bytes */
+  CMOE_ERR_HIP = -4          /* a HIP call failed; see cmoe_last_hip_error                    */
+};
+
+/* Hyper-parameters of one layer (Sec. 3.1-3.4). */
+typedef struct {
+  int32_t d;          /* model width                                                */
+  int32_t d_ff;       /* hidden width of the expert FFN                             */
+  int32_t G;          /* number of clusters                                         */
+  int32_t K;          /* experts per cluster (uniform, Sec. 3.1)                    */
+  int32_t r;          /* rank of the residual factors (Sec. 3.2): 4, 8, 16 or 32    */
+  int32_t top_k;      /* experts kept inside the selected cluster (Sec. 3.3)        */
+  int32_t q_group;    /* INT4 scale-group length along the long dimension (Sec. 3.4) */
+  int32_t activation; /* 0 = GELU, erf form                                         */
+} cmoe_config;
+
+/* Stored parameters.  Expert slot e = c*K + j belongs to cluster c (cluster-major).
+ * Factor tensors are rank-major: row rho of expert e holds L values along the long
+ * dimension (L = d for v1 and u2, d_ff for u1 and v2), element n in byte n/2 with even
+ * n in the low nibble, codes two's-complement in [-8, 7], value = scale[n/q_group]*code.
+ *   W1_e[o][i] = w1_base[c][o][i] + sum_rho u1[e][rho][o] * v1[e][rho][i]   (d_ff x d)
+ *   W2_e[o][i] = w2_base[c][o][i] + sum_rho u2[e][rho][o] * v2[e][rho][i]   (d x d_ff)
+ */
+typedef struct {
+  const cmoe_f16 *router_cluster; /* [G][d]       group prototypes u_g (Sec. 3.3)          */
+  const cmoe_f16 *router_expert;  /* [G*K][d]     expert routing vectors v_i               */
+  const float *cluster_bias;      /* [G] or NULL  added to z_g; NULL = the paper's router  */
+  const cmoe_f16 *w1_base;        /* [G][d_ff][d]                                          */
+  const cmoe_f16 *w2_base;        /* [G][d][d_ff]                                          */
+  const uint8_t *v1_q, *u1_q, *v2_q, *u2_q; /* [G*K][r][L/2]                                */
+  const cmoe_f16 *v1_s, *u1_s, *v2_s, *u2_s; /* [G*K][r][L/q_group]                         */
+} cmoe_weights;
+
+typedef struct cmoe_handle cmoe_handle;
+
+/* Validates the configuration and creates a handle (host state only).
+ * Supported: d and d_ff multiples of 64 with d <= 8192; 1 <= G <= 64; 1 <= K <= 32;
+ * r in {4, 8, 16, 32}; K*r <= 512; 1 <= top_k <= min(K, 8); q_group a multiple of 8 dividing d and
+ * d_ff; activation = 0.  Anything else: CMOE_ERR_UNSUPPORTED. */
+int cmoe_create(const cmoe_config *cfg, cmoe_handle **out);
+int cmoe_destroy(cmoe_handle *h);
+
+/* Bytes of device workspace that cmoe_permute / cmoe_ffn_forward / cmoe_combine /
+ * cmoe_forward need for up to T_max tokens (one buffer serves all of them; contents
+ * need not be preserved between calls).  Returns 0 for a NULL handle or T_max < 0. */
+size_t cmoe_workspace_bytes(const cmoe_handle *h, int32_t T_max);
+
+/* Sec. 3.3, both stages.  x [T][d] f16 ->
+ *   cluster_id [T]        argmax_g (u_g.x + bias_g)
+ *   expert_idx [T][top_k] global slots of the top_k largest v_i.x inside that cluster
+ *   gate       [T][top_k] f32, softmax over the selected logits (sums to one) */
+int cmoe_route(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, int32_t T,
+               int32_t *cluster_id, int32_t *expert_idx, float *gate, void *stream);
+
+/* Group-level dispatch on one device (Sec. 3.3): stable counting sort of tokens by
+ * cluster.  offsets [G+1] exclusive prefix sum of cluster loads; perm [T] token of
+ * sorted row p; inv_perm [T] sorted row of token t. */
+int cmoe_permute(cmoe_handle *h, const int32_t *cluster_id, int32_t T, int32_t *perm,
+                 int32_t *inv_perm, int32_t *offsets, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+/* Expert computation with base reuse (Sec. 3.2), in cluster-sorted row order p
+ * (token t = perm[p], cluster c, experts e_j, gates g_j):
+ *   Hb = W1_base(c) x_t;  a_j = GELU(Hb + U1_{e_j}(V1_{e_j} x_t));  A = sum_j g_j a_j
+ *   y_base_sorted[p] = W2_base(c) A            [T][d] f16
+ *   s_down[t][j]     = V2_{e_j} a_j            [T][top_k][r] f32, token order */
+int cmoe_ffn_forward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, int32_t T,
+                     const int32_t *perm, const int32_t *offsets, const int32_t *expert_idx,
+                     const float *gate, cmoe_f16 *y_base_sorted, float *s_down, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* Residual of the second matrix, gated combine and return to token order:
+ *   y[t] = y_base_sorted[inv_perm[t]] + sum_j g_j U2_{e_j} s_down[t][j]     [T][d] f16 */
+int cmoe_combine(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *y_base_sorted,
+                 const float *s_down, const int32_t *perm, const int32_t *inv_perm,
+                 const int32_t *offsets, const int32_t *expert_idx, const float *gate, int32_t T,
+                 cmoe_f16 *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* The whole layer: route -> permute -> ffn_forward -> combine on one stream.
+ * cluster_id, expert_idx, gate, perm, inv_perm, offsets are outputs as above (all
+ * required, caller-allocated). */
+int cmoe_forward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, int32_t T, cmoe_f16 *y,
+                 int32_t *cluster_id, int32_t *expert_idx, float *gate, int32_t *perm,
+                 int32_t *inv_perm, int32_t *offsets, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+/* hipError_t (as int) of the last failed HIP call made through this handle, 0 if none. */
+int cmoe_last_hip_error(const cmoe_handle *h);
+const char *cmoe_status_string(int status);
+
+/* Name and average duration (ms) bookkeeping for benchmarking: when enabled, every kernel
+ * launched through the handle is bracketed by HIP events on its stream.
+ * cmoe_timing_read synchronises those events and writes, for each of n_max slots, the
+ * accumulated milliseconds and launch counts; returns the number of slots used and resets
+ * the accumulators.  Slot names: cmoe_timing_name(i).  Not for production use. */
+int cmoe_timing_enable(cmoe_handle *h, int on);
+int cmoe_timing_read(cmoe_handle *h, double *ms_sum, int32_t *count, int32_t n_max);
+const char *cmoe_timing_name(int32_t slot);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CMOE_H */

@@ -1,0 +1,6 @@
+"""Clustered, compressed MoE FFN layer forward for MI355X: thin binding over libcmoe.so.
+
+All compute runs in the HIP library (include/cmoe.h); this package only marshals
+arguments.  PyTorch supplies device memory and streams.
+"""
+from .binding import (CmoeError, Layer, lib, lib_path, status_string)  # noqa: F401

@@ -1,0 +1,203 @@
+"""ctypes binding of libcmoe.so.  Same names and argument order as include/cmoe.h.
+
+Argument marshalling only: tensors are passed as raw device pointers
+(`tensor.data_ptr()`), the stream as the current torch stream's handle.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(PKG, "libcmoe.so")
+_lib = None
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
+           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_last_hip_error", "cmoe_status_string",
+           "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
+
+
+class CmoeError(RuntimeError):
+    def __init__(self, status: int, where: str, hip: int = 0):
+        self.status, self.hip = status, hip
+        super().__init__(f"{where}: {status_string(status)} (status {status}, hipError {hip})")
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("d", "d_ff", "G", "K", "r", "top_k", "q_group", "activation")]
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("router_cluster", "router_expert", "cluster_bias", "w1_base", "w2_base",
+                                          "v1_q", "u1_q", "v2_q", "u2_q", "v1_s", "u1_s", "v2_s", "u2_s")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Loads libcmoe.so (built in-tree by paper_2510_02345_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} is not built: run `python -m paper_2510_02345_amd.build`")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    L.cmoe_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    L.cmoe_destroy.argtypes = [vp]
+    L.cmoe_workspace_bytes.argtypes = [vp, i32]
+    L.cmoe_workspace_bytes.restype = sz
+    L.cmoe_route.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp]
+    L.cmoe_permute.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.cmoe_ffn_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_combine.argtypes = [vp, C.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.cmoe_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_last_hip_error.argtypes = [vp]
+    L.cmoe_status_string.argtypes = [C.c_int]
+    L.cmoe_status_string.restype = C.c_char_p
+    L.cmoe_timing_enable.argtypes = [vp, C.c_int]
+    L.cmoe_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32), i32]
+    L.cmoe_timing_name.argtypes = [i32]
+    L.cmoe_timing_name.restype = C.c_char_p
+    for name in EXPORTS:
+        if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().cmoe_status_string(status).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class Layer:
+    """One layer: a cmoe handle, its device weights and a workspace for up to T_max tokens."""
+
+    WEIGHT_NAMES = ("router_cluster", "router_expert", "cluster_bias", "w1_base", "w2_base",
+                    "v1_q", "u1_q", "v2_q", "u2_q", "v1_s", "u1_s", "v2_s", "u2_s")
+
+    def __init__(self, d, d_ff, G, K, r, top_k, q_group, weights: Dict[str, object], T_max: int, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = Config(d, d_ff, G, K, r, top_k, q_group, 0)
+        self.device = torch.device(device)
+        self._h = C.c_void_p()
+        rc = lib().cmoe_create(C.byref(self.cfg), C.byref(self._h))
+        if rc != OK:
+            raise CmoeError(rc, "cmoe_create")
+        self.w_t = {}
+        for n in self.WEIGHT_NAMES:
+            v = weights.get(n)
+            if v is None:
+                self.w_t[n] = None
+            elif isinstance(v, torch.Tensor):
+                self.w_t[n] = v.to(self.device).contiguous()
+            else:
+                self.w_t[n] = torch.from_numpy(v).to(self.device).contiguous()
+        self.w = Weights(*[_ptr(self.w_t[n]) for n in self.WEIGHT_NAMES])
+        self.T_max = T_max
+        self.ws_bytes = lib().cmoe_workspace_bytes(self._h, T_max)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
+        assert self.ws.data_ptr() % 256 == 0
+
+    def close(self):
+        if self._h:
+            lib().cmoe_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- helpers ---------------------------------------------------------
+    def _stream(self):
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def _check(self, rc, where):
+        if rc != OK:
+            raise CmoeError(rc, where, lib().cmoe_last_hip_error(self._h))
+
+    def _empty(self, shape, dtype):
+        return self.torch.empty(shape, dtype=dtype, device=self.device)
+
+    # -- the C ABI, one method per entry point ------------------------------
+    def route(self, x):
+        t = self.torch
+        T, k = x.shape[0], self.cfg.top_k
+        cid = self._empty((T,), t.int32)
+        eidx = self._empty((T, k), t.int32)
+        gate = self._empty((T, k), t.float32)
+        self._check(lib().cmoe_route(self._h, C.byref(self.w), _ptr(x), T, _ptr(cid), _ptr(eidx), _ptr(gate),
+                                     self._stream()), "cmoe_route")
+        return cid, eidx, gate
+
+    def permute(self, cluster_id):
+        t = self.torch
+        T = cluster_id.shape[0]
+        perm = self._empty((T,), t.int32)
+        inv = self._empty((T,), t.int32)
+        offsets = self._empty((self.cfg.G + 1,), t.int32)
+        self._check(lib().cmoe_permute(self._h, _ptr(cluster_id), T, _ptr(perm), _ptr(inv), _ptr(offsets),
+                                       _ptr(self.ws), self.ws.numel(), self._stream()), "cmoe_permute")
+        return perm, inv, offsets
+
+    def ffn_forward(self, x, perm, offsets, expert_idx, gate):
+        t = self.torch
+        T = x.shape[0]
+        yb = self._empty((T, self.cfg.d), t.float16)
+        s = self._empty((T, self.cfg.top_k, self.cfg.r), t.float32)
+        self._check(lib().cmoe_ffn_forward(self._h, C.byref(self.w), _ptr(x), T, _ptr(perm), _ptr(offsets),
+                                           _ptr(expert_idx), _ptr(gate), _ptr(yb), _ptr(s), _ptr(self.ws),
+                                           self.ws.numel(), self._stream()), "cmoe_ffn_forward")
+        return yb, s
+
+    def combine(self, yb, s, perm, inv_perm, offsets, expert_idx, gate):
+        t = self.torch
+        T = yb.shape[0]
+        y = self._empty((T, self.cfg.d), t.float16)
+        self._check(lib().cmoe_combine(self._h, C.byref(self.w), _ptr(yb), _ptr(s), _ptr(perm), _ptr(inv_perm),
+                                       _ptr(offsets), _ptr(expert_idx), _ptr(gate), T, _ptr(y), _ptr(self.ws),
+                                       self.ws.numel(), self._stream()), "cmoe_combine")
+        return y
+
+    def forward_buffers(self, T):
+        t = self.torch
+        k = self.cfg.top_k
+        return dict(y=self._empty((T, self.cfg.d), t.float16), cluster_id=self._empty((T,), t.int32),
+                    expert_idx=self._empty((T, k), t.int32), gate=self._empty((T, k), t.float32),
+                    perm=self._empty((T,), t.int32), inv_perm=self._empty((T,), t.int32),
+                    offsets=self._empty((self.cfg.G + 1,), t.int32))
+
+    def forward(self, x, out=None):
+        T = x.shape[0]
+        o = out if out is not None else self.forward_buffers(T)
+        self._check(lib().cmoe_forward(self._h, C.byref(self.w), _ptr(x), T, _ptr(o["y"]), _ptr(o["cluster_id"]),
+                                       _ptr(o["expert_idx"]), _ptr(o["gate"]), _ptr(o["perm"]), _ptr(o["inv_perm"]),
+                                       _ptr(o["offsets"]), _ptr(self.ws), self.ws.numel(), self._stream()),
+                    "cmoe_forward")
+        return o
+
+    # -- per-kernel timing (HIP events recorded by the library on the launch stream) ------
+    def timing_enable(self, on: bool):
+        self._check(lib().cmoe_timing_enable(self._h, int(on)), "cmoe_timing_enable")
+
+    def timing_read(self):
+        n = 16
+        ms = (C.c_double * n)()
+        cnt = (C.c_int32 * n)()
+        used = lib().cmoe_timing_read(self._h, ms, cnt, n)
+        if used < 0:
+            raise CmoeError(used, "cmoe_timing_read", lib().cmoe_last_hip_error(self._h))
+        return {lib().cmoe_timing_name(i).decode(): (ms[i], cnt[i]) for i in range(used)}

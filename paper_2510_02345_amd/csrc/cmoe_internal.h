@@ -1,0 +1,91 @@
+// Internal declarations shared by the HIP translation units of libcmoe.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cmoe.h"
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// Derived sizes of one layer.
+struct cmoe_dims {
+  int d, d_ff, G, K, r, k, q;
+  int KR;   // K * r: concatenated rank rows of one cluster
+  int KRp;  // KR rounded up to a multiple of 32 (one 32-row MFMA block)
+};
+
+enum cmoe_timing_slot {
+  TS_ROUTE = 0,
+  TS_PERMUTE,
+  TS_DEQUANT,
+  TS_T1,
+  TS_GEMM1,
+  TS_SREDUCE,
+  TS_GEMM2,
+  TS_COMBINE,
+  TS_COUNT
+};
+
+struct cmoe_timing {
+  bool on = false;
+  static const int MAX_EV = 4096;
+  hipEvent_t ev[MAX_EV][2];
+  int slot_of[MAX_EV];
+  int n_ev = 0;
+  int n_created = 0;
+};
+
+struct cmoe_handle {
+  uint32_t magic;
+  cmoe_dims dm;
+  int last_hip_error;
+  cmoe_timing tm;
+};
+
+// Workspace layout for T tokens (byte offsets, all 256-byte aligned).
+struct cmoe_ws_layout {
+  size_t blk_counts;  // int32 [n_blocks][G]   permute: per-block cluster histogram -> bases
+  size_t v1cat;       // f16 [G][KRp][d]       dequantised V1, rows kk = j*r + rho
+  size_t u1t;         // f16 [G][d_ff][KRp]    dequantised U1, transposed
+  size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2, columns permuted inside 16-groups
+  size_t u2t;         // f16 [G][d][KRp]       dequantised U2, transposed
+  size_t t1ext;       // f16 [T][k][KRp]       V1 x, one-hot expanded over the cluster's experts
+  size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows
+  size_t spart;       // f32 [n_tiles][T][k][r] partial V2 a per column tile of d_ff
+  size_t yb;          // f16 [T][d]            cmoe_forward only: y_base_sorted
+  size_t sdown;       // f32 [T][k][r]         cmoe_forward only: s_down
+  size_t total;
+};
+
+static const int PERMUTE_BLOCK = 1024;  // tokens per workgroup in the permutation kernels
+static const int G1_BN = 128;           // rows of d_ff per workgroup tile in the fused up-projection
+
+cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T);
+
+// Kernel launchers (each returns the hipError_t of its launch).
+hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
+                        int* expert_idx, float* gate, hipStream_t st);
+hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
+                          int* blk_counts, hipStream_t st);
+hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* v1cat,
+                              half_t* u1t, half_t* v2p, hipStream_t st);
+hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,
+                             hipStream_t st);
+hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
+                     const int* expert_idx, const half_t* v1cat, half_t* t1ext, hipStream_t st);
+hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+                        const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
+                        const half_t* v2p, const half_t* t1ext, half_t* a, float* spart, hipStream_t st);
+hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, float* s_down,
+                          hipStream_t st);
+hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
+                        half_t* y_base_sorted, hipStream_t st);
+hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* y_base_sorted, const float* s_down,
+                          const int* perm, const int* offsets, const int* expert_idx, const float* gate, int T,
+                          half_t* y, hipStream_t st);

@@ -1,0 +1,222 @@
+// Two-stage hierarchical router (Sec. 3.3, Eq. 9 and Eq. 10) and the stable
+// token-to-cluster permutation (the single-device part of group-level dispatch).
+#include "cmoe_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ __forceinline__ float dot8(half8 a, half8 b, float acc) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc = fmaf((float)a[i], (float)b[i], acc);
+  return acc;
+}
+
+constexpr int ROUTE_WAVES = 4;
+
+// One wavefront per token.  The token's row stays in registers for both stages: z_g over
+// all G prototypes, then l_j over the K routing vectors of the winning cluster only, so
+// the work per token is (G + K) dot products of length d (Sec. 3.3).
+template <int MAXC>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void route_kernel(
+    const half_t* __restrict__ x, const half_t* __restrict__ rc, const half_t* __restrict__ re,
+    const float* __restrict__ bias, int T, int d, int G, int K, int k, int* __restrict__ cluster_id,
+    int* __restrict__ expert_idx, float* __restrict__ gate) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * ROUTE_WAVES + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const int nchunk = d >> 3;
+  half8 xv[MAXC];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    int ch = lane + 64 * i;
+    xv[i] = (ch < nchunk) ? *(const half8*)(x + (size_t)t * d + ch * 8) : half8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  // stage 1: the softmax of Eq. 9 is monotone, so the most probable cluster is the
+  // largest logit; strict '>' keeps the lowest index on ties
+  float best = -INFINITY;
+  int c = 0;
+  for (int g = 0; g < G; ++g) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      int ch = lane + 64 * i;
+      if (ch < nchunk) acc = dot8(xv[i], *(const half8*)(rc + (size_t)g * d + ch * 8), acc);
+    }
+    acc = wave_sum(acc);
+    if (bias != nullptr) acc += bias[g];
+    if (acc > best) {
+      best = acc;
+      c = g;
+    }
+  }
+  // stage 2: logits of the K experts of cluster c; lane j keeps l_j
+  float mine = -INFINITY;
+  for (int j = 0; j < K; ++j) {
+    float acc = 0.f;
+    const half_t* v = re + (size_t)(c * K + j) * d;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      int ch = lane + 64 * i;
+      if (ch < nchunk) acc = dot8(xv[i], *(const half8*)(v + ch * 8), acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == j) mine = acc;
+  }
+  // top-k by k rounds of (largest value, lowest lane) selection over the wavefront
+  float sel_l[8];
+  int sel_j[8];
+  float lmax = 0.f;
+#pragma unroll
+  for (int a = 0; a < 8; ++a) {
+    sel_l[a] = 0.f;
+    sel_j[a] = 0;
+    if (a < k) {
+      float m = mine;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      unsigned long long who = __ballot(mine == m);
+      int j = __ffsll((long long)who) - 1;
+      sel_l[a] = m;
+      sel_j[a] = j;
+      if (a == 0) lmax = m;
+      if (lane == j) mine = -INFINITY;
+    }
+  }
+  if (lane == 0) {
+    cluster_id[t] = c;
+    float den = 0.f;
+    float ex[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+      ex[a] = (a < k) ? expf(sel_l[a] - lmax) : 0.f;
+      den += ex[a];
+    }
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+      if (a < k) {
+        expert_idx[(size_t)t * k + a] = c * K + sel_j[a];
+        gate[(size_t)t * k + a] = ex[a] / den;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- permutation
+// Pass 1: per-block histogram of cluster ids (LDS integer atomics: order-independent).
+__global__ __launch_bounds__(PERMUTE_BLOCK) void permute_hist_kernel(const int* __restrict__ cluster_id, int T, int G,
+                                                                     int* __restrict__ blk_counts) {
+  __shared__ int hist[64];
+  if (threadIdx.x < 64) hist[threadIdx.x] = 0;
+  __syncthreads();
+  int t = blockIdx.x * PERMUTE_BLOCK + threadIdx.x;
+  if (t < T) atomicAdd(&hist[min(max(cluster_id[t], 0), G - 1)], 1);
+  __syncthreads();
+  if (threadIdx.x < G) blk_counts[(size_t)blockIdx.x * G + threadIdx.x] = hist[threadIdx.x];
+}
+
+// Pass 2: one workgroup.  offsets = exclusive scan of the cluster totals; each block's
+// count is replaced by the first sorted row that block may write for that cluster.
+__global__ __launch_bounds__(64) void permute_scan_kernel(int n_blocks, int G, int* __restrict__ blk_counts,
+                                                          int* __restrict__ offsets) {
+  __shared__ int total[64];
+  int g = threadIdx.x;
+  if (g < G) {
+    int run = 0;
+    for (int b = 0; b < n_blocks; ++b) {
+      int v = blk_counts[(size_t)b * G + g];
+      blk_counts[(size_t)b * G + g] = run;
+      run += v;
+    }
+    total[g] = run;
+  }
+  __syncthreads();
+  if (g == 0) {
+    int run = 0;
+    for (int c = 0; c < G; ++c) {
+      offsets[c] = run;
+      int v = total[c];
+      total[c] = run;
+      run += v;
+    }
+    offsets[G] = run;
+  }
+  __syncthreads();
+  if (g < G) {
+    int base = total[g];
+    for (int b = 0; b < n_blocks; ++b) blk_counts[(size_t)b * G + g] += base;
+  }
+}
+
+// Pass 3: stable ranks.  Inside a block, a token's rank among equal clusters is the count
+// in earlier wavefronts plus the number of lower lanes with the same cluster (ballot).
+__global__ __launch_bounds__(PERMUTE_BLOCK) void permute_rank_kernel(const int* __restrict__ cluster_id, int T, int G,
+                                                                     const int* __restrict__ blk_base,
+                                                                     int* __restrict__ perm,
+                                                                     int* __restrict__ inv_perm) {
+  constexpr int NW = PERMUTE_BLOCK / 64;
+  __shared__ int wcount[NW][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x * PERMUTE_BLOCK + threadIdx.x;
+  const int c = (t < T) ? min(max(cluster_id[t], 0), G - 1) : -1;
+  int my_rank = 0;
+  for (int g = 0; g < G; ++g) {
+    unsigned long long m = __ballot(c == g);
+    if (lane == 0) wcount[wave][g] = __popcll(m);
+    if (c == g) my_rank = __popcll(m & ((1ull << lane) - 1ull));
+  }
+  __syncthreads();
+  if (t < T) {
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wcount[w][c];
+    int pos = blk_base[(size_t)blockIdx.x * G + c] + before + my_rank;
+    perm[pos] = t;
+    inv_perm[t] = pos;
+  }
+}
+
+__global__ void zero_offsets_kernel(int G, int* offsets) {
+  if ((int)threadIdx.x <= G) offsets[threadIdx.x] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
+                        int* expert_idx, float* gate, hipStream_t st) {
+  dim3 grid((T + ROUTE_WAVES - 1) / ROUTE_WAVES), block(ROUTE_WAVES * 64);
+  const half_t* rc = (const half_t*)w.router_cluster;
+  const half_t* re = (const half_t*)w.router_expert;
+  int chunks_per_lane = (dm.d / 8 + 63) / 64;
+  if (chunks_per_lane <= 2)
+    hipLaunchKernelGGL(route_kernel<2>, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                       cluster_id, expert_idx, gate);
+  else if (chunks_per_lane <= 4)
+    hipLaunchKernelGGL(route_kernel<4>, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                       cluster_id, expert_idx, gate);
+  else if (chunks_per_lane <= 8)
+    hipLaunchKernelGGL(route_kernel<8>, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                       cluster_id, expert_idx, gate);
+  else
+    hipLaunchKernelGGL(route_kernel<16>, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                       cluster_id, expert_idx, gate);
+  return hipGetLastError();
+}
+
+hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
+                          int* blk_counts, hipStream_t st) {
+  if (T == 0) {
+    hipLaunchKernelGGL(zero_offsets_kernel, dim3(1), dim3(128), 0, st, dm.G, offsets);
+    return hipGetLastError();
+  }
+  int n_blocks = (T + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
+  hipLaunchKernelGGL(permute_hist_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
+                     blk_counts);
+  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(64), 0, st, n_blocks, dm.G, blk_counts, offsets);
+  hipLaunchKernelGGL(permute_rank_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
+                     blk_counts, perm, inv_perm);
+  return hipGetLastError();
+}

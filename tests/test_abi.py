@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol that
+include/cmoe.h declares, and rejects bad arguments before any HIP call (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2510_02345_amd as cm
+from paper_2510_02345_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cmoe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = cm.lib()
+    names = _declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def _create(**kw):
+    base = dict(d=128, d_ff=512, G=2, K=4, r=4, top_k=1, q_group=32, activation=0)
+    base.update(kw)
+    cfg = B.Config(*[base[n] for n in ("d", "d_ff", "G", "K", "r", "top_k", "q_group", "activation")])
+    h = C.c_void_p()
+    rc = cm.lib().cmoe_create(C.byref(cfg), C.byref(h))
+    return rc, h
+
+
+def test_create_validates_configuration():
+    rc, h = _create()
+    assert rc == B.OK and h.value
+    assert cm.lib().cmoe_destroy(h) == B.OK
+    assert cm.lib().cmoe_destroy(None) == B.ERR_INVALID_ARG
+    for bad in (dict(d=100), dict(d_ff=500), dict(r=5), dict(top_k=5), dict(top_k=9, K=16), dict(q_group=12),
+                dict(q_group=48), dict(G=65), dict(K=33), dict(K=32, r=32), dict(activation=1), dict(d=16384)):
+        rc, h = _create(**bad)
+        assert rc == B.ERR_UNSUPPORTED, bad
+        assert not h.value
+    for bad in (dict(d=0), dict(G=-1), dict(top_k=0)):
+        rc, h = _create(**bad)
+        assert rc == B.ERR_INVALID_ARG, bad
+    assert cm.lib().cmoe_create(None, None) == B.ERR_INVALID_ARG
+
+
+def test_workspace_bytes_monotone_and_covers_intermediates():
+    rc, h = _create(d=768, d_ff=3072, G=2, K=4, r=8, top_k=2, q_group=32)
+    L = cm.lib()
+    assert L.cmoe_workspace_bytes(None, 10) == 0
+    assert L.cmoe_workspace_bytes(h, -1) == 0
+    w0, w1, w2 = (L.cmoe_workspace_bytes(h, t) for t in (0, 1000, 4096))
+    assert 0 < w0 < w1 < w2
+    # at least the f16 hidden activations A [T][d_ff] and y_base_sorted [T][d]
+    assert w2 - w0 >= 4096 * (3072 + 768) * 2
+    L.cmoe_destroy(h)
+
+
+def test_calls_reject_bad_arguments_without_touching_the_gpu():
+    rc, h = _create()
+    L = cm.lib()
+    w = B.Weights()                                   # all NULL
+    assert L.cmoe_route(h, C.byref(w), None, 4, None, None, None, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route(h, None, None, 0, None, None, None, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route(None, C.byref(w), None, 0, None, None, None, None) == B.ERR_INVALID_ARG
+    fake = 0x1000                                     # aligned, never dereferenced on the host
+    w2 = B.Weights(*([fake] * 13))
+    assert L.cmoe_route(h, C.byref(w2), fake, -1, fake, fake, fake, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route(h, C.byref(w2), fake + 2, 4, fake, fake, fake, None) == B.ERR_INVALID_ARG   # misaligned x
+    assert L.cmoe_route(h, C.byref(w2), fake, 0, fake, fake, fake, None) == B.OK                    # T = 0 no-op
+    # workspace checks come before any launch
+    assert L.cmoe_permute(h, fake, 8, fake, fake, fake, None, 0, None) == B.ERR_WORKSPACE
+    assert L.cmoe_permute(h, fake, 8, fake, fake, fake, fake + 16, 1 << 30, None) == B.ERR_WORKSPACE  # misaligned
+    assert L.cmoe_permute(h, fake, 8, fake, fake, fake, fake, 16, None) == B.ERR_WORKSPACE            # too small
+    assert L.cmoe_ffn_forward(h, C.byref(w2), fake, 8, fake, fake, fake, fake, fake, fake, fake, 16, None) == B.ERR_WORKSPACE
+    assert L.cmoe_ffn_forward(h, C.byref(w), fake, 8, fake, fake, fake, fake, fake, fake, fake, 1 << 30, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_combine(h, C.byref(w2), fake, fake, fake, fake, fake, fake, fake, 8, None, fake, 1 << 30, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_forward(h, C.byref(w2), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == B.ERR_WORKSPACE
+    assert L.cmoe_last_hip_error(h) == 0
+    assert cm.status_string(B.ERR_WORKSPACE).startswith("workspace")
+    assert cm.status_string(B.OK) == "ok"
+    L.cmoe_destroy(h)
+
+
+def test_timing_names():
+    L = cm.lib()
+    names = [L.cmoe_timing_name(i).decode() for i in range(8)]
+    assert names[0] == "route" and "gemm1_fused" in names and L.cmoe_timing_name(99) == b""

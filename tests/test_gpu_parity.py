@@ -1,0 +1,202 @@
+"""GPU parity: the HIP library (through the C ABI) against the FP64 oracle.
+
+Bars: routing indices, permutation and offsets bit-exact; gates to 1e-5; layer output
+max|y - y_ref| <= 1e-2 * RMS(y_ref) and sum|y - y_ref| / sum|y_ref| <= 2e-3.
+Intermediates (y_base_sorted, s_down) use the same max/RMS bar.
+"""
+import numpy as np
+import pytest
+
+import cmoe_inputs as ci
+from oracle import cmoe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+MAX_OVER_RMS = 1e-2
+MEAN_REL = 2e-3
+
+
+def _layer(cfg, w, T_max=None):
+    import paper_2510_02345_amd as cm
+    return cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, T_max if T_max is not None else cfg.T)
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _check_y(y, y_ref, what):
+    m = orc.error_metrics(y, y_ref)
+    print(f"{what}: max/rms={m['max_over_rms']:.3e} mean_rel={m['mean_rel']:.3e}", flush=True)
+    assert np.all(np.isfinite(np.asarray(y, dtype=np.float64))), what
+    assert m["max_over_rms"] <= MAX_OVER_RMS, (what, m)
+    assert m["mean_rel"] <= MEAN_REL, (what, m)
+    return m
+
+
+def _stepwise(cfg, w=None):
+    """Each entry point on its own against the oracle, then cmoe_forward."""
+    print(f"case {cfg}", flush=True)
+    w = w if w is not None else ci.generate(cfg)
+    ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    rw = orc.ffn_rewrite(w, w["x"], ref["perm"], ref["offsets"], ref["expert_idx"], ref["gate"], cfg.K, cfg.q)
+    layer = _layer(cfg, w)
+    x = _dev(w["x"])
+
+    cid, eidx, gate = layer.route(x)
+    _sync()
+    assert np.array_equal(cid.cpu().numpy(), ref["cluster_id"])
+    assert np.array_equal(eidx.cpu().numpy(), ref["expert_idx"])
+    assert np.allclose(gate.cpu().numpy(), ref["gate"], rtol=1e-5, atol=1e-6)
+
+    # each later step is fed the oracle's inputs, so an upstream error cannot hide
+    perm, inv, offsets = layer.permute(_dev(ref["cluster_id"]))
+    _sync()
+    assert np.array_equal(offsets.cpu().numpy(), ref["offsets"])
+    assert np.array_equal(perm.cpu().numpy(), ref["perm"])
+    assert np.array_equal(inv.cpu().numpy(), ref["inv_perm"])
+
+    g32 = _dev(ref["gate"].astype(np.float32))
+    yb, s = layer.ffn_forward(x, _dev(ref["perm"]), _dev(ref["offsets"]), _dev(ref["expert_idx"]), g32)
+    _sync()
+    if cfg.T:
+        _check_y(yb.cpu().numpy(), rw["y_base_sorted"], "y_base_sorted")
+        _check_y(s.cpu().numpy(), rw["s"], "s_down")
+
+    yb_ref = _dev(rw["y_base_sorted"].astype(np.float16))
+    s_ref = _dev(rw["s"].astype(np.float32))
+    y = layer.combine(yb_ref, s_ref, _dev(ref["perm"]), _dev(ref["inv_perm"]), _dev(ref["offsets"]),
+                      _dev(ref["expert_idx"]), g32)
+    _sync()
+    if cfg.T:
+        _check_y(y.cpu().numpy(), ref["y"], "combine")
+
+    out = layer.forward(x)
+    _sync()
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["cluster_id"])
+    assert np.array_equal(out["expert_idx"].cpu().numpy(), ref["expert_idx"])
+    assert np.array_equal(out["perm"].cpu().numpy(), ref["perm"])
+    assert np.array_equal(out["inv_perm"].cpu().numpy(), ref["inv_perm"])
+    assert np.array_equal(out["offsets"].cpu().numpy(), ref["offsets"])
+    m = None
+    if cfg.T:
+        m = _check_y(out["y"].cpu().numpy(), ref["y"], "forward")
+    layer.close()
+    return m, ref
+
+
+SMALL = [
+    # several row tiles and a ragged tail in every cluster; K*r = 32
+    ci.small_config("ragged", T=777, d=128, d_ff=384, G=3, K=4, r=8, k=2, q=32, seed=41),
+    # K*r = 16 < 32 (padded rank panel), k = 1
+    ci.small_config("padded", T=300, d=64, d_ff=192, G=2, K=4, r=4, k=1, q=8, seed=42),
+    # one cluster, r = 32, all K selected
+    ci.small_config("flat", T=130, d=192, d_ff=256, G=1, K=3, r=32, k=3, q=64, seed=43),
+    # many clusters, few tokens: most row tiles nearly empty, some clusters empty
+    ci.small_config("sparse", T=19, d=64, d_ff=128, G=16, K=2, r=16, k=2, q=16, seed=44),
+    # k = 4 of K = 8, r = 4: two experts share an 8-row group of the rank panel
+    ci.small_config("k4", T=257, d=128, d_ff=256, G=2, K=8, r=4, k=4, q=32, seed=45),
+    ci.small_config("one", T=1, d=64, d_ff=64, G=2, K=2, r=8, k=2, q=8, seed=46),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_small_shapes_every_entry_point(cfg):
+    _stepwise(cfg)
+
+
+def test_empty_input_is_a_noop():
+    cfg = ci.small_config("empty", T=0, d=64, d_ff=128, G=2, K=2, r=8, k=2, q=8, seed=47)
+    _stepwise(cfg)
+
+
+def test_empty_cluster_weights_never_read():
+    # all tokens forced into cluster 1 by the bias; the weights of cluster 0 are NaN / garbage
+    cfg = ci.small_config("onecluster", T=200, d=64, d_ff=128, G=2, K=4, r=8, k=2, q=8, seed=48)
+    w = ci.generate(cfg)
+    w["cluster_bias"] = np.array([-100.0, 100.0], dtype=np.float32)
+    for n in ("w1_base", "w2_base"):
+        w[n][0] = np.float16(np.nan)
+    for n in ("v1", "u1", "v2", "u2"):
+        w[n + "_s"][:cfg.K] = np.float16(np.nan)
+    _stepwise(cfg, w)
+
+
+def test_residual_path_is_live():
+    # factors ten times larger: the residual terms are far above the tolerance, so a
+    # path that dropped or mis-indexed them would fail here
+    cfg = ci.small_config("bigres", T=500, d=128, d_ff=512, G=2, K=4, r=8, k=2, q=32, factor_std=0.2, seed=49)
+    w = ci.generate(cfg)
+    m, ref = _stepwise(cfg, w)
+    w0 = dict(w)
+    for n in ("u1", "u2"):
+        w0[n + "_s"] = np.zeros_like(w[n + "_s"])
+    y0 = orc.ffn_naive(w0, w["x"], ref["expert_idx"], ref["gate"], cfg.K, cfg.q)
+    assert orc.error_metrics(y0, ref["y"])["max_over_rms"] > 20 * MAX_OVER_RMS
+
+
+def test_forward_is_deterministic():
+    import torch
+    cfg = ci.small_config("det", T=1500, d=128, d_ff=512, G=3, K=4, r=16, k=2, q=32, seed=50)
+    w = ci.generate(cfg)
+    layer = _layer(cfg, w)
+    x = _dev(w["x"])
+    a = layer.forward(x)
+    _sync()
+    ya = a["y"].clone()
+    layer.ws.fill_(0x7f)
+    b = layer.forward(x)
+    _sync()
+    assert torch.equal(ya, b["y"])
+    layer.close()
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_config_full_output(idx):
+    _stepwise(ci.config(idx))
+
+
+def _sampled(cfg, n_sample, seed=0):
+    """Full-size run through cmoe_forward; indices checked on every token, the output on
+    a random sample of tokens that the dense per-expert oracle computes one by one."""
+    print(f"case {cfg}", flush=True)
+    w = ci.generate(cfg)
+    cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
+    offsets, perm, inv = orc.permute(cid, cfg.G)
+    layer = _layer(cfg, w)
+    out = layer.forward(_dev(w["x"]))
+    _sync()
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), cid)
+    assert np.array_equal(out["expert_idx"].cpu().numpy(), eidx)
+    assert np.allclose(out["gate"].cpu().numpy(), gate, rtol=1e-5, atol=1e-6)
+    assert np.array_equal(out["offsets"].cpu().numpy(), offsets)
+    assert np.array_equal(out["perm"].cpu().numpy(), perm)
+    assert np.array_equal(out["inv_perm"].cpu().numpy(), inv)
+    y = out["y"].cpu().numpy()
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    rng = np.random.default_rng(seed)
+    rows = np.sort(rng.choice(cfg.T, size=min(n_sample, cfg.T), replace=False))
+    # always include the first and last sorted row of every cluster (tile edges)
+    edges = [perm[o] for o in offsets[:-1] if o < cfg.T] + [perm[o - 1] for o in offsets[1:] if o > 0]
+    rows = np.unique(np.concatenate([rows, np.array(edges, dtype=np.int64)]))
+    y_ref = orc.ffn_naive(w, w["x"][rows], eidx[rows], gate[rows], cfg.K, cfg.q)
+    _check_y(y[rows], y_ref, f"{cfg.name} sampled {len(rows)} tokens")
+    layer.close()
+
+
+def test_config2_zipf_loads():
+    _sampled(ci.config(2), 4096)
+
+
+def test_config3_large_T():
+    _sampled(ci.config(3), 1024)
+
+
+def test_config4_weight_bound():
+    _sampled(ci.config(4), 64)
