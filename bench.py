@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the clustered, compressed MoE FFN layer forward on one MI355X.
+
+A step is one pass of the whole hot path (route -> permute -> expert FFNs with shared
+bases and INT4 rank-r residuals -> combine) over one batch of synthetic tokens, through
+the C ABI (cmoe_forward).  Inputs and weights are resident in HBM before timing starts.
+
+Prints ONE JSON line: whole-layer tokens/s on the named workload, a roofline object for
+the dominant kernel (durations from HIP events recorded by the library on the launch
+stream, in a second pass over the same steps), the same for the weight-bound
+configuration, and the FP64 oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_F16_TFLOPS = 2500.0     # MI355X dense FP16 matrix peak
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E peak
+
+
+def kernel_work(cfg, kernel, clusters_hit, experts_hit):
+    """Algorithmic flops and bytes of ONE launch of a kernel of the path (per-token
+    figures of the method times the tokens a launch processes; intermediates that only
+    exist because of how the path is split into kernels are not credited)."""
+    T, d, f, k, r = cfg.T, cfg.d, cfg.d_ff, cfg.k, cfg.r
+    if kernel == "gemm1_fused":      # W1_base x, + U1 t1, GELU, gated sum, V2 a
+        flops = T * (2 * d * f + 4 * k * r * f)
+        byts = clusters_hit * f * d * 2 + experts_hit * (r * f + 4 * r * f // cfg.q) + T * d * 2
+    elif kernel == "gemm2":          # W2_base A
+        flops = T * 2 * d * f
+        byts = clusters_hit * f * d * 2 + T * d * 2
+    elif kernel == "t1":             # V1 x
+        flops = T * 2 * k * r * d
+        byts = experts_hit * (r * d // 2 + 2 * r * d // cfg.q) + T * d * 2
+    elif kernel == "combine":        # + U2 s, un-permute
+        flops = T * 2 * k * r * d
+        byts = experts_hit * (r * d // 2 + 2 * r * d // cfg.q) + 2 * T * d * 2
+    elif kernel == "route":
+        flops = T * 2 * d * (cfg.G + cfg.K)
+        byts = T * d * 2 + (cfg.G + cfg.E) * d * 2
+    else:
+        flops, byts = 0, 0
+    return flops, byts
+
+
+def run_config(cfg, steps, warmup, want_traffic=None):
+    import numpy as np
+    import torch
+
+    import cmoe_inputs as ci
+    import paper_2510_02345_amd as cm
+
+    w = ci.generate(cfg)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T, device="cuda:0")
+    x = torch.from_numpy(w["x"]).to("cuda:0")
+    out = layer.forward_buffers(cfg.T)
+    for _ in range(warmup):
+        layer.forward(x, out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        layer.forward(x, out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / steps * 1e3
+
+    # second pass over the same steps with per-kernel HIP events on the launch stream
+    layer.timing_enable(True)
+    for _ in range(steps):
+        layer.forward(x, out)
+    torch.cuda.synchronize()
+    tm = layer.timing_read()
+    layer.timing_enable(False)
+    per_kernel = {n: (ms / steps) for n, (ms, cnt) in tm.items() if cnt}
+
+    eidx = out["expert_idx"].cpu().numpy()
+    offs = out["offsets"].cpu().numpy()
+    clusters_hit = int((np.diff(offs) > 0).sum())
+    experts_hit = int(len(np.unique(eidx)))
+    layer.close()
+    return dict(ms_per_step=ms_per_step, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
+                experts_hit=experts_hit, inputs=w)
+
+
+def roofline(cfg, res, bound, traffic_table):
+    import cmoe_inputs as ci
+    pk = res["per_kernel_ms"]
+    dom = max(pk, key=lambda n: pk[n])
+    flops, byts = kernel_work(cfg, dom, res["clusters_hit"], res["experts_hit"])
+    sec = pk[dom] * 1e-3
+    traffic = traffic_table.get(f"{cfg.name}:{dom}")
+    if bound == "mfma":
+        ach, peak, unit = flops / sec / 1e12, PEAK_F16_TFLOPS, "TFLOP/s"
+    else:
+        ach, peak, unit = byts / sec / 1e9, PEAK_HBM_GBS, "GB/s"
+    whole_flops = ci.flops_per_token(cfg)["total"] * cfg.T
+    whole_bytes = ci.algorithmic_bytes(cfg, res["clusters_hit"], res["experts_hit"])["total"]
+    step_s = res["ms_per_step"] * 1e-3
+    return {"bound": bound, "kernel": dom, "achieved": round(ach, 2), "peak": peak, "unit": unit,
+            "frac": round(ach / peak, 4), "traffic": traffic, "kernel_ms": round(pk[dom], 4),
+            "per_kernel_ms": {n: round(v, 4) for n, v in pk.items()},
+            "whole_path_frac_mfma": round(whole_flops / step_s / 1e12 / PEAK_F16_TFLOPS, 4),
+            "whole_path_frac_hbm": round(whole_bytes / step_s / 1e9 / PEAK_HBM_GBS, 4)}
+
+
+def cpu_baseline(cfg, w, sample):
+    """The FP64 oracle (plain definition: per-expert dense FFNs) on the first `sample`
+    tokens of the workload, on the host cores."""
+    from oracle import cmoe_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ws = dict(w)
+    x = w["x"][:sample]
+    t0 = time.perf_counter()
+    orc.forward_naive(ws, x, cfg.K, cfg.k, cfg.q)
+    dt = time.perf_counter() - t0
+    return {"value": round(sample / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {sample} of {cfg.T} tokens of {cfg.name}, forward_naive (FP64, numpy/OpenBLAS), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="index into the workload list (default: largest-T)")
+    ap.add_argument("--no-weight-bound", action="store_true", help="skip the weight-bound (C4) leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import cmoe_inputs as ci
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    traffic_table = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic_table = json.load(open(tpath))
+
+    cfg = ci.config(args.config)
+    res = run_config(cfg, args.steps, args.warmup)
+    bound = "hbm" if cfg.name == "C4" else "mfma"
+    line = {
+        "metric": "tokens/s through clustered-MoE FFN layer (1 GPU)",
+        "value": round(cfg.T / (res["ms_per_step"] * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} G={cfg.G} K={cfg.K} r={cfg.r} "
+                               f"top_k={cfg.k} q={cfg.q} router={cfg.router}",
+                   "clusters_hit": res["clusters_hit"], "experts_hit": res["experts_hit"]},
+        "roofline": roofline(cfg, res, bound, traffic_table),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
+    del res
+    if not args.no_weight_bound and cfg.name != "C4":
+        c4 = ci.config(4)
+        r4 = run_config(c4, max(args.steps, 20), max(args.warmup, 5))
+        line["weight_bound"] = {
+            "workload": f"{c4.name}: T={c4.T} d={c4.d} d_ff={c4.d_ff} G={c4.G} K={c4.K} r={c4.r} top_k={c4.k} q={c4.q}",
+            "value": round(c4.T / (r4["ms_per_step"] * 1e-3), 1), "unit": "tokens/s",
+            "ms_per_step": round(r4["ms_per_step"], 4),
+            "clusters_hit": r4["clusters_hit"], "experts_hit": r4["experts_hit"],
+            "roofline": roofline(c4, r4, "hbm", traffic_table)}
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

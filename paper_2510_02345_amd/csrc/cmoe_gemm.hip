@@ -209,7 +209,7 @@ struct EpiT1 {
       if (p >= t.m_end) continue;
       int tok = perm[p];
       for (int j = 0; j < k; ++j) {
-        int e = expert_idx[(size_t)tok * k + j] - t.c * K;
+        int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
         half_t* row = t1ext + ((size_t)p * k + j) * KRp;
 #pragma unroll
         for (int a = 0; a < TL::NB; ++a) {
@@ -278,7 +278,7 @@ struct EpiFusedUp {
 #pragma unroll
         for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
         if (j < k) {
-          e[j] = expert_idx[(size_t)tok * k + j] - t.c * K;
+          e[j] = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
           gj[j] = valid ? gate[(size_t)tok * k + j] : 0.f;
           t1row[j] = t1ext + ((size_t)pc * k + j) * KRp;
           int lo = (e[j] * r) >> 4, hi = (e[j] * r + r - 1) >> 4, ps = (e[j] * r) >> 5;
@@ -350,7 +350,7 @@ struct EpiFusedUp {
           int pp = t.m0 + m;
           if (pp >= t.m_end) continue;
           int tk = perm[pp];
-          int ee = expert_idx[(size_t)tk * k + j] - t.c * K;
+          int ee = min(max(expert_idx[(size_t)tk * k + j] - t.c * K, 0), K - 1);
           int row = (ee % epb) * r + rho;
           float sum = 0.f;
 #pragma unroll
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(CB_WAVES * 64) void combine_kernel(
     int p = m0 + m;
     if (p >= m_end) continue;
     int tok = perm[p];
-    int e = expert_idx[(size_t)tok * k + j] - c * K;
+    int e = min(max(expert_idx[(size_t)tok * k + j] - c * K, 0), K - 1);
     float v = gate[(size_t)tok * k + j] * s_down[((size_t)tok * k + j) * r + rho];
     sext[m * lds + e * r + rho] = (half_t)v;
     if (rho == 0) atomicOr(&s_cmask, (0xffffffffu >> (31 - (e * r + r - 1) / 16)) & (0xffffffffu << ((e * r) / 16)));
