@@ -1,5 +1,5 @@
 // Grouped matrix-core kernels of the expert computation (Sec. 3.2):
-//   t1   = V1 x                       (all experts of the token's cluster, then masked)
+//   t1   = V1 x                       (all experts of the token's cluster, selected rows kept)
 //   Hb   = W1_base(c) x  -> fused: + U1 t1, GELU, gated sum A, s = V2 a
 //   Yb   = W2_base(c) A
 //   y    = Yb + sum_j g_j U2 s_j, back in token order
@@ -8,23 +8,23 @@
 // v_mfma_f32_32x32x16_f16 (rows n of the 32x32 block), the tokens are the B operand
 // (columns m).  A lane of a 32x32 accumulator block then holds ONE token (column
 // m = lane % 32) and 16 output rows n = 8*(v/4) + 4*(lane/32) + v%4, v = 0..15.  That is
-// what lets the per-token quantities (experts, gates) live in per-lane registers, and lets
-// an accumulator block be fed back as the B operand of the next product without leaving
-// registers (its rows become the contraction index).
+// what lets the per-token quantities (experts, gates, t1) live in per-lane registers, and
+// lets an accumulator block be fed back as the B operand of the next product without
+// leaving registers (its rows become the contraction index).
 #include "cmoe_internal.h"
 
 namespace {
 
-template <int BN_, int BM_, int WAVES_N_, int WAVES_M_>
+template <int BN_, int BM_, int WAVES_N_, int WAVES_M_, int OCC_>
 struct Tile {
-  static constexpr int BN = BN_, BM = BM_, WAVES_N = WAVES_N_, WAVES_M = WAVES_M_;
+  static constexpr int BN = BN_, BM = BM_, WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, OCC = OCC_;
   static constexpr int NT = WAVES_N * WAVES_M * 64;
   static constexpr int WN = BN / WAVES_N, WM = BM / WAVES_M;
   static constexpr int NB = WN / 32, MB = WM / 32;
   static constexpr int BK = 64;        // contraction elements per LDS stage
   static constexpr int LDK = BK + 8;   // padded LDS row (halfs): 144 B, conflict-free b128 reads
   static constexpr int WCH = BN * (BK / 8) / NT, XCH = BM * (BK / 8) / NT;  // 16-B chunks per thread
-  static constexpr int SMEM_HALFS = 2 * (BN + BM) * LDK;
+  static constexpr int SMEM_HALFS = (BN + BM) * LDK;
   static_assert(BN % (32 * WAVES_N) == 0 && BM % (32 * WAVES_M) == 0, "wave tile");
   static_assert((BN * (BK / 8)) % NT == 0 && (BM * (BK / 8)) % NT == 0, "load split");
 };
@@ -50,11 +50,24 @@ __device__ __forceinline__ float16v mfma16(half8 a, half8 b, float16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+// GELU(u) = u * Phi(u), Phi by the erf form.  erf(z), z = |u|/sqrt(2), is evaluated with
+// the classical five-term rational-exponential formula 1 - (a1 t + ... + a5 t^5) exp(-z^2),
+// t = 1/(1 + p z) (absolute error below 1.5e-7), using the hardware exp2 and reciprocal.
+__device__ __forceinline__ float gelu_erf(float u) {
+  const float z = fabsf(u) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
+  float poly = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  poly = fmaf(t, poly, 0.5f * 1.421413741f);
+  poly = fmaf(t, poly, 0.5f * -0.284496736f);
+  poly = fmaf(t, poly, 0.5f * 0.254829592f);
+  const float ex = __builtin_amdgcn_exp2f(u * u * -0.72134752044448170f);  // exp(-u^2/2)
+  const float q = poly * t * ex;                                          // (1 - erf(z)) / 2
+  return u * (u > 0.f ? 1.0f - q : q);
+}
 
 template <class TL, class Epi>
-__global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmArgs g, Epi epi) {
-  __shared__ __attribute__((aligned(16))) half_t smem[TL::SMEM_HALFS];
+__global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Epi epi) {
+  __shared__ __attribute__((aligned(16))) half_t smem[Epi::template smem_halfs<TL>()];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn = wave % TL::WAVES_N, wm = wave / TL::WAVES_N;
 
@@ -76,8 +89,8 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmArgs g, Epi epi) {
   if (c == g.G) return;
   const int n0 = n_tile * TL::BN;
 
-  half_t* sW = smem;                               // [2][BN][LDK]
-  half_t* sX = smem + 2 * TL::BN * TL::LDK;        // [2][BM][LDK]
+  half_t* sW = smem;                        // [BN][LDK]
+  half_t* sX = smem + TL::BN * TL::LDK;     // [BM][LDK]
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
 
   const half_t* gw[TL::WCH];
@@ -113,23 +126,22 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmArgs g, Epi epi) {
   for (int i = 0; i < TL::WCH; ++i) rw[i] = *(const half8*)(gw[i]);
 #pragma unroll
   for (int i = 0; i < TL::XCH; ++i) rx[i] = *(const half8*)(gx[i]);
-#pragma unroll
-  for (int i = 0; i < TL::WCH; ++i) *(half8*)(sW + lw[i]) = rw[i];
-#pragma unroll
-  for (int i = 0; i < TL::XCH; ++i) *(half8*)(sX + lx[i]) = rx[i];
-  __syncthreads();
 
   const int frag_row = lane & 31, frag_col = (lane >> 5) * 8;
+  const half_t* cw = sW + (wn * TL::WN + frag_row) * TL::LDK + frag_col;
+  const half_t* cx = sX + (wm * TL::WM + frag_row) * TL::LDK + frag_col;
   for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
+#pragma unroll
+    for (int i = 0; i < TL::WCH; ++i) *(half8*)(sW + lw[i]) = rw[i];
+#pragma unroll
+    for (int i = 0; i < TL::XCH; ++i) *(half8*)(sX + lx[i]) = rx[i];
+    __syncthreads();
     if (kt + 1 < KT) {
 #pragma unroll
       for (int i = 0; i < TL::WCH; ++i) rw[i] = *(const half8*)(gw[i] + (size_t)(kt + 1) * TL::BK);
 #pragma unroll
       for (int i = 0; i < TL::XCH; ++i) rx[i] = *(const half8*)(gx[i] + (size_t)(kt + 1) * TL::BK);
     }
-    const half_t* cw = sW + cur * TL::BN * TL::LDK + (wn * TL::WN + frag_row) * TL::LDK + frag_col;
-    const half_t* cx = sX + cur * TL::BM * TL::LDK + (wm * TL::WM + frag_row) * TL::LDK + frag_col;
 #pragma unroll
     for (int ks = 0; ks < TL::BK / 16; ++ks) {
       half8 fa[TL::NB], fb[TL::MB];
@@ -141,14 +153,6 @@ __global__ __launch_bounds__(TL::NT) void gemm_nt_kernel(GemmArgs g, Epi epi) {
       for (int a = 0; a < TL::NB; ++a)
 #pragma unroll
         for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
-    }
-    if (kt + 1 < KT) {
-      half_t* nw = sW + (cur ^ 1) * TL::BN * TL::LDK;
-      half_t* nx = sX + (cur ^ 1) * TL::BM * TL::LDK;
-#pragma unroll
-      for (int i = 0; i < TL::WCH; ++i) *(half8*)(nw + lw[i]) = rw[i];
-#pragma unroll
-      for (int i = 0; i < TL::XCH; ++i) *(half8*)(nx + lx[i]) = rx[i];
     }
     __syncthreads();
   }
@@ -172,6 +176,8 @@ struct EpiStore {
   half_t* out;
   int ldo, N;
   template <class TL>
+  static constexpr int smem_halfs() { return TL::SMEM_HALFS; }
+  template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
     const int h = t.lane >> 5;
 #pragma unroll
@@ -190,16 +196,16 @@ struct EpiStore {
   }
 };
 
-// ---------------------------------------------------------------- epilogue: t1, one-hot expanded
-// acc rows are kk = j_local * r + rho over ALL experts of the cluster.  For the token's
-// j-th selected expert e_j only the r rows of e_j are kept, the rest written as zero:
-//   t1ext[p][j][kk] = (kk / r == e_j - c*K) ? (V1 x)[kk] : 0
-// so that U1cat^T (d_ff x K*r) times t1ext[p][j] equals U1_{e_j} (V1_{e_j} x).
+// ---------------------------------------------------------------- epilogue: t1 = V1_{e_j} x
+// acc rows are kk = j_local * r + rho over ALL experts of the cluster; for the token's
+// j-th selected expert only its r rows are kept:  t1[p][j][rho] = acc[(e_j - c*K)*r + rho].
 struct EpiT1 {
-  half_t* t1ext;
+  half_t* t1;  // [T][k][r], sorted rows
   const int* perm;
   const int* expert_idx;
   int k, K, r, KRp;
+  template <class TL>
+  static constexpr int smem_halfs() { return TL::SMEM_HALFS; }
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
     const int h = t.lane >> 5;
@@ -210,17 +216,15 @@ struct EpiT1 {
       int tok = perm[p];
       for (int j = 0; j < k; ++j) {
         int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
-        half_t* row = t1ext + ((size_t)p * k + j) * KRp;
+        half_t* row = t1 + ((size_t)p * k + j) * r;
 #pragma unroll
         for (int a = 0; a < TL::NB; ++a) {
           int nb = t.n0 + t.wn * TL::WN + a * 32;
           if (nb >= KRp) continue;
 #pragma unroll
           for (int qd = 0; qd < 4; ++qd) {
-            int kk = nb + 8 * qd + 4 * h;
-            half4 v = to_half4(acc[a][b], qd);
-            if (kk / r != e) v = half4{0, 0, 0, 0};
-            *(half4*)(row + kk) = v;
+            int kk = nb + 8 * qd + 4 * h;  // 4 consecutive rank rows, all of one expert (r % 4 == 0)
+            if (kk / r == e) *(half4*)(row + (kk - e * r)) = to_half4(acc[a][b], qd);
           }
         }
       }
@@ -230,132 +234,209 @@ struct EpiT1 {
 
 // ---------------------------------------------------------------- epilogue: fused up-projection
 // acc = Hb^T block (rows n of d_ff, columns = tokens).  Per token column and selected
-// expert j:  h_j = Hb + U1cat^T t1ext_j  (matrix core, contraction over kk, empty 16-chunks
-// skipped), a_j = GELU(h_j), A += g_j a_j, and s_j += V2 a_j by feeding the a_j block back
-// as B operand (contraction over the block's 32 rows n).  The V2 product runs over
-// "passes" of 32 rank rows (32/r experts); a lane contributes to a pass only if its
-// token's expert lies in it, so after all passes row (e_j % (32/r))*r + rho of the
-// accumulator holds s_j[rho].
-template <int KMAX>
+// expert j:  h_j = Hb + U1cat^T t1ext_j with t1ext_j the token's t1_j placed at the rank rows
+// of expert e_j and zero elsewhere (matrix core, contraction over the cluster's K*r rank
+// rows in chunks of 16; a chunk no token of the 32-column block needs is skipped);
+// a_j = GELU(h_j); A += g_j a_j; s_j += V2 a_j by feeding the a_j block back as B operand
+// (contraction over the block's 32 rows n).  The V2 product runs over "passes" of 32 rank
+// rows (32/r experts); a lane contributes to a pass only if its token's expert lies in
+// it, so after all passes row (e_j % (32/r))*r + rho of the accumulator holds s_j[rho].
+// With STAGE the U1 / V2 panels of the tile are staged through LDS (K*r <= 128);
+// otherwise they are read from global memory.
+template <int R, int KMAX, bool STAGE>
 struct EpiFusedUp {
-  const half_t* u1t;    // [G][d_ff][KRp]
-  const half_t* v2p;    // [G][KRp][d_ff], columns permuted inside 16-groups
-  const half_t* t1ext;  // [T][k][KRp]
+  const half_t* u1t;  // [G][d_ff][KRp]
+  const half_t* v2p;  // [G][KRp][d_ff], columns permuted inside 16-groups
+  const half_t* t1;   // [T][k][r], sorted rows
   const int* perm;
   const int* expert_idx;
   const float* gate;
-  half_t* A;            // [T][d_ff]
-  float* spart;         // [n_tiles][T][k][r]
-  int T, k, K, r, KRp, d_ff;
+  half_t* A;          // [T][d_ff]
+  float* spart;       // [n_tiles][T][k][r]
+  int T, k, K, KRp, d_ff;
+
+  static constexpr int EPB = 32 / R;  // experts per 32 rank rows
+  static constexpr int NF = (R == 32) ? 2 : 1;
+
+  template <class TL>
+  static constexpr int smem_halfs() {
+    return STAGE ? (TL::SMEM_HALFS > TL::BN * (128 + 8) + 128 * (TL::BN + 8) ? TL::SMEM_HALFS
+                                                                            : TL::BN * (128 + 8) + 128 * (TL::BN + 8))
+                 : TL::SMEM_HALFS;
+  }
+
+  __device__ static __forceinline__ bool chunk_has(int e, int kc) {
+    return R == 32 ? (e == (kc >> 1)) : R == 16 ? (e == kc) : R == 8 ? ((e >> 1) == kc) : ((e >> 2) == kc);
+  }
+  // B operand of chunk kc for a lane whose token selected expert e with t1 fragments f
+  __device__ static __forceinline__ half8 t1_frag(int e, int kc, int h, const half8 (&f)[NF]) {
+    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (R == 32) return (e == (kc >> 1)) ? ((kc & 1) ? f[NF - 1] : f[0]) : z;
+    if (R == 16) return (e == kc) ? f[0] : z;
+    if (R == 8) return (e == 2 * kc + h) ? f[0] : z;
+    half8 o = z;  // R == 4: slots 0..3 are expert 4kc+2h, slots 4..7 expert 4kc+2h+1
+    if (e == 4 * kc + 2 * h) {
+      o[0] = f[0][0]; o[1] = f[0][1]; o[2] = f[0][2]; o[3] = f[0][3];
+    } else if (e == 4 * kc + 2 * h + 1) {
+      o[4] = f[0][0]; o[5] = f[0][1]; o[6] = f[0][2]; o[7] = f[0][3];
+    }
+    return o;
+  }
 
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+    static_assert(TL::WAVES_N == 1, "one wavefront spans the tile's rows n, so s needs no cross-wave sum");
     const int h = t.lane >> 5, ml = t.lane & 31;
     const half_t* u1c = u1t + (size_t)t.c * d_ff * KRp;
     const half_t* v2c = v2p + (size_t)t.c * KRp * d_ff;
-    const int n_chunks = KRp / 16, n_pass = KRp / 32, epb = 32 / r;
-    float* sbuf = (float*)t.smem;  // [WAVES_N][BM][33] floats, reuses the tile buffers
-    static_assert(TL::WAVES_N * TL::BM * 33 * 4 <= TL::SMEM_HALFS * 2, "s buffer fits");
+    const int n_chunks = KRp / 16, n_pass = KRp / 32;
+    const int ldu = KRp + 8, ldv = TL::BN + 8;
+    half_t* sU = t.smem;                 // [BN][KRp + 8]
+    half_t* sV = t.smem + TL::BN * ldu;  // [KRp][BN + 8]
 
-#pragma unroll 1
+    // per-lane token state of every 32-column block this wavefront owns
+    int e[TL::MB][KMAX];
+    float gj[TL::MB][KMAX];
+    half8 f[TL::MB][KMAX][NF];
+    int pp[TL::MB];
+    bool valid[TL::MB];
+#pragma unroll
     for (int b = 0; b < TL::MB; ++b) {
-      const int p = t.m0 + t.wm * TL::WM + b * 32 + ml;
-      const bool valid = p < t.m_end;
-      const int pc = valid ? p : t.m_end - 1;
+      pp[b] = t.m0 + t.wm * TL::WM + b * 32 + ml;
+      valid[b] = pp[b] < t.m_end;
+      const int pc = valid[b] ? pp[b] : t.m_end - 1;
       const int tok = perm[pc];
-      int e[KMAX];
-      float gj[KMAX];
-      unsigned cmask[KMAX], pmask[KMAX];
-      const half_t* t1row[KMAX];
-      float16v sacc[KMAX];
 #pragma unroll
       for (int j = 0; j < KMAX; ++j) {
-        e[j] = 0;
-        gj[j] = 0.f;
-        cmask[j] = 0;
-        pmask[j] = 0;
-        t1row[j] = t1ext;
+        e[b][j] = 0;
+        gj[b][j] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
+        for (int i = 0; i < NF; ++i) f[b][j][i] = half8{0, 0, 0, 0, 0, 0, 0, 0};
         if (j < k) {
-          e[j] = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
-          gj[j] = valid ? gate[(size_t)tok * k + j] : 0.f;
-          t1row[j] = t1ext + ((size_t)pc * k + j) * KRp;
-          int lo = (e[j] * r) >> 4, hi = (e[j] * r + r - 1) >> 4, ps = (e[j] * r) >> 5;
-          for (int kc = 0; kc < n_chunks; ++kc)
-            if (__ballot(valid && kc >= lo && kc <= hi) != 0ull) cmask[j] |= 1u << kc;
-          for (int q = 0; q < n_pass; ++q)
-            if (__ballot(valid && q == ps) != 0ull) pmask[j] |= 1u << q;
+          e[b][j] = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
+          gj[b][j] = valid[b] ? gate[(size_t)tok * k + j] : 0.f;
+          const half_t* tr = t1 + ((size_t)pc * k + j) * R;
+          if (R == 32) {
+            f[b][j][0] = *(const half8*)(tr + 8 * h);
+            f[b][j][NF - 1] = *(const half8*)(tr + 16 + 8 * h);
+          } else if (R == 16) {
+            f[b][j][0] = *(const half8*)(tr + 8 * h);
+          } else if (R == 8) {
+            f[b][j][0] = *(const half8*)(tr);
+          } else {
+            half4 q4 = *(const half4*)(tr);
+            f[b][j][0][0] = q4[0]; f[b][j][0][1] = q4[1]; f[b][j][0][2] = q4[2]; f[b][j][0][3] = q4[3];
+          }
         }
       }
+    }
+
+    if (STAGE) {
+      // the main loop ended on a barrier: the tile buffers are free
+      constexpr int UB = 4;
+      const int u_chunks = TL::BN * (KRp / 8), ucpr = KRp / 8;
+      for (int base = t.tid; base < u_chunks; base += UB * TL::NT) {
+        half8 tmp[UB];
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < u_chunks) {
+            int row = idx / ucpr, ch = idx % ucpr;
+            tmp[i] = *(const half8*)(u1c + (size_t)min(t.n0 + row, d_ff - 1) * KRp + ch * 8);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < u_chunks) *(half8*)(sU + (idx / ucpr) * ldu + (idx % ucpr) * 8) = tmp[i];
+        }
+      }
+      const int v_chunks = KRp * (TL::BN / 8), vcpr = TL::BN / 8;
+      for (int base = t.tid; base < v_chunks; base += UB * TL::NT) {
+        half8 tmp[UB];
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < v_chunks) {
+            int row = idx / vcpr, ch = idx % vcpr;
+            tmp[i] = *(const half8*)(v2c + (size_t)row * d_ff + min(t.n0 + ch * 8, d_ff - 8));
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < v_chunks) *(half8*)(sV + (idx / vcpr) * ldv + (idx % vcpr) * 8) = tmp[i];
+        }
+      }
+      __syncthreads();
+    }
+
+#pragma unroll
+    for (int b = 0; b < TL::MB; ++b) {
+      float16v sacc[KMAX];
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
 #pragma unroll
       for (int a = 0; a < TL::NB; ++a) {
-        const int nb = t.n0 + t.wn * TL::WN + a * 32;
+        const int nb = t.n0 + a * 32;
         if (nb >= d_ff) continue;
-        const half_t* u1row = u1c + (size_t)(nb + ml) * KRp + 8 * h;
         float16v o;
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[v] = 0.f;
 #pragma unroll
         for (int j = 0; j < KMAX; ++j) {
           if (j >= k) continue;
+          const int ej = e[b][j];
           float16v hj = acc[a][b];
           for (int kc = 0; kc < n_chunks; ++kc) {
-            if (!((cmask[j] >> kc) & 1u)) continue;
-            half8 fa = *(const half8*)(u1row + kc * 16);
-            half8 fb = *(const half8*)(t1row[j] + kc * 16 + 8 * h);
-            hj = mfma16(fa, fb, hj);
+            if (__ballot(valid[b] && chunk_has(ej, kc)) == 0ull) continue;
+            half8 fa = STAGE ? *(const half8*)(sU + (a * 32 + ml) * ldu + kc * 16 + 8 * h)
+                             : *(const half8*)(u1c + (size_t)(nb + ml) * KRp + kc * 16 + 8 * h);
+            hj = mfma16(fa, t1_frag(ej, kc, h, f[b][j]), hj);
           }
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             hj[v] = gelu_erf(hj[v]);
-            o[v] += gj[j] * hj[v];
+            o[v] = fmaf(gj[b][j], hj[v], o[v]);
           }
-          const int my_pass = (e[j] * r) >> 5;
           for (int q = 0; q < n_pass; ++q) {
-            if (!((pmask[j] >> q) & 1u)) continue;
-            const bool on = valid && (q == my_pass);
-            const half_t* v2row = v2c + (size_t)(q * 32 + ml) * d_ff + nb + 8 * h;
+            const bool on = valid[b] && (ej / EPB == q);
+            if (__ballot(on) == 0ull) continue;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
               half8 fb;
 #pragma unroll
               for (int i = 0; i < 8; ++i) fb[i] = on ? (half_t)hj[8 * s + i] : (half_t)0.f;
-              half8 fa = *(const half8*)(v2row + 16 * s);
+              half8 fa = STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + a * 32 + 16 * s + 8 * h)
+                               : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s + 8 * h);
               sacc[j] = mfma16(fa, fb, sacc[j]);
             }
           }
         }
-        if (valid) {
+        if (valid[b]) {
 #pragma unroll
-          for (int qd = 0; qd < 4; ++qd) *(half4*)(A + (size_t)p * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
+          for (int qd = 0; qd < 4; ++qd)
+            *(half4*)(A + (size_t)pp[b] * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
         }
       }
-      // s partial of this column block: sum over the wavefronts that split the rows n,
-      // in a fixed order, one selected expert at a time through LDS
-      for (int j = 0; j < k; ++j) {
-        __syncthreads();
-        float* mine = sbuf + ((size_t)t.wn * TL::BM + t.wm * TL::WM + b * 32 + ml) * 33;
+      // partial s of this column tile: the lane holds rows 8*qd + 4h + (0..3) of the pass
+      // accumulator; those inside [b_e*R, b_e*R + R) are the token's s_j
+      if (valid[b]) {
 #pragma unroll
-        for (int jj = 0; jj < KMAX; ++jj) {
-          if (jj != j) continue;
+        for (int j = 0; j < KMAX; ++j) {
+          if (j >= k) continue;
+          const int be = (e[b][j] % EPB) * R;
+          float* dst = spart + (((size_t)t.n_tile * T + pp[b]) * k + j) * R;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) mine[8 * (v >> 2) + 4 * h + (v & 3)] = sacc[jj][v];
-        }
-        __syncthreads();
-        // rows of this b-block only: [wm*WM + b*32, +32) for every wm
-        for (int idx = t.tid; idx < TL::WAVES_M * 32 * r; idx += TL::NT) {
-          int rho = idx % r, mm = idx / r;
-          int m = (mm / 32) * TL::WM + b * 32 + (mm % 32);
-          int pp = t.m0 + m;
-          if (pp >= t.m_end) continue;
-          int tk = perm[pp];
-          int ee = min(max(expert_idx[(size_t)tk * k + j] - t.c * K, 0), K - 1);
-          int row = (ee % epb) * r + rho;
-          float sum = 0.f;
-#pragma unroll
-          for (int w = 0; w < TL::WAVES_N; ++w) sum += sbuf[((size_t)w * TL::BM + m) * 33 + row];
-          spart[(((size_t)t.n_tile * T + pp) * k + j) * r + rho] = sum;
+          for (int qd = 0; qd < 4; ++qd) {
+            int row0 = 8 * qd + 4 * h;
+            if (row0 >= be && row0 < be + R) {
+              float4v v4 = {sacc[j][4 * qd], sacc[j][4 * qd + 1], sacc[j][4 * qd + 2], sacc[j][4 * qd + 3]};
+              *(float4v*)(dst + row0 - be) = v4;
+            }
+          }
         }
       }
     }
@@ -451,7 +532,10 @@ __global__ __launch_bounds__(CB_WAVES * 64) void combine_kernel(
   }
 }
 
-using TileMain = Tile<128, 128, 2, 2>;
+// 128 weight rows x 256 tokens per workgroup, four wavefronts side by side along the
+// tokens (each 128 x 64), two workgroups per CU so that one's epilogue overlaps the
+// other's main loop.
+using TileMain = Tile<128, 256, 1, 4, 2>;
 static_assert(TileMain::BN == G1_BN, "workspace sizing assumes this column tile");
 
 template <class TL, class Epi>
@@ -462,35 +546,52 @@ hipError_t launch_gemm(const GemmArgs& g, int T, const Epi& epi, hipStream_t st)
   return hipGetLastError();
 }
 
+template <int R, int KMAX>
+hipError_t launch_gemm1_rk(const cmoe_dims& dm, const GemmArgs& g, int T, const int* perm, const int* expert_idx,
+                           const float* gate, const half_t* u1t, const half_t* v2p, const half_t* t1, half_t* a,
+                           float* spart, hipStream_t st) {
+  using TL = TileMain;
+  if (dm.KRp <= 128) {
+    EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+    return launch_gemm<TL>(g, T, epi, st);
+  }
+  EpiFusedUp<R, KMAX, false> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+  return launch_gemm<TL>(g, T, epi, st);
+}
+
+template <int R>
+hipError_t launch_gemm1_r(const cmoe_dims& dm, const GemmArgs& g, int T, const int* perm, const int* expert_idx,
+                          const float* gate, const half_t* u1t, const half_t* v2p, const half_t* t1, half_t* a,
+                          float* spart, hipStream_t st) {
+  if (dm.k <= 1) return launch_gemm1_rk<R, 1>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+  if (dm.k <= 2) return launch_gemm1_rk<R, 2>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+  if (dm.k <= 4) return launch_gemm1_rk<R, 4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+  return launch_gemm1_rk<R, 8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+}
+
 }  // namespace
 
 hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
-                     const int* expert_idx, const half_t* v1cat, half_t* t1ext, hipStream_t st) {
+                     const int* expert_idx, const half_t* v1cat, half_t* t1, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{v1cat, (long)dm.KRp * dm.d, dm.d, dm.KRp, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.KRp + TL::BN - 1) / TL::BN};
-  EpiT1 epi{t1ext, perm, expert_idx, dm.k, dm.K, dm.r, dm.KRp};
+  EpiT1 epi{t1, perm, expert_idx, dm.k, dm.K, dm.r, dm.KRp};
   return launch_gemm<TL>(g, T, epi, st);
 }
 
 hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
-                        const half_t* v2p, const half_t* t1ext, half_t* a, float* spart, hipStream_t st) {
+                        const half_t* v2p, const half_t* t1, half_t* a, float* spart, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.d_ff + TL::BN - 1) / TL::BN};
-  if (dm.k <= 1) {
-    EpiFusedUp<1> epi{u1t, v2p, t1ext, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.r, dm.KRp, dm.d_ff};
-    return launch_gemm<TL>(g, T, epi, st);
-  } else if (dm.k <= 2) {
-    EpiFusedUp<2> epi{u1t, v2p, t1ext, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.r, dm.KRp, dm.d_ff};
-    return launch_gemm<TL>(g, T, epi, st);
-  } else if (dm.k <= 4) {
-    EpiFusedUp<4> epi{u1t, v2p, t1ext, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.r, dm.KRp, dm.d_ff};
-    return launch_gemm<TL>(g, T, epi, st);
+  switch (dm.r) {
+    case 4: return launch_gemm1_r<4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+    case 8: return launch_gemm1_r<8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+    case 16: return launch_gemm1_r<16>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
+    default: return launch_gemm1_r<32>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
   }
-  EpiFusedUp<8> epi{u1t, v2p, t1ext, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.r, dm.KRp, dm.d_ff};
-  return launch_gemm<TL>(g, T, epi, st);
 }
 
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, float* s_down,
