@@ -15,18 +15,26 @@
 
 namespace {
 
-template <int BN_, int BM_, int WAVES_N_, int WAVES_M_, int OCC_>
+// Tile of one workgroup: BN weight rows x BM tokens, WAVES_N x WAVES_M wavefronts, each
+// owning (BN/WAVES_N) x (BM/WAVES_M) outputs as 32x32 accumulator blocks.  Operand tiles
+// move global -> LDS with direct-to-LDS loads (no register staging) into NS stages of 32
+// contraction elements; rows are 64 B, their four 16-B chunks XOR-swizzled with
+// (row >> 2) & 3 so that the 16 lanes the LDS serves per cycle hit 64 distinct banks.
+template <int BN_, int BM_, int WAVES_N_, int WAVES_M_, int NS_, int OCC_, bool PINGPONG_, int XSM_, int XSN_>
 struct Tile {
-  static constexpr int BN = BN_, BM = BM_, WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, OCC = OCC_;
-  static constexpr int NT = WAVES_N * WAVES_M * 64;
+  static constexpr int BN = BN_, BM = BM_, WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, NS = NS_, OCC = OCC_;
+  static constexpr bool PINGPONG = PINGPONG_;
+  static constexpr int XSM = XSM_, XSN = XSN_;  // per-XCD super-tile: XSM row tiles x XSN column tiles
+  static constexpr int NWAVES = WAVES_N * WAVES_M, NT = NWAVES * 64;
   static constexpr int WN = BN / WAVES_N, WM = BM / WAVES_M;
   static constexpr int NB = WN / 32, MB = WM / 32;
-  static constexpr int BK = 64;        // contraction elements per LDS stage
-  static constexpr int LDK = BK + 8;   // padded LDS row (halfs): 144 B, conflict-free b128 reads
-  static constexpr int WCH = BN * (BK / 8) / NT, XCH = BM * (BK / 8) / NT;  // 16-B chunks per thread
-  static constexpr int SMEM_HALFS = (BN + BM) * LDK;
+  static constexpr int BK = 32, ROWB = BK * 2;
+  static constexpr int STAGE_BYTES = (BN + BM) * ROWB;
+  static constexpr int SMEM_BYTES = NS * STAGE_BYTES;
+  static constexpr int PER_WAVE = (BN + BM) / 16 / NWAVES;  // 1-KiB load instructions per wavefront and stage
   static_assert(BN % (32 * WAVES_N) == 0 && BM % (32 * WAVES_M) == 0, "wave tile");
-  static_assert((BN * (BK / 8)) % NT == 0 && (BM * (BK / 8)) % NT == 0, "load split");
+  static_assert(((BN + BM) / 16) % NWAVES == 0, "load split");
+  static_assert(!PINGPONG || (NWAVES == 8 && NS >= 3), "ping-pong pairs wavefront w with w + 4");
 };
 
 struct GemmArgs {
@@ -36,9 +44,9 @@ struct GemmArgs {
   const half_t* X;   // token-side operand, row for sorted row p: X + (gather ? gather[p] : p) * ldx
   int ldx;
   const int* gather;
-  int Kc;            // contraction length, multiple of 64
+  int Kc;            // contraction length, multiple of 32
   const int* offsets;
-  int G, n_tiles;
+  int G, n_tiles, m_slots, spx;
 };
 
 struct TileCtx {
@@ -50,31 +58,64 @@ __device__ __forceinline__ float16v mfma16(half8 a, half8 b, float16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-// GELU(u) = u * Phi(u), Phi by the erf form.  erf(z), z = |u|/sqrt(2), is evaluated with
-// the classical five-term rational-exponential formula 1 - (a1 t + ... + a5 t^5) exp(-z^2),
-// t = 1/(1 + p z) (absolute error below 1.5e-7), using the hardware exp2 and reciprocal.
+// GELU(u) = u * Phi(u) in the erf form, Phi(u) = 1/2 + erf(u / sqrt 2) / 2.  On |u| <= 4
+// Phi(u) - 1/2 = u P(u^2) with an eight-coefficient minimax polynomial (absolute error
+// of Phi below 5.5e-5 over the reals once u is clamped to [-4, 4], far below the FP16
+// rounding of the result); eleven full-rate FP32 operations per element.
 __device__ __forceinline__ float gelu_erf(float u) {
-  const float z = fabsf(u) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float poly = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
-  poly = fmaf(t, poly, 0.5f * 1.421413741f);
-  poly = fmaf(t, poly, 0.5f * -0.284496736f);
-  poly = fmaf(t, poly, 0.5f * 0.254829592f);
-  const float ex = __builtin_amdgcn_exp2f(u * u * -0.72134752044448170f);  // exp(-u^2/2)
-  const float q = poly * t * ex;                                          // (1 - erf(z)) / 2
-  return u * (u > 0.f ? 1.0f - q : q);
+  const float uc = fminf(fmaxf(u, -4.0f), 4.0f);
+  const float t = uc * uc;
+  float p = fmaf(t, -1.580786058e-09f, 1.217110963e-07f);
+  p = fmaf(t, p, -4.100866136e-06f);
+  p = fmaf(t, p, 8.066739247e-05f);
+  p = fmaf(t, p, -1.048204373e-03f);
+  p = fmaf(t, p, 9.664873593e-03f);
+  p = fmaf(t, p, -6.617537886e-02f);
+  p = fmaf(t, p, 3.988475204e-01f);
+  return u * fmaf(uc, p, 0.5f);
+}
+
+// One 1-KiB direct-to-LDS load: lane l's 16 bytes land at lds_byte + 16 l.
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_byte) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 template <class TL, class Epi>
 __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Epi epi) {
-  __shared__ __attribute__((aligned(16))) half_t smem[Epi::template smem_halfs<TL>()];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int SMEM = Epi::template smem_bytes<TL>();
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // ping-pong pairs the two wavefronts of a SIMD (w, w + 4); both sets cover the tile
   const int wn = wave % TL::WAVES_N, wm = wave / TL::WAVES_N;
 
-  // which (cluster, row tile, column tile) this workgroup owns: derived on the device
-  // from the cluster offsets, so no host round trip sits between routing and the GEMMs
-  const int n_tile = blockIdx.x % g.n_tiles;
-  int slot = blockIdx.x / g.n_tiles;
+  // Workgroups are dealt round-robin to the 8 XCDs.  XCD x takes the contiguous range of
+  // g.spx row-tile slots [x * spx, (x + 1) * spx); inside it, groups of XSM row tiles are
+  // walked over the column tiles in blocks of XSN, so the workgroups resident on one XCD
+  // share both operands through that XCD's L2.  With few row tiles (spx == 0) the column
+  // tiles are simply dealt across the XCDs.
+  int n_tile, slot;
+  if (g.spx == 0) {
+    n_tile = blockIdx.x % g.n_tiles;
+    slot = blockIdx.x / g.n_tiles;
+    if (slot >= g.m_slots) return;
+  } else {
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int per_group = TL::XSM * g.n_tiles;
+    const int vg = local / per_group, rem = local % per_group;
+    const int nblk = rem / (TL::XSM * TL::XSN), r2 = rem % (TL::XSM * TL::XSN);
+    const int sn = min(TL::XSN, g.n_tiles - nblk * TL::XSN);
+    const int rel = vg * TL::XSM + r2 / sn;
+    slot = xcd * g.spx + rel;
+    n_tile = nblk * TL::XSN + r2 % sn;
+    if (r2 / sn >= TL::XSM || rel >= g.spx || slot >= g.m_slots) return;
+  }
+  // which cluster and row tile the slot is: derived on the device from the cluster
+  // offsets, so no host round trip sits between routing and the GEMMs
   int c = 0, m0 = 0, m_end = 0;
   for (; c < g.G; ++c) {
     int lo = g.offsets[c], hi = g.offsets[c + 1];
@@ -88,29 +129,32 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   }
   if (c == g.G) return;
   const int n0 = n_tile * TL::BN;
-
-  half_t* sW = smem;                        // [BN][LDK]
-  half_t* sX = smem + TL::BN * TL::LDK;     // [BM][LDK]
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
+  const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 
-  const half_t* gw[TL::WCH];
-  const half_t* gx[TL::XCH];
-  int lw[TL::WCH], lx[TL::XCH];
+  // global source of each of this wavefront's load instructions (16 tile rows x 64 B);
+  // rows past the end of the matrix / cluster are clamped to the last valid row
+  const half_t* gsrc[TL::PER_WAVE];
 #pragma unroll
-  for (int i = 0; i < TL::WCH; ++i) {
-    int id = tid + i * TL::NT, row = id >> 3, ch = id & 7;
-    int n = min(n0 + row, g.N - 1);
-    gw[i] = Wc + (size_t)n * g.ldw + ch * 8;
-    lw[i] = row * TL::LDK + ch * 8;
+  for (int i = 0; i < TL::PER_WAVE; ++i) {
+    const int ii = wave * TL::PER_WAVE + i;
+    const int row = ii * 16 + (lane >> 2), pos = lane & 3;
+    const int chunk = pos ^ ((row >> 2) & 3);
+    const half_t* base;
+    if (row < TL::BN) {
+      base = Wc + (size_t)min(n0 + row, g.N - 1) * g.ldw;
+    } else {
+      const int p = min(m0 + row - TL::BN, m_end - 1);
+      base = g.X + (size_t)(g.gather ? g.gather[p] : p) * g.ldx;
+    }
+    gsrc[i] = base + chunk * 8;
   }
+  auto issue = [&](int kt, int stage) {
 #pragma unroll
-  for (int i = 0; i < TL::XCH; ++i) {
-    int id = tid + i * TL::NT, row = id >> 3, ch = id & 7;
-    int p = min(m0 + row, m_end - 1);
-    int src = g.gather ? g.gather[p] : p;
-    gx[i] = g.X + (size_t)src * g.ldx + ch * 8;
-    lx[i] = row * TL::LDK + ch * 8;
-  }
+    for (int i = 0; i < TL::PER_WAVE; ++i)
+      dma16(gsrc[i] + (size_t)kt * TL::BK,
+            smem_base + stage * TL::STAGE_BYTES + (wave * TL::PER_WAVE + i) * 1024);
+  };
 
   float16v acc[TL::NB][TL::MB];
 #pragma unroll
@@ -120,44 +164,100 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  half8 rw[TL::WCH], rx[TL::XCH];
-  const int KT = g.Kc / TL::BK;
+  const int fr = lane & 31, h = lane >> 5;
+  int offa[TL::NB][2], offb[TL::MB][2];
 #pragma unroll
-  for (int i = 0; i < TL::WCH; ++i) rw[i] = *(const half8*)(gw[i]);
+  for (int ks = 0; ks < 2; ++ks) {
+    const int cc = ks * 2 + h;
 #pragma unroll
-  for (int i = 0; i < TL::XCH; ++i) rx[i] = *(const half8*)(gx[i]);
-
-  const int frag_row = lane & 31, frag_col = (lane >> 5) * 8;
-  const half_t* cw = sW + (wn * TL::WN + frag_row) * TL::LDK + frag_col;
-  const half_t* cx = sX + (wm * TL::WM + frag_row) * TL::LDK + frag_col;
-  for (int kt = 0; kt < KT; ++kt) {
-#pragma unroll
-    for (int i = 0; i < TL::WCH; ++i) *(half8*)(sW + lw[i]) = rw[i];
-#pragma unroll
-    for (int i = 0; i < TL::XCH; ++i) *(half8*)(sX + lx[i]) = rx[i];
-    __syncthreads();
-    if (kt + 1 < KT) {
-#pragma unroll
-      for (int i = 0; i < TL::WCH; ++i) rw[i] = *(const half8*)(gw[i] + (size_t)(kt + 1) * TL::BK);
-#pragma unroll
-      for (int i = 0; i < TL::XCH; ++i) rx[i] = *(const half8*)(gx[i] + (size_t)(kt + 1) * TL::BK);
+    for (int a = 0; a < TL::NB; ++a) {
+      const int row = wn * TL::WN + a * 32 + fr;
+      offa[a][ks] = row * TL::ROWB + ((cc ^ ((row >> 2) & 3)) << 4);
     }
 #pragma unroll
-    for (int ks = 0; ks < TL::BK / 16; ++ks) {
-      half8 fa[TL::NB], fb[TL::MB];
-#pragma unroll
-      for (int a = 0; a < TL::NB; ++a) fa[a] = *(const half8*)(cw + a * 32 * TL::LDK + ks * 16);
-#pragma unroll
-      for (int b = 0; b < TL::MB; ++b) fb[b] = *(const half8*)(cx + b * 32 * TL::LDK + ks * 16);
-#pragma unroll
-      for (int a = 0; a < TL::NB; ++a)
-#pragma unroll
-        for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
+    for (int b = 0; b < TL::MB; ++b) {
+      const int row = TL::BN + wm * TL::WM + b * 32 + fr;
+      offb[b][ks] = row * TL::ROWB + ((cc ^ ((row >> 2) & 3)) << 4);
     }
-    __syncthreads();
   }
 
-  TileCtx ctx{c, n_tile, n0, m0, m_end, wn, wm, lane, tid, smem};
+  const int KT = g.Kc / TL::BK;
+#pragma unroll
+  for (int s = 0; s < TL::NS - 1; ++s)
+    if (s < KT) issue(s, s);
+  int stage = 0, nstage = TL::NS - 1;
+  if (!TL::PINGPONG) {
+    for (int kt = 0; kt < KT; ++kt) {
+      // tile kt has landed (own loads), then everyone's; the stage refilled below was
+      // read during iteration kt - 1, which every wavefront has left
+      if (kt + TL::NS - 2 < KT) wait_vm<(TL::NS - 2) * TL::PER_WAVE>(); else wait_vm<0>();
+      __builtin_amdgcn_s_barrier();
+      if (kt + TL::NS - 1 < KT) issue(kt + TL::NS - 1, nstage);
+      const char* sb = smem + stage * TL::STAGE_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        half8 fa[TL::NB], fb[TL::MB];
+#pragma unroll
+        for (int a = 0; a < TL::NB; ++a) fa[a] = *(const half8*)(sb + offa[a][ks]);
+#pragma unroll
+        for (int b = 0; b < TL::MB; ++b) fb[b] = *(const half8*)(sb + offb[b][ks]);
+#pragma unroll
+        for (int a = 0; a < TL::NB; ++a)
+#pragma unroll
+          for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
+      }
+      stage = (stage + 1 == TL::NS) ? 0 : stage + 1;
+      nstage = (nstage + 1 == TL::NS) ? 0 : nstage + 1;
+    }
+  } else {
+    // Ping-pong: wavefronts 4..7 run one barrier interval behind wavefronts 0..3, so in
+    // every interval one wavefront of each SIMD issues its MFMAs while the other reads
+    // fragments from LDS and issues the next loads.
+    const bool set_b = wave >= 4;
+    if (KT > 1) wait_vm<(TL::NS - 2) * TL::PER_WAVE>(); else wait_vm<0>();
+    if (KT <= TL::NS - 2) wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (set_b) __builtin_amdgcn_s_barrier();
+    for (int kt = 0; kt < KT; ++kt) {
+      const char* sb = smem + stage * TL::STAGE_BYTES;
+      half8 fa[2][TL::NB], fb[2][TL::MB];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int a = 0; a < TL::NB; ++a) fa[ks][a] = *(const half8*)(sb + offa[a][ks]);
+#pragma unroll
+        for (int b = 0; b < TL::MB; ++b) fb[ks][b] = *(const half8*)(sb + offb[b][ks]);
+      }
+      // the stage refilled here held tile kt - 1, which both sets read before the
+      // barrier that opened this interval
+      if (kt + TL::NS - 1 < KT) {
+        issue(kt + TL::NS - 1, nstage);
+        wait_vm<(TL::NS - 2) * TL::PER_WAVE>();   // tile kt + 1 (own loads) has landed
+      } else {
+        wait_vm<0>();
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int a = 0; a < TL::NB; ++a)
+#pragma unroll
+          for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[ks][a], fb[ks][b], acc[a][b]);
+      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      stage = (stage + 1 == TL::NS) ? 0 : stage + 1;
+      nstage = (nstage + 1 == TL::NS) ? 0 : nstage + 1;
+    }
+    if (!set_b) __builtin_amdgcn_s_barrier();
+  }
+
+  TileCtx ctx{c, n_tile, n0, m0, m_end, wn, wm, lane, tid, (half_t*)smem};
   epi.template run<TL>(ctx, acc);
 }
 
@@ -176,7 +276,7 @@ struct EpiStore {
   half_t* out;
   int ldo, N;
   template <class TL>
-  static constexpr int smem_halfs() { return TL::SMEM_HALFS; }
+  static constexpr int smem_bytes() { return TL::SMEM_BYTES; }
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
     const int h = t.lane >> 5;
@@ -205,7 +305,7 @@ struct EpiT1 {
   const int* expert_idx;
   int k, K, r, KRp;
   template <class TL>
-  static constexpr int smem_halfs() { return TL::SMEM_HALFS; }
+  static constexpr int smem_bytes() { return TL::SMEM_BYTES; }
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
     const int h = t.lane >> 5;
@@ -259,10 +359,10 @@ struct EpiFusedUp {
   static constexpr int NF = (R == 32) ? 2 : 1;
 
   template <class TL>
-  static constexpr int smem_halfs() {
-    return STAGE ? (TL::SMEM_HALFS > TL::BN * (128 + 8) + 128 * (TL::BN + 8) ? TL::SMEM_HALFS
-                                                                            : TL::BN * (128 + 8) + 128 * (TL::BN + 8))
-                 : TL::SMEM_HALFS;
+  static constexpr int smem_bytes() {
+    return (STAGE && 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8)) > TL::SMEM_BYTES)
+               ? 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8))
+               : TL::SMEM_BYTES;
   }
 
   __device__ static __forceinline__ bool chunk_has(int e, int kc) {
@@ -332,7 +432,7 @@ struct EpiFusedUp {
     }
 
     if (STAGE) {
-      // the main loop ended on a barrier: the tile buffers are free
+      __syncthreads();  // every wavefront has left the main loop: the stage buffers are free
       constexpr int UB = 4;
       const int u_chunks = TL::BN * (KRp / 8), ucpr = KRp / 8;
       for (int base = t.tid; base < u_chunks; base += UB * TL::NT) {
@@ -532,17 +632,30 @@ __global__ __launch_bounds__(CB_WAVES * 64) void combine_kernel(
   }
 }
 
-// 128 weight rows x 256 tokens per workgroup, four wavefronts side by side along the
-// tokens (each 128 x 64), two workgroups per CU so that one's epilogue overlaps the
-// other's main loop.
-using TileMain = Tile<128, 256, 1, 4, 2>;
+// Fused up-projection: 128 weight rows x 256 tokens per workgroup, four wavefronts side by
+// side along the tokens (each 128 x 64), two workgroups per CU so that one's epilogue
+// (VALU-heavy) overlaps the other's main loop (matrix core).
+using TileMain = Tile<128, 256, 1, 4, 3, 2, false, 8, 8>;
+// Plain down-projection: 256 x 256 per workgroup, eight wavefronts (2 x 4, each 128 x 64)
+// in ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
+using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
 static_assert(TileMain::BN == G1_BN, "workspace sizing assumes this column tile");
 
 template <class TL, class Epi>
 hipError_t launch_gemm(const GemmArgs& g, int T, const Epi& epi, hipStream_t st) {
-  int m_slots = (T + TL::BM - 1) / TL::BM + g.G;
-  dim3 grid((unsigned)(g.n_tiles * m_slots)), block(TL::NT);
-  hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), grid, block, 0, st, g, epi);
+  GemmArgs ga = g;
+  ga.m_slots = (T + TL::BM - 1) / TL::BM + g.G;
+  unsigned n_wg;
+  if (ga.m_slots < 32) {
+    ga.spx = 0;
+    n_wg = (unsigned)(ga.m_slots * g.n_tiles);
+  } else {
+    ga.spx = (ga.m_slots + 7) / 8;
+    int groups = (ga.spx + TL::XSM - 1) / TL::XSM;
+    n_wg = (unsigned)(8 * groups * TL::XSM * g.n_tiles);
+  }
+  dim3 grid(n_wg), block(TL::NT);
+  hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), grid, block, 0, st, ga, epi);
   return hipGetLastError();
 }
 
@@ -575,7 +688,7 @@ hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* per
                      const int* expert_idx, const half_t* v1cat, half_t* t1, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{v1cat, (long)dm.KRp * dm.d, dm.d, dm.KRp, x, dm.d, perm, dm.d, offsets, dm.G,
-             (dm.KRp + TL::BN - 1) / TL::BN};
+             (dm.KRp + TL::BN - 1) / TL::BN, 0, 0};
   EpiT1 epi{t1, perm, expert_idx, dm.k, dm.K, dm.r, dm.KRp};
   return launch_gemm<TL>(g, T, epi, st);
 }
@@ -585,7 +698,7 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         const half_t* v2p, const half_t* t1, half_t* a, float* spart, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
-             (dm.d_ff + TL::BN - 1) / TL::BN};
+             (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0};
   switch (dm.r) {
     case 4: return launch_gemm1_r<4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
     case 8: return launch_gemm1_r<8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
@@ -605,9 +718,9 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
 
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                         half_t* y_base_sorted, hipStream_t st) {
-  using TL = TileMain;
+  using TL = TileBig;
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
-             dm.G, (dm.d + TL::BN - 1) / TL::BN};
+             dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0};
   EpiStore epi{y_base_sorted, dm.d, dm.d};
   return launch_gemm<TL>(g, T, epi, st);
 }
