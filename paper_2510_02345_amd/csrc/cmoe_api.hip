@@ -18,7 +18,8 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   };
   size_t Tz = (size_t)(T > 0 ? T : 0);
   size_t n_blocks = (Tz + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
-  size_t n_tiles = ((size_t)dm.d_ff + G1_BN - 1) / G1_BN;
+  size_t n_tiles = (T <= SKINNY_T) ? ((size_t)dm.d_ff + SKINNY_SN - 1) / SKINNY_SN
+                                   : ((size_t)dm.d_ff + G1_BN - 1) / G1_BN;
   L.blk_counts = take(sizeof(int32_t) * (n_blocks + 1) * dm.G);
   L.v1cat = take(sizeof(half_t) * dm.G * dm.KRp * dm.d);
   L.u1t = take(sizeof(half_t) * dm.G * dm.d_ff * dm.KRp);
@@ -238,11 +239,20 @@ extern "C" int cmoe_ffn_forward(cmoe_handle* h, const cmoe_weights* w, const cmo
   half_t* t1ext = (half_t*)(ws + L.t1ext);
   half_t* a = (half_t*)(ws + L.a);
   float* spart = (float*)(ws + L.spart);
+  if (T <= SKINNY_T) {
+    // few tokens: the layer is bound by streaming the base matrices once
+    CMOE_LAUNCH(TS_T1, launch_skinny_t1(dm, *w, (const half_t*)x, T, perm, expert_idx, t1ext, st));
+    CMOE_LAUNCH(TS_GEMM1, launch_skinny_up(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, gate, t1ext, a,
+                                           spart, st));
+    CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, dm.d_ff / SKINNY_SN, s_down, st));
+    CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
+    return CMOE_OK;
+  }
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, st));
   CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, perm, offsets, expert_idx, v1cat, t1ext, st));
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, gate, u1t, v2p, t1ext,
                                      a, spart, st));
-  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, s_down, st));
+  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
   CMOE_LAUNCH(TS_GEMM2, launch_gemm2(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
   return CMOE_OK;
 }
@@ -262,6 +272,11 @@ extern "C" int cmoe_combine(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
   hipStream_t st = (hipStream_t)stream;
   const cmoe_dims& dm = h->dm;
   cmoe_ws_layout L = cmoe_layout(dm, T);
+  if (T <= SKINNY_T) {
+    CMOE_LAUNCH(TS_COMBINE, launch_skinny_combine(dm, *w, (const half_t*)y_base_sorted, s_down, inv_perm,
+                                                  expert_idx, gate, T, (half_t*)y, st));
+    return CMOE_OK;
+  }
   half_t* u2t = (half_t*)((char*)workspace + L.u2t);
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
   CMOE_LAUNCH(TS_COMBINE, launch_combine(dm, u2t, (const half_t*)y_base_sorted, s_down, perm, offsets, expert_idx,

@@ -11,7 +11,7 @@
 // what lets the per-token quantities (experts, gates, t1) live in per-lane registers, and
 // lets an accumulator block be fed back as the B operand of the next product without
 // leaving registers (its rows become the contraction index).
-#include "cmoe_internal.h"
+#include "cmoe_device.h"
 
 namespace {
 
@@ -53,27 +53,6 @@ struct TileCtx {
   int c, n_tile, n0, m0, m_end, wn, wm, lane, tid;
   half_t* smem;
 };
-
-__device__ __forceinline__ float16v mfma16(half8 a, half8 b, float16v c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
-}
-
-// GELU(u) = u * Phi(u) in the erf form, Phi(u) = 1/2 + erf(u / sqrt 2) / 2.  On |u| <= 4
-// Phi(u) - 1/2 = u P(u^2) with an eight-coefficient minimax polynomial (absolute error
-// of Phi below 5.5e-5 over the reals once u is clamped to [-4, 4], far below the FP16
-// rounding of the result); eleven full-rate FP32 operations per element.
-__device__ __forceinline__ float gelu_erf(float u) {
-  const float uc = fminf(fmaxf(u, -4.0f), 4.0f);
-  const float t = uc * uc;
-  float p = fmaf(t, -1.580786058e-09f, 1.217110963e-07f);
-  p = fmaf(t, p, -4.100866136e-06f);
-  p = fmaf(t, p, 8.066739247e-05f);
-  p = fmaf(t, p, -1.048204373e-03f);
-  p = fmaf(t, p, 9.664873593e-03f);
-  p = fmaf(t, p, -6.617537886e-02f);
-  p = fmaf(t, p, 3.988475204e-01f);
-  return u * fmaf(uc, p, 0.5f);
-}
 
 // One 1-KiB direct-to-LDS load: lane l's 16 bytes land at lds_byte + 16 l.
 __device__ __forceinline__ void dma16(const void* g, unsigned lds_byte) {
@@ -261,15 +240,6 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   epi.template run<TL>(ctx, acc);
 }
 
-__device__ __forceinline__ half4 to_half4(const float16v& a, int qd) {
-  half4 o;
-  o[0] = (half_t)a[4 * qd + 0];
-  o[1] = (half_t)a[4 * qd + 1];
-  o[2] = (half_t)a[4 * qd + 2];
-  o[3] = (half_t)a[4 * qd + 3];
-  return o;
-}
-
 // ---------------------------------------------------------------- epilogue: plain store
 // out[p][n] = acc (f16), rows p in cluster-sorted order.
 struct EpiStore {
@@ -354,33 +324,13 @@ struct EpiFusedUp {
   half_t* A;          // [T][d_ff]
   float* spart;       // [n_tiles][T][k][r]
   int T, k, K, KRp, d_ff;
-
-  static constexpr int EPB = 32 / R;  // experts per 32 rank rows
-  static constexpr int NF = (R == 32) ? 2 : 1;
+  using FU = FusedUp<R, KMAX>;
 
   template <class TL>
   static constexpr int smem_bytes() {
     return (STAGE && 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8)) > TL::SMEM_BYTES)
                ? 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8))
                : TL::SMEM_BYTES;
-  }
-
-  __device__ static __forceinline__ bool chunk_has(int e, int kc) {
-    return R == 32 ? (e == (kc >> 1)) : R == 16 ? (e == kc) : R == 8 ? ((e >> 1) == kc) : ((e >> 2) == kc);
-  }
-  // B operand of chunk kc for a lane whose token selected expert e with t1 fragments f
-  __device__ static __forceinline__ half8 t1_frag(int e, int kc, int h, const half8 (&f)[NF]) {
-    const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (R == 32) return (e == (kc >> 1)) ? ((kc & 1) ? f[NF - 1] : f[0]) : z;
-    if (R == 16) return (e == kc) ? f[0] : z;
-    if (R == 8) return (e == 2 * kc + h) ? f[0] : z;
-    half8 o = z;  // R == 4: slots 0..3 are expert 4kc+2h, slots 4..7 expert 4kc+2h+1
-    if (e == 4 * kc + 2 * h) {
-      o[0] = f[0][0]; o[1] = f[0][1]; o[2] = f[0][2]; o[3] = f[0][3];
-    } else if (e == 4 * kc + 2 * h + 1) {
-      o[4] = f[0][0]; o[5] = f[0][1]; o[6] = f[0][2]; o[7] = f[0][3];
-    }
-    return o;
   }
 
   template <class TL>
@@ -395,41 +345,10 @@ struct EpiFusedUp {
     half_t* sV = t.smem + TL::BN * ldu;  // [KRp][BN + 8]
 
     // per-lane token state of every 32-column block this wavefront owns
-    int e[TL::MB][KMAX];
-    float gj[TL::MB][KMAX];
-    half8 f[TL::MB][KMAX][NF];
-    int pp[TL::MB];
-    bool valid[TL::MB];
+    typename FU::Tok tk[TL::MB];
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      pp[b] = t.m0 + t.wm * TL::WM + b * 32 + ml;
-      valid[b] = pp[b] < t.m_end;
-      const int pc = valid[b] ? pp[b] : t.m_end - 1;
-      const int tok = perm[pc];
-#pragma unroll
-      for (int j = 0; j < KMAX; ++j) {
-        e[b][j] = 0;
-        gj[b][j] = 0.f;
-#pragma unroll
-        for (int i = 0; i < NF; ++i) f[b][j][i] = half8{0, 0, 0, 0, 0, 0, 0, 0};
-        if (j < k) {
-          e[b][j] = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
-          gj[b][j] = valid[b] ? gate[(size_t)tok * k + j] : 0.f;
-          const half_t* tr = t1 + ((size_t)pc * k + j) * R;
-          if (R == 32) {
-            f[b][j][0] = *(const half8*)(tr + 8 * h);
-            f[b][j][NF - 1] = *(const half8*)(tr + 16 + 8 * h);
-          } else if (R == 16) {
-            f[b][j][0] = *(const half8*)(tr + 8 * h);
-          } else if (R == 8) {
-            f[b][j][0] = *(const half8*)(tr);
-          } else {
-            half4 q4 = *(const half4*)(tr);
-            f[b][j][0][0] = q4[0]; f[b][j][0][1] = q4[1]; f[b][j][0][2] = q4[2]; f[b][j][0][3] = q4[3];
-          }
-        }
-      }
-    }
+    for (int b = 0; b < TL::MB; ++b)
+      FU::load_tok(tk[b], t.m0 + t.wm * TL::WM + b * 32 + ml, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
 
     if (STAGE) {
       __syncthreads();  // every wavefront has left the main loop: the stage buffers are free
@@ -483,76 +402,51 @@ struct EpiFusedUp {
         const int nb = t.n0 + a * 32;
         if (nb >= d_ff) continue;
         float16v o;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[v] = 0.f;
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) {
-          if (j >= k) continue;
-          const int ej = e[b][j];
-          float16v hj = acc[a][b];
-          for (int kc = 0; kc < n_chunks; ++kc) {
-            if (__ballot(valid[b] && chunk_has(ej, kc)) == 0ull) continue;
-            half8 fa = STAGE ? *(const half8*)(sU + (a * 32 + ml) * ldu + kc * 16 + 8 * h)
-                             : *(const half8*)(u1c + (size_t)(nb + ml) * KRp + kc * 16 + 8 * h);
-            hj = mfma16(fa, t1_frag(ej, kc, h, f[b][j]), hj);
-          }
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            hj[v] = gelu_erf(hj[v]);
-            o[v] = fmaf(gj[b][j], hj[v], o[v]);
-          }
-          for (int q = 0; q < n_pass; ++q) {
-            const bool on = valid[b] && (ej / EPB == q);
-            if (__ballot(on) == 0ull) continue;
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-              half8 fb;
-#pragma unroll
-              for (int i = 0; i < 8; ++i) fb[i] = on ? (half_t)hj[8 * s + i] : (half_t)0.f;
-              half8 fa = STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + a * 32 + 16 * s + 8 * h)
-                               : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s + 8 * h);
-              sacc[j] = mfma16(fa, fb, sacc[j]);
-            }
-          }
-        }
-        if (valid[b]) {
+        auto uf = [&](int kc) {
+          return STAGE ? *(const half8*)(sU + (a * 32 + ml) * ldu + kc * 16 + 8 * h)
+                       : *(const half8*)(u1c + (size_t)(nb + ml) * KRp + kc * 16 + 8 * h);
+        };
+        auto vf = [&](int q, int s2) {
+          return STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + a * 32 + 16 * s2 + 8 * h)
+                       : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s2 + 8 * h);
+        };
+        FU::block(acc[a][b], tk[b], k, n_chunks, n_pass, h, uf, vf, o, sacc);
+        if (tk[b].valid) {
 #pragma unroll
           for (int qd = 0; qd < 4; ++qd)
-            *(half4*)(A + (size_t)pp[b] * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
+            *(half4*)(A + (size_t)tk[b].p * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
         }
       }
-      // partial s of this column tile: the lane holds rows 8*qd + 4h + (0..3) of the pass
-      // accumulator; those inside [b_e*R, b_e*R + R) are the token's s_j
-      if (valid[b]) {
-#pragma unroll
-        for (int j = 0; j < KMAX; ++j) {
-          if (j >= k) continue;
-          const int be = (e[b][j] % EPB) * R;
-          float* dst = spart + (((size_t)t.n_tile * T + pp[b]) * k + j) * R;
-#pragma unroll
-          for (int qd = 0; qd < 4; ++qd) {
-            int row0 = 8 * qd + 4 * h;
-            if (row0 >= be && row0 < be + R) {
-              float4v v4 = {sacc[j][4 * qd], sacc[j][4 * qd + 1], sacc[j][4 * qd + 2], sacc[j][4 * qd + 3]};
-              *(float4v*)(dst + row0 - be) = v4;
-            }
-          }
-        }
-      }
+      FU::store_s(tk[b], sacc, spart + (size_t)t.n_tile * T * k * R, k, h);
     }
   }
 };
 
 // ---------------------------------------------------------------- s partial reduction
-__global__ __launch_bounds__(256) void sreduce_kernel(const float* __restrict__ spart, const int* __restrict__ perm,
-                                                      int T, int kr, int n_tiles, float* __restrict__ s_down) {
-  size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (size_t)T * kr) return;
-  size_t p = idx / kr;
-  int w = (int)(idx % kr);
+// s_down[perm[p]][w] = sum over row tiles of spart[tile][p][w], in a fixed order: a block
+// owns 64 consecutive outputs, its NW wavefronts each sum every NW-th tile, and the NW
+// sums are added in wavefront order.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void sreduce_kernel(const float* __restrict__ spart,
+                                                          const int* __restrict__ perm, int T, int kr, int n_tiles,
+                                                          float* __restrict__ s_down) {
+  __shared__ float part[NW][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t total = (size_t)T * kr;
+  const size_t idx = (size_t)blockIdx.x * 64 + lane;
   float sum = 0.f;
-  for (int nt = 0; nt < n_tiles; ++nt) sum += spart[((size_t)nt * T + p) * kr + w];
-  s_down[(size_t)perm[p] * kr + w] = sum;
+  if (idx < total) {
+#pragma unroll 8
+    for (int nt = wave; nt < n_tiles; nt += NW) sum += spart[(size_t)nt * total + idx];
+  }
+  part[wave][lane] = sum;
+  __syncthreads();
+  if (wave == 0 && idx < total) {
+    float s2 = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s2 += part[w][lane];
+    s_down[(size_t)perm[idx / kr] * kr + idx % kr] = s2;
+  }
 }
 
 // ---------------------------------------------------------------- combine
@@ -707,12 +601,16 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   }
 }
 
-hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, float* s_down,
-                          hipStream_t st) {
+hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
+                          float* s_down, hipStream_t st) {
   int kr = dm.k * dm.r;
   size_t n = (size_t)T * kr;
-  hipLaunchKernelGGL(sreduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, spart, perm, T, kr,
-                     (dm.d_ff + G1_BN - 1) / G1_BN, s_down);
+  if (n_parts > 128)
+    hipLaunchKernelGGL(sreduce_kernel<16>, dim3((unsigned)((n + 63) / 64)), dim3(1024), 0, st, spart, perm, T, kr,
+                       n_parts, s_down);
+  else
+    hipLaunchKernelGGL(sreduce_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, spart, perm, T, kr,
+                       n_parts, s_down);
   return hipGetLastError();
 }
 

@@ -179,6 +179,134 @@ __global__ __launch_bounds__(PERMUTE_BLOCK) void permute_rank_kernel(const int* 
   }
 }
 
+// Few tokens: one workgroup (four wavefronts) per token, the logits of a stage spread over
+// the wavefronts so that their dot products run side by side instead of one after another.
+template <int MAXC>
+__global__ __launch_bounds__(256) void route_small_kernel(
+    const half_t* __restrict__ x, const half_t* __restrict__ rc, const half_t* __restrict__ re,
+    const float* __restrict__ bias, int T, int d, int G, int K, int k, int* __restrict__ cluster_id,
+    int* __restrict__ expert_idx, float* __restrict__ gate) {
+  __shared__ float zs[64];
+  __shared__ float ls[64];
+  __shared__ int cs;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x;
+  const int nchunk = d >> 3;
+  half8 xv[MAXC];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    int ch = lane + 64 * i;
+    xv[i] = (ch < nchunk) ? *(const half8*)(x + (size_t)t * d + ch * 8) : half8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  auto dot = [&](const half_t* v) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      int ch = lane + 64 * i;
+      if (ch < nchunk) acc = dot8(xv[i], *(const half8*)(v + ch * 8), acc);
+    }
+    return wave_sum(acc);
+  };
+  for (int g = wave; g < G; g += 4) {
+    float z = dot(rc + (size_t)g * d);
+    if (bias != nullptr) z += bias[g];
+    if (lane == 0) zs[g] = z;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float best = -INFINITY;
+    int c = 0;
+    for (int g = 0; g < G; ++g)
+      if (zs[g] > best) {
+        best = zs[g];
+        c = g;
+      }
+    cs = c;
+  }
+  __syncthreads();
+  const int c = cs;
+  for (int j = wave; j < K; j += 4) {
+    float l = dot(re + (size_t)(c * K + j) * d);
+    if (lane == 0) ls[j] = l;
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  float mine = (lane < K) ? ls[lane] : -INFINITY;
+  float sel_l[8];
+  int sel_j[8];
+  float lmax = 0.f;
+#pragma unroll
+  for (int a = 0; a < 8; ++a) {
+    sel_l[a] = 0.f;
+    sel_j[a] = 0;
+    if (a < k) {
+      float m = mine;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+      unsigned long long who = __ballot(mine == m);
+      int j = __ffsll((long long)who) - 1;
+      sel_l[a] = m;
+      sel_j[a] = j;
+      if (a == 0) lmax = m;
+      if (lane == j) mine = -INFINITY;
+    }
+  }
+  if (lane == 0) {
+    cluster_id[t] = c;
+    float den = 0.f;
+    float ex[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+      ex[a] = (a < k) ? expf(sel_l[a] - lmax) : 0.f;
+      den += ex[a];
+    }
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+      if (a < k) {
+        expert_idx[(size_t)t * k + a] = c * K + sel_j[a];
+        gate[(size_t)t * k + a] = ex[a] / den;
+      }
+    }
+  }
+}
+
+// T <= 1024: histogram, scan and stable ranks in one workgroup.
+__global__ __launch_bounds__(PERMUTE_BLOCK) void permute_small_kernel(const int* __restrict__ cluster_id, int T, int G,
+                                                                      int* __restrict__ perm,
+                                                                      int* __restrict__ inv_perm,
+                                                                      int* __restrict__ offsets) {
+  constexpr int NW = PERMUTE_BLOCK / 64;
+  __shared__ int wcount[NW][64];
+  __shared__ int base[64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = threadIdx.x;
+  const int c = (t < T) ? min(max(cluster_id[t], 0), G - 1) : -1;
+  int my_rank = 0;
+  for (int g = 0; g < G; ++g) {
+    unsigned long long m = __ballot(c == g);
+    if (lane == 0) wcount[wave][g] = __popcll(m);
+    if (c == g) my_rank = __popcll(m & ((1ull << lane) - 1ull));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int g = 0; g < G; ++g) {
+      offsets[g] = run;
+      base[g] = run;
+      for (int w = 0; w < NW; ++w) run += wcount[w][g];
+    }
+    offsets[G] = run;
+  }
+  __syncthreads();
+  if (t < T) {
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wcount[w][c];
+    int pos = base[c] + before + my_rank;
+    perm[pos] = t;
+    inv_perm[t] = pos;
+  }
+}
+
 __global__ void zero_offsets_kernel(int G, int* offsets) {
   if ((int)threadIdx.x <= G) offsets[threadIdx.x] = 0;
 }
@@ -191,6 +319,22 @@ hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   const half_t* rc = (const half_t*)w.router_cluster;
   const half_t* re = (const half_t*)w.router_expert;
   int chunks_per_lane = (dm.d / 8 + 63) / 64;
+  if (T <= SKINNY_T) {
+    dim3 g1(T), b1(256);
+    if (chunks_per_lane <= 2)
+      hipLaunchKernelGGL(route_small_kernel<2>, g1, b1, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                         cluster_id, expert_idx, gate);
+    else if (chunks_per_lane <= 4)
+      hipLaunchKernelGGL(route_small_kernel<4>, g1, b1, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                         cluster_id, expert_idx, gate);
+    else if (chunks_per_lane <= 8)
+      hipLaunchKernelGGL(route_small_kernel<8>, g1, b1, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
+                         cluster_id, expert_idx, gate);
+    else
+      hipLaunchKernelGGL(route_small_kernel<16>, g1, b1, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K,
+                         dm.k, cluster_id, expert_idx, gate);
+    return hipGetLastError();
+  }
   if (chunks_per_lane <= 2)
     hipLaunchKernelGGL(route_kernel<2>, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
                        cluster_id, expert_idx, gate);
@@ -210,6 +354,11 @@ hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int
                           int* blk_counts, hipStream_t st) {
   if (T == 0) {
     hipLaunchKernelGGL(zero_offsets_kernel, dim3(1), dim3(128), 0, st, dm.G, offsets);
+    return hipGetLastError();
+  }
+  if (T <= PERMUTE_BLOCK) {
+    hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G, perm,
+                       inv_perm, offsets);
     return hipGetLastError();
   }
   int n_blocks = (T + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
