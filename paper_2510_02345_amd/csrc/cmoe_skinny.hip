@@ -23,33 +23,89 @@ constexpr int SK_ROWS = 64;   // weight rows per workgroup
 constexpr int SK_RB = 2;      // 32-row blocks per workgroup
 constexpr int SK_WAVES = 4;   // wavefronts splitting the contraction
 
-// acc[rb] += sum_k W[row(rb)][k] X[col][k] over 64-element steps [it0, it1).
-// pa[rb] / pb already point at the lane's row / column and 8-element slot (8 * (lane / 32)).
-__device__ __forceinline__ void skinny_stream(const half_t* const (&pa)[SK_RB], const half_t* pb, int it0, int it1,
-                                              float16v (&acc)[SK_RB]) {
-  half8 a0[SK_RB][4], b0[4], a1[SK_RB][4], b1[4];
-  auto load = [&](int it, half8(&a)[SK_RB][4], half8(&b)[4]) {
-    const size_t off = (size_t)it * 64;
+// One 1-KiB direct-to-LDS load: lane l's 16 bytes land at lds_byte + 16 l.
+__device__ __forceinline__ void dma16(const void* g, unsigned lds_byte) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+constexpr int SK_COLS = 16;                         // tokens per pass over a cluster
+constexpr int SK_A_BYTES = SK_ROWS * 128;           // 64 weight rows x 64 elements
+constexpr int SK_B_BYTES = SK_COLS * 128;           // 16 token rows x 64 elements
+constexpr int SK_STAGE = SK_A_BYTES + SK_B_BYTES;   // one wavefront stage
+constexpr int SK_RING = 2 * SK_STAGE;               // two stages per wavefront
+constexpr int SK_DMA = (SK_ROWS + SK_COLS) / 8;     // 1-KiB loads per stage (8 rows x 128 B each)
+
+// acc[rb] += sum_k W[row(rb)][k] X[col][k] over the 64-element steps [it0, it1) of this
+// wavefront.  Both operands stream global -> LDS one step ahead of the matrix-core work,
+// as whole 128-byte lines per row, into a two-stage ring private to the wavefront (so no
+// barrier is needed, only vmcnt), chunks XOR-swizzled with (row >> 1) & 7.
+//   wrow / brow: the lane's row (lane / 8) of the first 8-row group of the weight / token
+//                tile at step 0, WITHOUT the chunk offset (the swizzle depends on the row);
+//                w_stride / b_stride: elements between 8-row groups (token rows beyond the
+//                pass are clamped by the caller through brow1)
+// Accumulator columns 16..31 repeat columns 0..15.
+__device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_stride, const half_t* brow0,
+                                              const half_t* brow1, char* ring, unsigned ring_lds, int lane, int it0,
+                                              int it1, float16v (&acc)[SK_RB]) {
+  if (it0 >= it1) return;
+  const int fr = lane & 31, h = lane >> 5;
+  int offa[SK_RB][4], offb[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+#pragma unroll
+    for (int rb = 0; rb < SK_RB; ++rb) {
+      const int row = rb * 32 + fr;
+      offa[rb][s] = row * 128 + (((2 * s + h) ^ ((row >> 1) & 7)) << 4);
+    }
+    const int brow = fr & (SK_COLS - 1);
+    offb[s] = SK_A_BYTES + brow * 128 + (((2 * s + h) ^ ((brow >> 1) & 7)) << 4);
+  }
+  // lane l of load i fills row 8i + l/8, chunk position l%8, with source chunk position ^ swizzle(row)
+  const int lrow = lane >> 3, lpos = lane & 7;
+  const int c0 = (lpos ^ (lrow >> 1)) << 3, c1 = (lpos ^ (lrow >> 1) ^ 4) << 3;  // even / odd groups
+  auto issue = [&](int it, int stage) {
+    const unsigned dst = ring_lds + stage * SK_STAGE;
+#pragma unroll
+    for (int i = 0; i < SK_ROWS / 8; ++i)
+      dma16(wrow + ((i & 1) ? c1 : c0) + (size_t)i * w_stride + (size_t)it * 64, dst + i * 1024);
+    dma16(brow0 + c0 + (size_t)it * 64, dst + SK_A_BYTES);
+    dma16(brow1 + c1 + (size_t)it * 64, dst + SK_A_BYTES + 1024);
+  };
+  auto compute = [&](int stage) {
+    const char* sb = ring + stage * SK_STAGE;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
+      half8 fa[SK_RB];
 #pragma unroll
-      for (int rb = 0; rb < SK_RB; ++rb) a[rb][s] = *(const half8*)(pa[rb] + off + s * 16);
-      b[s] = *(const half8*)(pb + off + s * 16);
+      for (int rb = 0; rb < SK_RB; ++rb) fa[rb] = *(const half8*)(sb + offa[rb][s]);
+      const half8 fb = *(const half8*)(sb + offb[s]);
+#pragma unroll
+      for (int rb = 0; rb < SK_RB; ++rb) acc[rb] = mfma16(fa[rb], fb, acc[rb]);
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the stage has been read: it may be refilled
   };
-  auto compute = [&](half8(&a)[SK_RB][4], half8(&b)[4]) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int rb = 0; rb < SK_RB; ++rb) acc[rb] = mfma16(a[rb][s], b[s], acc[rb]);
-  };
-  if (it0 >= it1) return;
-  load(it0, a0, b0);
+  issue(it0, 0);
   for (int it = it0; it < it1; it += 2) {
-    if (it + 1 < it1) load(it + 1, a1, b1);
-    compute(a0, b0);
-    if (it + 2 < it1) load(it + 2, a0, b0);
-    if (it + 1 < it1) compute(a1, b1);
+    if (it + 1 < it1) {
+      issue(it + 1, 1);
+      wait_vm<SK_DMA>();
+    } else {
+      wait_vm<0>();
+    }
+    compute(0);
+    if (it + 1 < it1) {
+      if (it + 2 < it1) {
+        issue(it + 2, 0);
+        wait_vm<SK_DMA>();
+      } else {
+        wait_vm<0>();
+      }
+      compute(1);
+    }
   }
 }
 
@@ -76,14 +132,15 @@ __device__ __forceinline__ void skinny_reduce(float* red, int wave, int lane, co
 struct SkinnyTile {
   int c, n0, m0, m_end;
 };
-// grid: x = row block, y = cluster, z = pass over the cluster's tokens (32 per pass)
+// grid: x = row block, y = cluster, z = pass over the cluster's tokens (SK_COLS per pass);
+// m_end is the end of the pass
 __device__ __forceinline__ bool skinny_tile(const int* offsets, SkinnyTile& t) {
   t.c = blockIdx.y;
   t.n0 = blockIdx.x * SK_ROWS;
-  const int lo = offsets[t.c];
-  t.m_end = offsets[t.c + 1];
-  t.m0 = lo + blockIdx.z * 32;
-  return t.m0 < t.m_end;
+  const int lo = offsets[t.c], hi = offsets[t.c + 1];
+  t.m0 = lo + blockIdx.z * SK_COLS;
+  t.m_end = min(hi, t.m0 + SK_COLS);
+  return t.m0 < hi;
 }
 
 // ---------------------------------------------------------------- t1 = V1_e x
@@ -134,7 +191,9 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
   constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
   constexpr int SU_BYTES = SK_ROWS * LDU * 2;
   constexpr int R0_BYTES = RED_BYTES > SU_BYTES ? RED_BYTES : SU_BYTES;
-  __shared__ __attribute__((aligned(16))) char smem[R0_BYTES + KRPMAX * LDV * 2];
+  constexpr int EPI_BYTES = R0_BYTES + KRPMAX * LDV * 2;
+  constexpr int RINGS = SK_WAVES * SK_RING;
+  __shared__ __attribute__((aligned(1024))) char smem[EPI_BYTES > RINGS ? EPI_BYTES : RINGS];
   float* red = (float*)smem;
   half_t* sU = (half_t*)smem;               // [64][LDU]   U1 tile, transposed (after red is dead)
   half_t* sV = (half_t*)(smem + R0_BYTES);  // [KRp][LDV]  V2 tile, columns permuted in 16-groups
@@ -173,19 +232,21 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
   }
 
   // ---- stream W1_base(c) rows [n0, n0 + 64) once; this wavefront's share of d
-  const half_t* pa[SK_RB];
-#pragma unroll
-  for (int rb = 0; rb < SK_RB; ++rb)
-    pa[rb] = w1_base + ((size_t)t.c * d_ff + t.n0 + rb * 32 + fr) * d + 8 * h;
-  const int pcol = min(t.m0 + fr, t.m_end - 1);
-  const half_t* pb = x + (size_t)perm[pcol] * d + 8 * h;
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const int lrow = lane >> 3;
+  const half_t* wrow = w1_base + ((size_t)t.c * d_ff + t.n0 + lrow) * d;
+  const half_t* brow0 = x + (size_t)perm[min(t.m0 + lrow, t.m_end - 1)] * d;
+  const half_t* brow1 = x + (size_t)perm[min(t.m0 + 8 + lrow, t.m_end - 1)] * d;
   float16v acc[SK_RB];
 #pragma unroll
   for (int rb = 0; rb < SK_RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
   const int iters = d / 64;
-  skinny_stream(pa, pb, wave * iters / SK_WAVES, (wave + 1) * iters / SK_WAVES, acc);
+  skinny_stream(wrow, (size_t)8 * d, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
+                wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
+  __syncthreads();  // every ring has been consumed: its space becomes red
 
   float16v hb;
   skinny_reduce(red, wave, lane, acc, hb);
@@ -233,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
   // ---- per-(token, expert) residual, GELU, gated sum, V2 product: one wavefront per block
   if (wave < SK_RB) {
     typename FU::Tok tk;
-    FU::load_tok(tk, t.m0 + fr, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
+    FU::load_tok(tk, fr < SK_COLS ? t.m0 + fr : t.m_end, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
     float16v sacc[KMAX];
 #pragma unroll
     for (int j = 0; j < KMAX; ++j)
@@ -257,26 +318,32 @@ __global__ __launch_bounds__(256, 2) void skinny_down_kernel(const half_t* __res
                                                              const half_t* __restrict__ w2_base,
                                                              const int* __restrict__ offsets, int d, int d_ff,
                                                              half_t* __restrict__ yb) {
-  __shared__ __attribute__((aligned(16))) float red[SK_WAVES * SK_RB * 16 * 64];
+  constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
+  constexpr int RINGS = SK_WAVES * SK_RING;
+  __shared__ __attribute__((aligned(1024))) char smem[RED_BYTES > RINGS ? RED_BYTES : RINGS];
+  float* red = (float*)smem;
   SkinnyTile t;
   if (!skinny_tile(offsets, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 31, h = lane >> 5;
-  const half_t* pa[SK_RB];
-#pragma unroll
-  for (int rb = 0; rb < SK_RB; ++rb)
-    pa[rb] = w2_base + ((size_t)t.c * d + t.n0 + rb * 32 + fr) * d_ff + 8 * h;
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const int lrow = lane >> 3;
+  const half_t* wrow = w2_base + ((size_t)t.c * d + t.n0 + lrow) * d_ff;
   const int p = t.m0 + fr;
-  const half_t* pb = A + (size_t)min(p, t.m_end - 1) * d_ff + 8 * h;
+  const half_t* brow0 = A + (size_t)min(t.m0 + lrow, t.m_end - 1) * d_ff;
+  const half_t* brow1 = A + (size_t)min(t.m0 + 8 + lrow, t.m_end - 1) * d_ff;
   float16v acc[SK_RB];
 #pragma unroll
   for (int rb = 0; rb < SK_RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
   const int iters = d_ff / 64;
-  skinny_stream(pa, pb, wave * iters / SK_WAVES, (wave + 1) * iters / SK_WAVES, acc);
+  skinny_stream(wrow, (size_t)8 * d_ff, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
+                wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
+  __syncthreads();  // every ring has been consumed: its space becomes red
   float16v hb;
   skinny_reduce(red, wave, lane, acc, hb);
-  if (wave < SK_RB && p < t.m_end) {
+  if (wave < SK_RB && fr < SK_COLS && p < t.m_end) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd)
       *(half4*)(yb + (size_t)p * d + t.n0 + wave * 32 + 8 * qd + 4 * h) = to_half4(hb, qd);
@@ -332,7 +399,7 @@ template <int R, int KMAX>
 hipError_t launch_up_rk(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
                         float* spart, hipStream_t st) {
-  dim3 grid(dm.d_ff / SK_ROWS, dm.G, (T + 31) / 32), block(256);
+  dim3 grid(dm.d_ff / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
   if (dm.KRp <= 256)
     hipLaunchKernelGGL((skinny_up_kernel<R, KMAX, 256>), grid, block, 0, st, x, (const half_t*)w.w1_base, w.u1_q,
                        (const half_t*)w.u1_s, w.v2_q, (const half_t*)w.v2_s, t1, perm, offsets, expert_idx, gate, T,
@@ -376,7 +443,7 @@ hipError_t launch_skinny_up(const cmoe_dims& dm, const cmoe_weights& w, const ha
 
 hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                               half_t* y_base_sorted, hipStream_t st) {
-  dim3 grid(dm.d / SK_ROWS, dm.G, (T + 31) / 32), block(256);
+  dim3 grid(dm.d / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
   hipLaunchKernelGGL(skinny_down_kernel, grid, block, 0, st, a, (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff,
                      y_base_sorted);
   return hipGetLastError();
