@@ -19,8 +19,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-constexpr int SK_ROWS = 64;   // weight rows per workgroup
-constexpr int SK_RB = 2;      // 32-row blocks per workgroup
+constexpr int SK_ROWS = 32;   // weight rows per workgroup
+constexpr int SK_RB = SK_ROWS / 32;  // 32-row blocks per workgroup
+constexpr int SK_NCH = SK_ROWS / 8;  // 8-row chunks per workgroup
+constexpr int SK_OCC = 3;     // workgroups per CU the LDS budget is sized for
 constexpr int SK_WAVES = 4;   // wavefronts splitting the contraction
 
 // One 1-KiB direct-to-LDS load: lane l's 16 bytes land at lds_byte + 16 l.
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(1024) void skinny_t1_kernel(const half_t* __restric
 
 // ---------------------------------------------------------------- fused up-projection
 template <int R, int KMAX, int KRPMAX>
-__global__ __launch_bounds__(256, 2) void skinny_up_kernel(
+__global__ __launch_bounds__(256, SK_OCC) void skinny_up_kernel(
     const half_t* __restrict__ x, const half_t* __restrict__ w1_base, const uint8_t* __restrict__ u1_q,
     const half_t* __restrict__ u1_s, const uint8_t* __restrict__ v2_q, const half_t* __restrict__ v2_s,
     const half_t* __restrict__ t1, const int* __restrict__ perm, const int* __restrict__ offsets,
@@ -202,8 +204,12 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
   if (!skinny_tile(offsets, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 31, h = lane >> 5;
 
+  // ---- per-lane token state of the epilogue, requested before the weight stream starts
+  typename FU::Tok tk;
+  FU::load_tok(tk, fr < SK_COLS ? t.m0 + fr : t.m_end, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
+
   // ---- request this thread's share of the cluster's INT4 factor tiles (zero beyond K*r)
-  constexpr int FTASKS = KRPMAX * 8 / 256;
+  constexpr int FTASKS = KRPMAX * SK_NCH / 256;
   unsigned u_bytes[FTASKS];
   half_t u_sc[FTASKS];
   unsigned short v_bytes[FTASKS][2];
@@ -211,12 +217,12 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
 #pragma unroll
   for (int i2 = 0; i2 < FTASKS; ++i2) {
     const int task = tid + i2 * 256;
-    const int n8 = task & 7, kk = task >> 3;
+    const int n8 = task % SK_NCH, kk = task / SK_NCH;
     u_bytes[i2] = 0;
     u_sc[i2] = (half_t)0.f;
     v_bytes[i2][0] = v_bytes[i2][1] = 0;
     v_sc[i2][0] = v_sc[i2][1] = (half_t)0.f;
-    if (task < KRp * 8 && kk < K * R) {
+    if (task < KRp * SK_NCH && kk < K * R) {
       const size_t row = (size_t)t.c * K * R + kk;
       const int n = t.n0 + n8 * 8;
       u_bytes[i2] = *(const unsigned*)(u1_q + row * (d_ff / 2) + n / 2);
@@ -258,8 +264,8 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
 #pragma unroll
   for (int i2 = 0; i2 < FTASKS; ++i2) {   // U1: 8 consecutive n of one rank row, transposed
     const int task = tid + i2 * 256;
-    if (task < KRp * 8) {
-      const int n8 = task & 7, kk = task >> 3;
+    if (task < KRp * SK_NCH) {
+      const int n8 = task % SK_NCH, kk = task / SK_NCH;
       const float sc = (float)u_sc[i2];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -272,8 +278,8 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
 #pragma unroll
   for (int i2 = 0; i2 < FTASKS; ++i2) {   // V2: 8 output positions of one rank row
     const int task = tid + i2 * 256;
-    if (task < KRp * 8) {
-      const int c8 = task & 7, kk = task >> 3;
+    if (task < KRp * SK_NCH) {
+      const int c8 = task % SK_NCH, kk = task / SK_NCH;
       half8 o;
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
@@ -293,8 +299,6 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
 
   // ---- per-(token, expert) residual, GELU, gated sum, V2 product: one wavefront per block
   if (wave < SK_RB) {
-    typename FU::Tok tk;
-    FU::load_tok(tk, fr < SK_COLS ? t.m0 + fr : t.m_end, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
     float16v sacc[KMAX];
 #pragma unroll
     for (int j = 0; j < KMAX; ++j)
@@ -314,7 +318,7 @@ __global__ __launch_bounds__(256, 2) void skinny_up_kernel(
 }
 
 // ---------------------------------------------------------------- down-projection
-__global__ __launch_bounds__(256, 2) void skinny_down_kernel(const half_t* __restrict__ A,
+__global__ __launch_bounds__(256, SK_OCC) void skinny_down_kernel(const half_t* __restrict__ A,
                                                              const half_t* __restrict__ w2_base,
                                                              const int* __restrict__ offsets, int d, int d_ff,
                                                              half_t* __restrict__ yb) {
