@@ -179,10 +179,11 @@ __global__ __launch_bounds__(PERMUTE_BLOCK) void permute_rank_kernel(const int* 
   }
 }
 
-// Few tokens: one workgroup (four wavefronts) per token, the logits of a stage spread over
+// Few tokens: one workgroup (eight wavefronts) per token, the logits of a stage spread over
 // the wavefronts so that their dot products run side by side instead of one after another.
+constexpr int RS_WAVES = 8;
 template <int MAXC>
-__global__ __launch_bounds__(256) void route_small_kernel(
+__global__ __launch_bounds__(RS_WAVES * 64) void route_small_kernel(
     const half_t* __restrict__ x, const half_t* __restrict__ rc, const half_t* __restrict__ re,
     const float* __restrict__ bias, int T, int d, int G, int K, int k, int* __restrict__ cluster_id,
     int* __restrict__ expert_idx, float* __restrict__ gate) {
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(256) void route_small_kernel(
     }
     return wave_sum(acc);
   };
-  for (int g = wave; g < G; g += 4) {
+  for (int g = wave; g < G; g += RS_WAVES) {
     float z = dot(rc + (size_t)g * d);
     if (bias != nullptr) z += bias[g];
     if (lane == 0) zs[g] = z;
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(256) void route_small_kernel(
   }
   __syncthreads();
   const int c = cs;
-  for (int j = wave; j < K; j += 4) {
+  for (int j = wave; j < K; j += RS_WAVES) {
     float l = dot(re + (size_t)(c * K + j) * d);
     if (lane == 0) ls[j] = l;
   }
@@ -320,7 +321,7 @@ hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   const half_t* re = (const half_t*)w.router_expert;
   int chunks_per_lane = (dm.d / 8 + 63) / 64;
   if (T <= SKINNY_T) {
-    dim3 g1(T), b1(256);
+    dim3 g1(T), b1(RS_WAVES * 64);
     if (chunks_per_lane <= 2)
       hipLaunchKernelGGL(route_small_kernel<2>, g1, b1, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k,
                          cluster_id, expert_idx, gate);

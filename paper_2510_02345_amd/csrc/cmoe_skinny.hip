@@ -162,18 +162,29 @@ __global__ __launch_bounds__(1024) void skinny_t1_kernel(const half_t* __restric
     const uint8_t* qr = v1_q + row * (d / 2);
     const half_t* sr = v1_s + row * (d / q);
     float acc = 0.f;
-    for (int ch = lane; ch < d / 8; ch += 64) {   // 8 elements: 4 code bytes, one scale
-      const unsigned bytes = *(const unsigned*)(qr + ch * 4);
-      const half8 xv = *(const half8*)(xr + ch * 8);
-      const float sc = (float)sr[(ch * 8) / q];
-      float part = 0.f;
+    for (int ch0 = lane; ch0 < d / 8; ch0 += 256) {   // 8 elements per chunk: 4 code bytes, one scale
+      unsigned bytes[4];
+      half8 xv[4];
+      float sc[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const unsigned b = (bytes >> (8 * i)) & 0xffu;
-        part = fmaf(nib_lo(b), (float)xv[2 * i], part);
-        part = fmaf(nib_hi(b), (float)xv[2 * i + 1], part);
+      for (int u = 0; u < 4; ++u) {
+        const int ch = ch0 + 64 * u;
+        const bool in = ch < d / 8;
+        bytes[u] = in ? *(const unsigned*)(qr + ch * 4) : 0u;
+        xv[u] = in ? *(const half8*)(xr + ch * 8) : half8{0, 0, 0, 0, 0, 0, 0, 0};
+        sc[u] = in ? (float)sr[(ch * 8) / q] : 0.f;
       }
-      acc = fmaf(sc, part, acc);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned b = (bytes[u] >> (8 * i)) & 0xffu;
+          part = fmaf(nib_lo(b), (float)xv[u][2 * i], part);
+          part = fmaf(nib_hi(b), (float)xv[u][2 * i + 1], part);
+        }
+        acc = fmaf(sc[u], part, acc);
+      }
     }
     acc = wave_sum(acc);
     if (lane == 0) t1[((size_t)p * k + j) * r + rho] = (half_t)acc;
@@ -371,32 +382,37 @@ __global__ __launch_bounds__(256) void skinny_combine_kernel(const half_t* __res
   if (tid < k * r) gs[tid] = gate[(size_t)t * k + tid / r] * s_down[(size_t)t * k * r + tid];
   if (tid < k) es[tid] = expert_idx[(size_t)t * k + tid];
   __syncthreads();
-  const half_t* ybr = yb + (size_t)inv_perm[t] * d;
-  for (int ch = tid; ch < d / 8; ch += 256) {
-    const half8 b8 = *(const half8*)(ybr + ch * 8);
-    float acc[8];
+  const int ch = blockIdx.y * 256 + tid;  // 8 output columns
+  if (ch >= d / 8) return;
+  const half8 b8 = *(const half8*)(yb + (size_t)inv_perm[t] * d + ch * 8);
+  float acc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = (float)b8[i];
-    for (int j = 0; j < k; ++j) {
-      const size_t row0 = (size_t)es[j] * r;
-#pragma unroll 4
-      for (int rho = 0; rho < r; ++rho) {
-        const size_t row = row0 + rho;
-        const unsigned bytes = *(const unsigned*)(u2_q + row * (d / 2) + ch * 4);
-        const float sc = (float)u2_s[row * (d / q) + (ch * 8) / q] * gs[j * r + rho];
+  for (int i = 0; i < 8; ++i) acc[i] = (float)b8[i];
+  for (int j = 0; j < k; ++j) {
+    const size_t row0 = (size_t)es[j] * r;
+    for (int rho0 = 0; rho0 < r; rho0 += 4) {   // r is a multiple of 4: four rows per batch of loads
+      unsigned bytes[4];
+      float sc[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t row = row0 + rho0 + u;
+        bytes[u] = *(const unsigned*)(u2_q + row * (d / 2) + ch * 4);
+        sc[u] = (float)u2_s[row * (d / q) + (ch * 8) / q] * gs[j * r + rho0 + u];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const unsigned b = (bytes >> (8 * i)) & 0xffu;
-          acc[2 * i] = fmaf(sc, nib_lo(b), acc[2 * i]);
-          acc[2 * i + 1] = fmaf(sc, nib_hi(b), acc[2 * i + 1]);
+          const unsigned b = (bytes[u] >> (8 * i)) & 0xffu;
+          acc[2 * i] = fmaf(sc[u], nib_lo(b), acc[2 * i]);
+          acc[2 * i + 1] = fmaf(sc[u], nib_hi(b), acc[2 * i + 1]);
         }
-      }
     }
-    half8 o;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = (half_t)acc[i];
-    *(half8*)(y + (size_t)t * d + ch * 8) = o;
   }
+  half8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (half_t)acc[i];
+  *(half8*)(y + (size_t)t * d + ch * 8) = o;
 }
 
 template <int R, int KMAX>
@@ -456,7 +472,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
 hipError_t launch_skinny_combine(const cmoe_dims& dm, const cmoe_weights& w, const half_t* y_base_sorted,
                                  const float* s_down, const int* inv_perm, const int* expert_idx, const float* gate,
                                  int T, half_t* y, hipStream_t st) {
-  hipLaunchKernelGGL(skinny_combine_kernel, dim3(T), dim3(256), 0, st, y_base_sorted, s_down, inv_perm, expert_idx,
+  hipLaunchKernelGGL(skinny_combine_kernel, dim3(T, (dm.d / 8 + 255) / 256), dim3(256), 0, st, y_base_sorted, s_down, inv_perm, expert_idx,
                      gate, w.u2_q, (const half_t*)w.u2_s, dm.d, dm.q, dm.r, dm.k, y);
   return hipGetLastError();
 }
