@@ -20,7 +20,8 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   size_t n_blocks = (Tz + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
   size_t n_tiles = (T <= SKINNY_T) ? ((size_t)dm.d_ff + SKINNY_SN - 1) / SKINNY_SN
                                    : ((size_t)dm.d_ff + G1_BN - 1) / G1_BN;
-  L.blk_counts = take(sizeof(int32_t) * (n_blocks + 1) * dm.G);
+  L.blk_counts = take(sizeof(int32_t) * (n_blocks + 1) * (dm.G > 64 ? dm.G : 64));
+  L.sort_i32 = take(sizeof(int32_t) * (8 * Tz + 256));
   L.v1cat = take(sizeof(half_t) * dm.G * dm.KRp * dm.d);
   L.u1t = take(sizeof(half_t) * dm.G * dm.d_ff * dm.KRp);
   L.v2p = take(sizeof(half_t) * dm.G * dm.KRp * dm.d_ff);
@@ -248,12 +249,25 @@ extern "C" int cmoe_ffn_forward(cmoe_handle* h, const cmoe_weights* w, const cmo
     CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
     return CMOE_OK;
   }
+  // inside each cluster, order the rows by their selected experts (when the slots fit the
+  // counting sort's 64 bins); all intermediates live in that refined order, the
+  // down-projection writes its rows back to the caller's cluster-sorted order
+  const int* rperm = perm;
+  const int* rowmap = nullptr;
+  if (dm.G * dm.K <= 64) {
+    int* si = (int*)(ws + L.sort_i32);
+    int* rm = si + 5 * (size_t)T + 128;
+    int* p2 = si + 6 * (size_t)T + 128;
+    CMOE_LAUNCH(TS_PERMUTE, launch_pair_sort(dm, perm, expert_idx, T, si, (int*)(ws + L.blk_counts), rm, p2, st));
+    rperm = p2;
+    rowmap = rm;
+  }
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, st));
-  CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, perm, offsets, expert_idx, v1cat, t1ext, st));
-  CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, gate, u1t, v2p, t1ext,
-                                     a, spart, st));
-  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
-  CMOE_LAUNCH(TS_GEMM2, launch_gemm2(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
+  CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
+  CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, rperm, offsets, expert_idx, gate, u1t, v2p,
+                                     t1ext, a, spart, st));
+  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
+  CMOE_LAUNCH(TS_GEMM2, launch_gemm2(dm, *w, a, T, offsets, rowmap, (half_t*)y_base_sorted, st));
   return CMOE_OK;
 }
 

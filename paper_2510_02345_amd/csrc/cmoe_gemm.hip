@@ -160,6 +160,12 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
     }
   }
 
+  // 32-column blocks of this wavefront that hold at least one real token (a ragged last
+  // row tile of a cluster skips the matrix-core work of the others)
+  bool bv[TL::MB];
+#pragma unroll
+  for (int b = 0; b < TL::MB; ++b) bv[b] = m0 + wm * TL::WM + b * 32 < m_end;
+
   const int KT = g.Kc / TL::BK;
 #pragma unroll
   for (int s = 0; s < TL::NS - 1; ++s)
@@ -179,11 +185,14 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
         for (int a = 0; a < TL::NB; ++a) fa[a] = *(const half8*)(sb + offa[a][ks]);
 #pragma unroll
-        for (int b = 0; b < TL::MB; ++b) fb[b] = *(const half8*)(sb + offb[b][ks]);
+        for (int b = 0; b < TL::MB; ++b)
+          if (bv[b]) fb[b] = *(const half8*)(sb + offb[b][ks]);
 #pragma unroll
-        for (int a = 0; a < TL::NB; ++a)
+        for (int b = 0; b < TL::MB; ++b)
+          if (bv[b]) {
 #pragma unroll
-          for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
+            for (int a = 0; a < TL::NB; ++a) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
+          }
       }
       stage = (stage + 1 == TL::NS) ? 0 : stage + 1;
       nstage = (nstage + 1 == TL::NS) ? 0 : nstage + 1;
@@ -205,7 +214,8 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
         for (int a = 0; a < TL::NB; ++a) fa[ks][a] = *(const half8*)(sb + offa[a][ks]);
 #pragma unroll
-        for (int b = 0; b < TL::MB; ++b) fb[ks][b] = *(const half8*)(sb + offb[b][ks]);
+        for (int b = 0; b < TL::MB; ++b)
+          if (bv[b]) fb[ks][b] = *(const half8*)(sb + offb[b][ks]);
       }
       // the stage refilled here held tile kt - 1, which both sets read before the
       // barrier that opened this interval
@@ -223,9 +233,11 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int a = 0; a < TL::NB; ++a)
+        for (int b = 0; b < TL::MB; ++b)
+          if (bv[b]) {
 #pragma unroll
-          for (int b = 0; b < TL::MB; ++b) acc[a][b] = mfma16(fa[ks][a], fb[ks][b], acc[a][b]);
+            for (int a = 0; a < TL::NB; ++a) acc[a][b] = mfma16(fa[ks][a], fb[ks][b], acc[a][b]);
+          }
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_barrier();
@@ -244,6 +256,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 // out[p][n] = acc (f16), rows p in cluster-sorted order.
 struct EpiStore {
   half_t* out;
+  const int* rowmap;  // row p of the tile order is written to out[rowmap[p]] (NULL: identity)
   int ldo, N;
   template <class TL>
   static constexpr int smem_bytes() { return TL::SMEM_BYTES; }
@@ -254,13 +267,14 @@ struct EpiStore {
     for (int b = 0; b < TL::MB; ++b) {
       int p = t.m0 + t.wm * TL::WM + b * 32 + (t.lane & 31);
       if (p >= t.m_end) continue;
+      const size_t orow = rowmap ? rowmap[p] : p;
 #pragma unroll
       for (int a = 0; a < TL::NB; ++a) {
         int nb = t.n0 + t.wn * TL::WN + a * 32;
         if (nb >= N) continue;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd)
-          *(half4*)(out + (size_t)p * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+          *(half4*)(out + orow * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
       }
     }
   }
@@ -335,7 +349,7 @@ struct EpiFusedUp {
 
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
-    static_assert(TL::WAVES_N == 1, "one wavefront spans the tile's rows n, so s needs no cross-wave sum");
+    static_assert(TL::WN == G1_BN, "one s partial per wavefront row range of G1_BN rows");
     const int h = t.lane >> 5, ml = t.lane & 31;
     const half_t* u1c = u1t + (size_t)t.c * d_ff * KRp;
     const half_t* v2c = v2p + (size_t)t.c * KRp * d_ff;
@@ -399,15 +413,16 @@ struct EpiFusedUp {
         for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
 #pragma unroll
       for (int a = 0; a < TL::NB; ++a) {
-        const int nb = t.n0 + a * 32;
+        const int nl = t.wn * TL::WN + a * 32;  // first row of the block inside the tile
+        const int nb = t.n0 + nl;
         if (nb >= d_ff) continue;
         float16v o;
         auto uf = [&](int kc) {
-          return STAGE ? *(const half8*)(sU + (a * 32 + ml) * ldu + kc * 16 + 8 * h)
+          return STAGE ? *(const half8*)(sU + (nl + ml) * ldu + kc * 16 + 8 * h)
                        : *(const half8*)(u1c + (size_t)(nb + ml) * KRp + kc * 16 + 8 * h);
         };
         auto vf = [&](int q, int s2) {
-          return STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + a * 32 + 16 * s2 + 8 * h)
+          return STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + nl + 16 * s2 + 8 * h)
                        : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s2 + 8 * h);
         };
         FU::block(acc[a][b], tk[b], k, n_chunks, n_pass, h, uf, vf, o, sacc);
@@ -417,7 +432,7 @@ struct EpiFusedUp {
             *(half4*)(A + (size_t)tk[b].p * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
         }
       }
-      FU::store_s(tk[b], sacc, spart + (size_t)t.n_tile * T * k * R, k, h);
+      FU::store_s(tk[b], sacc, spart + (size_t)(t.n_tile * TL::WAVES_N + t.wn) * T * k * R, k, h);
     }
   }
 };
@@ -533,7 +548,8 @@ using TileMain = Tile<128, 256, 1, 4, 3, 2, false, 8, 8>;
 // Plain down-projection: 256 x 256 per workgroup, eight wavefronts (2 x 4, each 128 x 64)
 // in ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
 using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
-static_assert(TileMain::BN == G1_BN, "workspace sizing assumes this column tile");
+using TileUp = TileBig;  // tile of the fused up-projection
+static_assert(TileUp::WN == G1_BN, "workspace sizing assumes one s partial per G1_BN rows");
 
 template <class TL, class Epi>
 hipError_t launch_gemm(const GemmArgs& g, int T, const Epi& epi, hipStream_t st) {
@@ -557,7 +573,7 @@ template <int R, int KMAX>
 hipError_t launch_gemm1_rk(const cmoe_dims& dm, const GemmArgs& g, int T, const int* perm, const int* expert_idx,
                            const float* gate, const half_t* u1t, const half_t* v2p, const half_t* t1, half_t* a,
                            float* spart, hipStream_t st) {
-  using TL = TileMain;
+  using TL = TileUp;
   if (dm.KRp <= 128) {
     EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
     return launch_gemm<TL>(g, T, epi, st);
@@ -590,7 +606,7 @@ hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* per
 hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
                         const half_t* v2p, const half_t* t1, half_t* a, float* spart, hipStream_t st) {
-  using TL = TileMain;
+  using TL = TileUp;
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0};
   switch (dm.r) {
@@ -615,11 +631,11 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
 }
 
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
-                        half_t* y_base_sorted, hipStream_t st) {
+                        const int* rowmap, half_t* y_base_sorted, hipStream_t st) {
   using TL = TileBig;
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0};
-  EpiStore epi{y_base_sorted, dm.d, dm.d};
+  EpiStore epi{y_base_sorted, rowmap, dm.d, dm.d};
   return launch_gemm<TL>(g, T, epi, st);
 }
 

@@ -50,7 +50,8 @@ struct cmoe_handle {
 
 // Workspace layout for T tokens (byte offsets, all 256-byte aligned).
 struct cmoe_ws_layout {
-  size_t blk_counts;  // int32 [n_blocks][G]   permute: per-block cluster histogram -> bases
+  size_t blk_counts;  // int32 [n_blocks][max(G,64)] permute: per-block histogram -> bases
+  size_t sort_i32;    // int32 [6*T + 128]     pair sort scratch, rowmap [T], perm2 [T] at 4T+128, 5T+128
   size_t v1cat;       // f16 [G][KRp][d]       dequantised V1, rows kk = j*r + rho
   size_t u1t;         // f16 [G][d_ff][KRp]    dequantised U1, transposed
   size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2, columns permuted inside 16-groups
@@ -75,6 +76,10 @@ hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         int* expert_idx, float* gate, hipStream_t st);
 hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
                           int* blk_counts, hipStream_t st);
+hipError_t launch_permute_bins(int bins, const int* keys, int T, int* perm, int* inv_perm, int* offsets,
+                               int* blk_counts, hipStream_t st);
+hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* expert_idx, int T, int* scratch,
+                            int* blk_counts, int* rowmap, int* perm2, hipStream_t st);
 hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* v1cat,
                               half_t* u1t, half_t* v2p, hipStream_t st);
 hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,
@@ -97,7 +102,7 @@ hipError_t launch_skinny_combine(const cmoe_dims& dm, const cmoe_weights& w, con
 hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                               half_t* y_base_sorted, hipStream_t st);
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
-                        half_t* y_base_sorted, hipStream_t st);
+                        const int* rowmap, half_t* y_base_sorted, hipStream_t st);
 hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* y_base_sorted, const float* s_down,
                           const int* perm, const int* offsets, const int* expert_idx, const float* gate, int T,
                           half_t* y, hipStream_t st);

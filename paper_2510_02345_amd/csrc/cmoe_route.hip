@@ -314,6 +314,58 @@ __global__ void zero_offsets_kernel(int G, int* offsets) {
 
 }  // namespace
 
+namespace {
+// key[i] = expert_idx[perm[map ? map[i] : i]][col]
+__global__ __launch_bounds__(256) void gather_key_kernel(const int* __restrict__ expert_idx,
+                                                         const int* __restrict__ perm, const int* __restrict__ map,
+                                                         int col, int k, int T, int* __restrict__ key) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= T) return;
+  int p = map ? map[i] : i;
+  key[i] = expert_idx[(size_t)perm[p] * k + col];
+}
+// rowmap[i] = perm_a[perm_b[i]] (cluster-sorted row of refined row i), perm2[i] = its token
+__global__ __launch_bounds__(256) void compose_kernel(const int* __restrict__ perm, const int* __restrict__ perm_a,
+                                                      const int* __restrict__ perm_b, int T,
+                                                      int* __restrict__ rowmap, int* __restrict__ perm2) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= T) return;
+  int p = perm_a ? perm_a[perm_b[i]] : perm_b[i];
+  rowmap[i] = p;
+  perm2[i] = perm[p];
+}
+}  // namespace
+
+// Refines the cluster-sorted order: inside every cluster, rows are ordered by (first
+// selected expert, second selected expert, original order), by two stable counting-sort
+// passes over the global expert slots (least significant key first).  Because the slot of
+// the first expert is cluster-major, cluster boundaries (offsets) do not move.  Rows of a
+// 32-token block then mostly share their experts, so the fused up-projection skips most
+// rank chunks.  scratch: 6 * T + 65 ints.
+hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* expert_idx, int T, int* scratch,
+                            int* blk_counts, int* rowmap, int* perm2, hipStream_t st) {
+  const int E = dm.G * dm.K;
+  int* key = scratch;
+  int* perm_a = scratch + (size_t)T;
+  int* perm_b = scratch + 2 * (size_t)T;
+  int* inv = scratch + 3 * (size_t)T;
+  int* offs = scratch + 4 * (size_t)T;   // E + 1 <= 65 ints
+  dim3 grid((T + 255) / 256), block(256);
+  hipError_t e;
+  const int* first_map = nullptr;
+  if (dm.k >= 2) {
+    hipLaunchKernelGGL(gather_key_kernel, grid, block, 0, st, expert_idx, perm, (const int*)nullptr, 1, dm.k, T, key);
+    e = launch_permute_bins(E, key, T, perm_a, inv, offs, blk_counts, st);
+    if (e != hipSuccess) return e;
+    first_map = perm_a;
+  }
+  hipLaunchKernelGGL(gather_key_kernel, grid, block, 0, st, expert_idx, perm, first_map, 0, dm.k, T, key);
+  e = launch_permute_bins(E, key, T, perm_b, inv, offs, blk_counts, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(compose_kernel, grid, block, 0, st, perm, first_map, perm_b, T, rowmap, perm2);
+  return hipGetLastError();
+}
+
 hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
                         int* expert_idx, float* gate, hipStream_t st) {
   dim3 grid((T + ROUTE_WAVES - 1) / ROUTE_WAVES), block(ROUTE_WAVES * 64);
@@ -353,6 +405,12 @@ hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t
 
 hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
                           int* blk_counts, hipStream_t st) {
+  return launch_permute_bins(dm.G, cluster_id, T, perm, inv_perm, offsets, blk_counts, st);
+}
+
+hipError_t launch_permute_bins(int bins, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
+                               int* blk_counts, hipStream_t st) {
+  struct { int G; } dm{bins};
   if (T == 0) {
     hipLaunchKernelGGL(zero_offsets_kernel, dim3(1), dim3(128), 0, st, dm.G, offsets);
     return hipGetLastError();
