@@ -47,6 +47,9 @@ struct GemmArgs {
   int Kc;            // contraction length, multiple of 32
   const int* offsets;
   int G, n_tiles, m_slots, spx;
+  const half_t* W2;  // optional: rows >= w_split of the weight operand come from W2 (same ldw)
+  int w_split;
+  int T_all;         // offsets == NULL: one group holding rows [0, T_all)
 };
 
 struct TileCtx {
@@ -96,17 +99,23 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   // which cluster and row tile the slot is: derived on the device from the cluster
   // offsets, so no host round trip sits between routing and the GEMMs
   int c = 0, m0 = 0, m_end = 0;
-  for (; c < g.G; ++c) {
-    int lo = g.offsets[c], hi = g.offsets[c + 1];
-    int tiles = (hi - lo + TL::BM - 1) / TL::BM;
-    if (slot < tiles) {
-      m0 = lo + slot * TL::BM;
-      m_end = hi;
-      break;
+  if (g.offsets == nullptr) {
+    m0 = slot * TL::BM;
+    m_end = g.T_all;
+    if (m0 >= m_end) return;
+  } else {
+    for (; c < g.G; ++c) {
+      int lo = g.offsets[c], hi = g.offsets[c + 1];
+      int tiles = (hi - lo + TL::BM - 1) / TL::BM;
+      if (slot < tiles) {
+        m0 = lo + slot * TL::BM;
+        m_end = hi;
+        break;
+      }
+      slot -= tiles;
     }
-    slot -= tiles;
+    if (c == g.G) return;
   }
-  if (c == g.G) return;
   const int n0 = n_tile * TL::BN;
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
   const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
@@ -121,7 +130,8 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
     const int chunk = pos ^ ((row >> 2) & 3);
     const half_t* base;
     if (row < TL::BN) {
-      base = Wc + (size_t)min(n0 + row, g.N - 1) * g.ldw;
+      const int n = min(n0 + row, g.N - 1);
+      base = (g.W2 != nullptr && n >= g.w_split) ? g.W2 + (size_t)(n - g.w_split) * g.ldw : Wc + (size_t)n * g.ldw;
     } else {
       const int p = min(m0 + row - TL::BN, m_end - 1);
       base = g.X + (size_t)(g.gather ? g.gather[p] : p) * g.ldx;
@@ -275,6 +285,84 @@ struct EpiStore {
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd)
           *(half4*)(out + orow * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+      }
+    }
+  }
+};
+
+// ---------------------------------------------------------------- epilogue: two-stage routing
+// acc rows are the logits of all G prototypes (rows 0..G-1) and all G*K expert vectors
+// (rows G..G+E-1) for the tile's tokens.  The decision is the paper's (Sec. 3.3): the
+// cluster with the largest z_g (+ bias) first, then the k largest l_i among that cluster's K
+// experts only, lowest index on ties, gates = softmax over the selected logits.  (All E
+// expert logits are computed because one matrix-core product over the routers is cheaper
+// here than K dot products per token on the vector units; the unselected clusters' logits
+// are discarded.)
+struct EpiRoute {
+  const float* bias;
+  int* cluster_id;
+  int* expert_idx;
+  float* gate;
+  int G, K, k;
+  template <class TL>
+  static constexpr int smem_bytes() {
+    return TL::BM * (TL::BN + 1) * 4 > TL::SMEM_BYTES ? TL::BM * (TL::BN + 1) * 4 : TL::SMEM_BYTES;
+  }
+  template <class TL>
+  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+    constexpr int LD = TL::BN + 1;
+    float* lg = (float*)t.smem;  // [BM tokens][BN + 1 logits]
+    const int h = t.lane >> 5, ml = t.lane & 31;
+    __syncthreads();  // the stage buffers are free
+#pragma unroll
+    for (int b = 0; b < TL::MB; ++b) {
+      const int m = t.wm * TL::WM + b * 32 + ml;
+#pragma unroll
+      for (int a = 0; a < TL::NB; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          lg[m * LD + t.wn * TL::WN + a * 32 + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[a][b][v];
+    }
+    __syncthreads();
+    for (int m = t.tid; m < TL::BM; m += TL::NT) {
+      const int tok = t.m0 + m;
+      if (tok >= t.m_end) continue;
+      const float* row = lg + m * LD;
+      float best = -INFINITY;
+      int c = 0;
+      for (int g = 0; g < G; ++g) {
+        float z = row[g] + (bias ? bias[g] : 0.f);
+        if (z > best) {
+          best = z;
+          c = g;
+        }
+      }
+      const float* l = row + G + c * K;
+      unsigned long long taken = 0ull;  // K <= 32
+      float sel[8];
+      int selj[8];
+      float den = 0.f;
+      for (int a = 0; a < k; ++a) {
+        float bl = -INFINITY;
+        int bj = 0;
+        for (int j = 0; j < K; ++j)
+          if (!((taken >> j) & 1ull) && l[j] > bl) {
+            bl = l[j];
+            bj = j;
+          }
+        taken |= 1ull << bj;
+        sel[a] = bl;
+        selj[a] = bj;
+      }
+      const float lmax = sel[0];
+      for (int a = 0; a < k; ++a) {
+        sel[a] = expf(sel[a] - lmax);
+        den += sel[a];
+      }
+      cluster_id[tok] = c;
+      for (int a = 0; a < k; ++a) {
+        expert_idx[(size_t)tok * k + a] = c * K + selj[a];
+        gate[(size_t)tok * k + a] = sel[a] / den;
       }
     }
   }
@@ -598,7 +686,7 @@ hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* per
                      const int* expert_idx, const half_t* v1cat, half_t* t1, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{v1cat, (long)dm.KRp * dm.d, dm.d, dm.KRp, x, dm.d, perm, dm.d, offsets, dm.G,
-             (dm.KRp + TL::BN - 1) / TL::BN, 0, 0};
+             (dm.KRp + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   EpiT1 epi{t1, perm, expert_idx, dm.k, dm.K, dm.r, dm.KRp};
   return launch_gemm<TL>(g, T, epi, st);
 }
@@ -608,7 +696,7 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         const half_t* v2p, const half_t* t1, half_t* a, float* spart, hipStream_t st) {
   using TL = TileUp;
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
-             (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0};
+             (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   switch (dm.r) {
     case 4: return launch_gemm1_r<4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
     case 8: return launch_gemm1_r<8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
@@ -634,7 +722,7 @@ hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         const int* rowmap, half_t* y_base_sorted, hipStream_t st) {
   using TL = TileBig;
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
-             dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0};
+             dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   EpiStore epi{y_base_sorted, rowmap, dm.d, dm.d};
   return launch_gemm<TL>(g, T, epi, st);
 }
@@ -649,5 +737,21 @@ hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* 
   hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(n_groups * m_slots)), dim3(CB_WAVES * 64), 0, st, u2t,
                      y_base_sorted, s_down, perm, offsets, expert_idx, gate, dm.G, dm.K, dm.k, dm.r, dm.KRp, dm.d,
                      n_groups, y);
+  return hipGetLastError();
+}
+
+// Matrix-core router for large T (G + G*K logits per token fit one 128-row tile).
+hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
+                             int* expert_idx, float* gate, hipStream_t st) {
+  using TL = TileMain;
+  const int rows = dm.G + dm.G * dm.K;
+  GemmArgs g{(const half_t*)w.router_cluster, 0, dm.d, rows, x, dm.d, nullptr, dm.d, nullptr, 1, 1, 0, 0,
+             (const half_t*)w.router_expert, dm.G, T};
+  EpiRoute epi{w.cluster_bias, cluster_id, expert_idx, gate, dm.G, dm.K, dm.k};
+  GemmArgs ga = g;
+  ga.m_slots = (T + TL::BM - 1) / TL::BM;
+  ga.spx = 0;
+  dim3 grid((unsigned)ga.m_slots), block(TL::NT);
+  hipLaunchKernelGGL((gemm_nt_kernel<TL, EpiRoute>), grid, block, 0, st, ga, epi);
   return hipGetLastError();
 }

@@ -74,6 +74,8 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T);
 // Kernel launchers (each returns the hipError_t of its launch).
 hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
                         int* expert_idx, float* gate, hipStream_t st);
+hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
+                             int* expert_idx, float* gate, hipStream_t st);
 hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
                           int* blk_counts, hipStream_t st);
 hipError_t launch_permute_bins(int bins, const int* keys, int T, int* perm, int* inv_perm, int* offsets,

@@ -372,6 +372,8 @@ hipError_t launch_route(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   const half_t* rc = (const half_t*)w.router_cluster;
   const half_t* re = (const half_t*)w.router_expert;
   int chunks_per_lane = (dm.d / 8 + 63) / 64;
+  if (T > SKINNY_T && dm.G + dm.G * dm.K <= 128)
+    return launch_route_mfma(dm, w, x, T, cluster_id, expert_idx, gate, st);
   if (T <= SKINNY_T) {
     dim3 g1(T), b1(RS_WAVES * 64);
     if (chunks_per_lane <= 2)

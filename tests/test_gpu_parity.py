@@ -103,6 +103,9 @@ SMALL = [
     # k = 4 of K = 8, r = 4: two experts share an 8-row group of the rank panel
     ci.small_config("k4", T=257, d=128, d_ff=256, G=2, K=8, r=4, k=4, q=32, seed=45),
     ci.small_config("one", T=1, d=64, d_ff=64, G=2, K=2, r=8, k=2, q=8, seed=46),
+    # more than 128 router rows and more than 64 expert slots: wavefront-per-token router,
+    # no secondary expert sort
+    ci.small_config("manyexperts", T=400, d=64, d_ff=128, G=20, K=8, r=4, k=2, q=8, seed=51),
 ]
 
 
