@@ -218,10 +218,27 @@ extern "C" int cmoe_permute(cmoe_handle* h, const int32_t* cluster_id, int32_t T
   return CMOE_OK;
 }
 
+// y_fused != NULL: when the shapes allow it, the down-projection also applies the residual of
+// the second matrix and writes y in token order (y_base_sorted is then not produced);
+// *fused tells the caller whether that happened.
+static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T, const int32_t* perm,
+                    const int32_t* offsets, const int32_t* expert_idx, const float* gate, cmoe_f16* y_base_sorted,
+                    float* s_down, cmoe_f16* y_fused, bool* fused, void* workspace, size_t workspace_bytes,
+                    void* stream);
+
 extern "C" int cmoe_ffn_forward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T,
                                 const int32_t* perm, const int32_t* offsets, const int32_t* expert_idx,
                                 const float* gate, cmoe_f16* y_base_sorted, float* s_down, void* workspace,
                                 size_t workspace_bytes, void* stream) {
+  return ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, y_base_sorted, s_down, nullptr, nullptr, workspace,
+                  workspace_bytes, stream);
+}
+
+static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T, const int32_t* perm,
+                    const int32_t* offsets, const int32_t* expert_idx, const float* gate, cmoe_f16* y_base_sorted,
+                    float* s_down, cmoe_f16* y_fused, bool* fused, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  if (fused) *fused = false;
   if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
   if (!weights_ffn_ok(w)) return CMOE_ERR_INVALID_ARG;
   if (T == 0) return CMOE_OK;
@@ -267,6 +284,14 @@ extern "C" int cmoe_ffn_forward(cmoe_handle* h, const cmoe_weights* w, const cmo
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, rperm, offsets, expert_idx, gate, u1t, v2p,
                                      t1ext, a, spart, st));
   CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
+  if (y_fused != nullptr && dm.KRp <= 128 && weights_combine_ok(w)) {
+    half_t* u2t = (half_t*)(ws + L.u2t);
+    CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
+    CMOE_LAUNCH(TS_GEMM2, launch_gemm2_combine(dm, *w, a, T, offsets, rperm, u2t, s_down, expert_idx, gate,
+                                               (half_t*)y_fused, st));
+    *fused = true;
+    return CMOE_OK;
+  }
   CMOE_LAUNCH(TS_GEMM2, launch_gemm2(dm, *w, a, T, offsets, rowmap, (half_t*)y_base_sorted, st));
   return CMOE_OK;
 }
@@ -317,8 +342,10 @@ extern "C" int cmoe_forward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
   if (rc != CMOE_OK) return rc;
   rc = cmoe_permute(h, cluster_id, T, perm, inv_perm, offsets, workspace, workspace_bytes, stream);
   if (rc != CMOE_OK || T == 0) return rc;
-  rc = cmoe_ffn_forward(h, w, x, T, perm, offsets, expert_idx, gate, yb, s_down, workspace, workspace_bytes, stream);
-  if (rc != CMOE_OK) return rc;
+  bool fused = false;
+  rc = ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, yb, s_down, y, &fused, workspace, workspace_bytes,
+                stream);
+  if (rc != CMOE_OK || fused) return rc;
   return cmoe_combine(h, w, yb, s_down, perm, inv_perm, offsets, expert_idx, gate, T, y, workspace, workspace_bytes,
                       stream);
 }

@@ -290,6 +290,95 @@ struct EpiStore {
   }
 };
 
+// ---------------------------------------------------------------- epilogue: down-projection + combine
+// acc = (W2_base A)^T block.  Adds the residual of the second matrix as one more
+// matrix-core contraction over the cluster's rank rows, y^T += U2cat^T sext^T with
+// sext[m][e_j*r + rho] = g_j s_j[rho] (zero elsewhere, chunks no token of a 32-column block
+// needs are skipped), and writes the rows straight to token order.  K*r <= 128.
+struct EpiDownCombine {
+  const half_t* u2t;     // [G][d][KRp]
+  const float* s_down;   // [T][k][r], token order
+  const int* rperm;      // token of tile row p
+  const int* expert_idx;
+  const float* gate;
+  half_t* y;             // [T][d], token order
+  int k, K, r, KRp, d;
+  template <class TL>
+  static constexpr int smem_bytes() {
+    return 2 * (TL::BN + TL::BM) * (128 + 8) > TL::SMEM_BYTES ? 2 * (TL::BN + TL::BM) * (128 + 8) : TL::SMEM_BYTES;
+  }
+  template <class TL>
+  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+    const int h = t.lane >> 5, ml = t.lane & 31;
+    const int ldu = KRp + 8, n_chunks = KRp / 16;
+    half_t* sU = t.smem;                 // [BN][ldu]  U2 rows of the tile
+    half_t* sS = t.smem + TL::BN * ldu;  // [BM][ldu]  expanded gated s of the tile's tokens
+    const half_t* u2c = u2t + (size_t)t.c * d * KRp;
+    __syncthreads();  // the stage buffers are free
+    {
+      constexpr int UB = 4;
+      const int u_chunks = TL::BN * (KRp / 8), ucpr = KRp / 8;
+      for (int base = t.tid; base < u_chunks; base += UB * TL::NT) {
+        half8 tmp[UB];
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < u_chunks) tmp[i] = *(const half8*)(u2c + (size_t)min(t.n0 + idx / ucpr, d - 1) * KRp + (idx % ucpr) * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+          int idx = base + i * TL::NT;
+          if (idx < u_chunks) *(half8*)(sU + (idx / ucpr) * ldu + (idx % ucpr) * 8) = tmp[i];
+        }
+      }
+      for (int i = t.tid; i < TL::BM * ldu / 8; i += TL::NT) ((half8*)sS)[i] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    __syncthreads();
+    for (int idx = t.tid; idx < TL::BM * k * r; idx += TL::NT) {
+      const int rho = idx % r, j = (idx / r) % k, m = idx / (r * k);
+      const int p = t.m0 + m;
+      if (p >= t.m_end) continue;
+      const int tok = rperm[p];
+      const int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
+      sS[m * ldu + e * r + rho] = (half_t)(gate[(size_t)tok * k + j] * s_down[((size_t)tok * k + j) * r + rho]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < TL::MB; ++b) {
+      const int ml_t = t.wm * TL::WM + b * 32 + ml;
+      const int p = t.m0 + ml_t;
+      const bool valid = p < t.m_end;
+      const int tok = rperm[valid ? p : t.m_end - 1];
+      unsigned mine = 0;
+      for (int j = 0; j < k; ++j) {
+        const int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
+        const int lo = (e * r) >> 4, hi = (e * r + r - 1) >> 4;
+        mine |= (0xffffffffu >> (31 - hi)) & (0xffffffffu << lo);
+      }
+      if (!valid) mine = 0;
+      unsigned cmask = 0;
+      for (int kc = 0; kc < n_chunks; ++kc)
+        if (__ballot((mine >> kc) & 1u) != 0ull) cmask |= 1u << kc;
+#pragma unroll
+      for (int a = 0; a < TL::NB; ++a) {
+        const int nl = t.wn * TL::WN + a * 32;
+        if (t.n0 + nl >= d) continue;
+        for (int kc = 0; kc < n_chunks; ++kc) {
+          if (!((cmask >> kc) & 1u)) continue;
+          const half8 fa = *(const half8*)(sU + (nl + ml) * ldu + kc * 16 + 8 * h);
+          const half8 fb = *(const half8*)(sS + ml_t * ldu + kc * 16 + 8 * h);
+          acc[a][b] = mfma16(fa, fb, acc[a][b]);
+        }
+        if (valid) {
+#pragma unroll
+          for (int qd = 0; qd < 4; ++qd)
+            *(half4*)(y + (size_t)tok * d + t.n0 + nl + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+        }
+      }
+    }
+  }
+};
+
 // ---------------------------------------------------------------- epilogue: two-stage routing
 // acc rows are the logits of all G prototypes (rows 0..G-1) and all G*K expert vectors
 // (rows G..G+E-1) for the tile's tokens.  The decision is the paper's (Sec. 3.3): the
@@ -754,4 +843,16 @@ hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const h
   dim3 grid((unsigned)ga.m_slots), block(TL::NT);
   hipLaunchKernelGGL((gemm_nt_kernel<TL, EpiRoute>), grid, block, 0, st, ga, epi);
   return hipGetLastError();
+}
+
+// Down-projection with the residual of the second matrix and the return to token order
+// fused into its epilogue (K*r <= 128).  rperm: token of each row of A.
+hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T,
+                                const int* offsets, const int* rperm, const half_t* u2t, const float* s_down,
+                                const int* expert_idx, const float* gate, half_t* y, hipStream_t st) {
+  using TL = TileBig;
+  GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
+             dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  EpiDownCombine epi{u2t, s_down, rperm, expert_idx, gate, y, dm.k, dm.K, dm.r, dm.KRp, dm.d};
+  return launch_gemm<TL>(g, T, epi, st);
 }

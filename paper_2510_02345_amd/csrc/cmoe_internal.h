@@ -105,6 +105,9 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
                               half_t* y_base_sorted, hipStream_t st);
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                         const int* rowmap, half_t* y_base_sorted, hipStream_t st);
+hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T,
+                                const int* offsets, const int* rperm, const half_t* u2t, const float* s_down,
+                                const int* expert_idx, const float* gate, half_t* y, hipStream_t st);
 hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* y_base_sorted, const float* s_down,
                           const int* perm, const int* offsets, const int* expert_idx, const float* gate, int T,
                           half_t* y, hipStream_t st);
