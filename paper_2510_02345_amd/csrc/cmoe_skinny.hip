@@ -138,7 +138,13 @@ struct SkinnyTile {
 // m_end is the end of the pass
 __device__ __forceinline__ bool skinny_tile(const int* offsets, SkinnyTile& t) {
   t.c = blockIdx.y;
-  t.n0 = blockIdx.x * SK_ROWS;
+  // Workgroups are dealt round-robin to the 8 XCDs.  The INT4 factor rows are 128-byte
+  // lines shared by 8 neighbouring row blocks, so inside every run of 64 blocks the 8
+  // workgroups that land on one XCD take 8 neighbouring row blocks: each line is then
+  // fetched into one L2 instead of eight.
+  int xb = blockIdx.x;
+  if ((gridDim.x & 7) == 0 && xb < (int)(gridDim.x & ~63u)) xb = (xb & ~63) + ((xb & 7) << 3) + ((xb >> 3) & 7);
+  t.n0 = xb * SK_ROWS;
   const int lo = offsets[t.c], hi = offsets[t.c + 1];
   t.m0 = lo + blockIdx.z * SK_COLS;
   t.m_end = min(hi, t.m0 + SK_COLS);
