@@ -34,6 +34,12 @@ def kernel_work(cfg, kernel, clusters_hit, experts_hit):
     if kernel == "gemm1_fused":      # W1_base x, + U1 t1, GELU, gated sum, V2 a
         flops = T * (2 * d * f + 4 * k * r * f)
         byts = clusters_hit * f * d * 2 + experts_hit * (r * f + 4 * r * f // cfg.q) + T * d * 2
+    elif kernel == "gemm1_base":     # W1_base x (weight-streaming path)
+        flops = T * 2 * d * f
+        byts = clusters_hit * f * d * 2 + T * d * 2
+    elif kernel == "residual_up":    # + U1 t1, GELU, gated sum, V2 a (weight-streaming path)
+        flops = T * 4 * k * r * f
+        byts = experts_hit * (r * f + 4 * r * f // cfg.q)
     elif kernel == "gemm2":          # W2_base A
         flops = T * 2 * d * f
         byts = clusters_hit * f * d * 2 + T * d * 2

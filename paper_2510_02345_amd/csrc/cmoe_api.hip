@@ -100,7 +100,8 @@ extern "C" const char* cmoe_status_string(int status) {
 
 // ---------------------------------------------------------------- per-kernel timing
 static const char* const kSlotNames[TS_COUNT] = {"route", "permute", "dequant", "t1", "gemm1_fused",
-                                                 "s_reduce", "gemm2", "combine"};
+                                                 "s_reduce", "gemm2", "combine", "gemm1_base",
+                                                 "residual_up"};
 
 extern "C" const char* cmoe_timing_name(int32_t slot) {
   return (slot >= 0 && slot < TS_COUNT) ? kSlotNames[slot] : "";
@@ -260,9 +261,9 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   if (T <= SKINNY_T) {
     // few tokens: the layer is bound by streaming the base matrices once
     CMOE_LAUNCH(TS_T1, launch_skinny_t1(dm, *w, (const half_t*)x, T, perm, expert_idx, t1ext, st));
-    CMOE_LAUNCH(TS_GEMM1, launch_skinny_up(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, gate, t1ext, a,
-                                           spart, st));
-    CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, dm.d_ff / SKINNY_SN, s_down, st));
+    CMOE_LAUNCH(TS_GEMM1_BASE, launch_skinny_hb(dm, *w, (const half_t*)x, T, perm, offsets, a, st));
+    CMOE_LAUNCH(TS_RESID_UP, launch_skinny_resid_up(dm, *w, T, perm, expert_idx, gate, t1ext, a, spart, st));
+    CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN, s_down, st));
     CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
     return CMOE_OK;
   }

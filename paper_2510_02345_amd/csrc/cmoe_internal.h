@@ -29,6 +29,8 @@ enum cmoe_timing_slot {
   TS_SREDUCE,
   TS_GEMM2,
   TS_COMBINE,
+  TS_GEMM1_BASE,
+  TS_RESID_UP,
   TS_COUNT
 };
 
@@ -67,7 +69,7 @@ struct cmoe_ws_layout {
 static const int PERMUTE_BLOCK = 1024;  // tokens per workgroup in the permutation kernels
 static const int G1_BN = 128;           // rows of d_ff per workgroup tile in the fused up-projection
 static const int SKINNY_T = 256;        // at most this many tokens: weight-streaming kernels
-static const int SKINNY_SN = 32;        // rows of d_ff per s partial in the weight-streaming path
+static const int SKINNY_SN = 2048;      // columns of d_ff per s partial in the weight-streaming path
 
 cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T);
 
@@ -95,9 +97,11 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
                           float* s_down, hipStream_t st);
 hipError_t launch_skinny_t1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                             const int* expert_idx, half_t* t1, hipStream_t st);
-hipError_t launch_skinny_up(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* offsets, const int* expert_idx, const float* gate, const half_t* t1,
-                            half_t* a, float* spart, hipStream_t st);
+hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+                            const int* offsets, half_t* hb, hipStream_t st);
+hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, int T, const int* perm,
+                                  const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
+                                  float* spart, hipStream_t st);
 hipError_t launch_skinny_combine(const cmoe_dims& dm, const cmoe_weights& w, const half_t* y_base_sorted,
                                  const float* s_down, const int* inv_perm, const int* expert_idx, const float* gate,
                                  int T, half_t* y, hipStream_t st);

@@ -197,148 +197,17 @@ __global__ __launch_bounds__(1024) void skinny_t1_kernel(const half_t* __restric
   }
 }
 
-// ---------------------------------------------------------------- fused up-projection
-template <int R, int KMAX, int KRPMAX>
-__global__ __launch_bounds__(256, SK_OCC) void skinny_up_kernel(
-    const half_t* __restrict__ x, const half_t* __restrict__ w1_base, const uint8_t* __restrict__ u1_q,
-    const half_t* __restrict__ u1_s, const uint8_t* __restrict__ v2_q, const half_t* __restrict__ v2_s,
-    const half_t* __restrict__ t1, const int* __restrict__ perm, const int* __restrict__ offsets,
-    const int* __restrict__ expert_idx, const float* __restrict__ gate, int T, int d, int d_ff, int K, int k, int q,
-    int KRp, half_t* __restrict__ A, float* __restrict__ spart) {
-  using FU = FusedUp<R, KMAX>;
-  constexpr int LDU = KRPMAX + 8, LDV = SK_ROWS + 8;
-  constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
-  constexpr int SU_BYTES = SK_ROWS * LDU * 2;
-  constexpr int R0_BYTES = RED_BYTES > SU_BYTES ? RED_BYTES : SU_BYTES;
-  constexpr int EPI_BYTES = R0_BYTES + KRPMAX * LDV * 2;
-  constexpr int RINGS = SK_WAVES * SK_RING;
-  __shared__ __attribute__((aligned(1024))) char smem[EPI_BYTES > RINGS ? EPI_BYTES : RINGS];
-  float* red = (float*)smem;
-  half_t* sU = (half_t*)smem;               // [64][LDU]   U1 tile, transposed (after red is dead)
-  half_t* sV = (half_t*)(smem + R0_BYTES);  // [KRp][LDV]  V2 tile, columns permuted in 16-groups
-
-  SkinnyTile t;
-  if (!skinny_tile(offsets, t)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 31, h = lane >> 5;
-
-  // ---- per-lane token state of the epilogue, requested before the weight stream starts
-  typename FU::Tok tk;
-  FU::load_tok(tk, fr < SK_COLS ? t.m0 + fr : t.m_end, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
-
-  // ---- request this thread's share of the cluster's INT4 factor tiles (zero beyond K*r)
-  constexpr int FTASKS = KRPMAX * SK_NCH / 256;
-  unsigned u_bytes[FTASKS];
-  half_t u_sc[FTASKS];
-  unsigned short v_bytes[FTASKS][2];
-  half_t v_sc[FTASKS][2];
-#pragma unroll
-  for (int i2 = 0; i2 < FTASKS; ++i2) {
-    const int task = tid + i2 * 256;
-    const int n8 = task % SK_NCH, kk = task / SK_NCH;
-    u_bytes[i2] = 0;
-    u_sc[i2] = (half_t)0.f;
-    v_bytes[i2][0] = v_bytes[i2][1] = 0;
-    v_sc[i2][0] = v_sc[i2][1] = (half_t)0.f;
-    if (task < KRp * SK_NCH && kk < K * R) {
-      const size_t row = (size_t)t.c * K * R + kk;
-      const int n = t.n0 + n8 * 8;
-      u_bytes[i2] = *(const unsigned*)(u1_q + row * (d_ff / 2) + n / 2);
-      u_sc[i2] = u1_s[row * (d_ff / q) + n / q];
-      const int g16 = (n8 * 8) & ~15, hh = n8 & 1;
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int nv = t.n0 + g16 + 8 * a + 4 * hh;
-        v_bytes[i2][a] = *(const unsigned short*)(v2_q + row * (d_ff / 2) + nv / 2);
-        v_sc[i2][a] = v2_s[row * (d_ff / q) + nv / q];
-      }
-    }
-  }
-
-  // ---- stream W1_base(c) rows [n0, n0 + 64) once; this wavefront's share of d
-  const int wv = __builtin_amdgcn_readfirstlane(wave);
-  const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-  const int lrow = lane >> 3;
-  const half_t* wrow = w1_base + ((size_t)t.c * d_ff + t.n0 + lrow) * d;
-  const half_t* brow0 = x + (size_t)perm[min(t.m0 + lrow, t.m_end - 1)] * d;
-  const half_t* brow1 = x + (size_t)perm[min(t.m0 + 8 + lrow, t.m_end - 1)] * d;
-  float16v acc[SK_RB];
-#pragma unroll
-  for (int rb = 0; rb < SK_RB; ++rb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-  const int iters = d / 64;
-  skinny_stream(wrow, (size_t)8 * d, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
-                wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
-  __syncthreads();  // every ring has been consumed: its space becomes red
-
-  float16v hb;
-  skinny_reduce(red, wave, lane, acc, hb);
-  __syncthreads();  // red is dead: its space becomes sU
-
-  // ---- INT4 factors of the cluster for these 64 rows -> LDS as f16 (Sec. 3.4); their
-  // code bytes and scales were requested before the weight stream started
-  const int KR = K * R;
-#pragma unroll
-  for (int i2 = 0; i2 < FTASKS; ++i2) {   // U1: 8 consecutive n of one rank row, transposed
-    const int task = tid + i2 * 256;
-    if (task < KRp * SK_NCH) {
-      const int n8 = task % SK_NCH, kk = task / SK_NCH;
-      const float sc = (float)u_sc[i2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const unsigned b = (u_bytes[i2] >> (8 * i)) & 0xffu;
-        sU[(n8 * 8 + 2 * i) * LDU + kk] = (half_t)(sc * nib_lo(b));
-        sU[(n8 * 8 + 2 * i + 1) * LDU + kk] = (half_t)(sc * nib_hi(b));
-      }
-    }
-  }
-#pragma unroll
-  for (int i2 = 0; i2 < FTASKS; ++i2) {   // V2: 8 output positions of one rank row
-    const int task = tid + i2 * 256;
-    if (task < KRp * SK_NCH) {
-      const int c8 = task % SK_NCH, kk = task / SK_NCH;
-      half8 o;
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const float sc = (float)v_sc[i2][a];
-        const unsigned bytes = v_bytes[i2][a];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const unsigned b = (bytes >> (8 * (i >> 1))) & 0xffu;
-          o[4 * a + i] = (half_t)(sc * ((i & 1) ? nib_hi(b) : nib_lo(b)));
-        }
-      }
-      *(half8*)(sV + kk * LDV + c8 * 8) = o;
-    }
-  }
-  (void)KR;
-  __syncthreads();
-
-  // ---- per-(token, expert) residual, GELU, gated sum, V2 product: one wavefront per block
-  if (wave < SK_RB) {
-    float16v sacc[KMAX];
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
-    float16v o;
-    auto uf = [&](int kc) { return *(const half8*)(sU + (wave * 32 + fr) * LDU + kc * 16 + 8 * h); };
-    auto vf = [&](int qq, int s2) { return *(const half8*)(sV + (qq * 32 + fr) * LDV + wave * 32 + 16 * s2 + 8 * h); };
-    FU::block(hb, tk, k, KRp / 16, KRp / 32, h, uf, vf, o, sacc);
-    const int nb = t.n0 + wave * 32;
-    if (tk.valid) {
-#pragma unroll
-      for (int qd = 0; qd < 4; ++qd) *(half4*)(A + (size_t)tk.p * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
-    }
-    FU::store_s(tk, sacc, spart + (size_t)(nb / 32) * T * k * R, k, h);
-  }
-}
-
-// ---------------------------------------------------------------- down-projection
-__global__ __launch_bounds__(256, SK_OCC) void skinny_down_kernel(const half_t* __restrict__ A,
-                                                             const half_t* __restrict__ w2_base,
-                                                             const int* __restrict__ offsets, int d, int d_ff,
-                                                             half_t* __restrict__ yb) {
+// ---------------------------------------------------------------- shared-base products
+// out[p][n] = sum_k W[c][n][k] X[row(p)][k] for the sorted rows p of cluster c (the product
+// the experts of a cluster share, Sec. 3.2): up-projection with W = W1_base, X = x gathered
+// through perm, out = Hb; down-projection with W = W2_base, X = A, out = y_base_sorted.
+// N: rows of W per cluster, Kc: contraction length, gather: row index of X per sorted row
+// or NULL for the identity.
+__global__ __launch_bounds__(256, SK_OCC) void skinny_base_kernel(const half_t* __restrict__ X,
+                                                                  const int* __restrict__ gather,
+                                                                  const half_t* __restrict__ W,
+                                                                  const int* __restrict__ offsets, int N, int Kc,
+                                                                  half_t* __restrict__ out) {
   constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
   constexpr int RINGS = SK_WAVES * SK_RING;
   __shared__ __attribute__((aligned(1024))) char smem[RED_BYTES > RINGS ? RED_BYTES : RINGS];
@@ -349,17 +218,22 @@ __global__ __launch_bounds__(256, SK_OCC) void skinny_down_kernel(const half_t* 
   const int wv = __builtin_amdgcn_readfirstlane(wave);
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
   const int lrow = lane >> 3;
-  const half_t* wrow = w2_base + ((size_t)t.c * d + t.n0 + lrow) * d_ff;
+  const half_t* wrow = W + ((size_t)t.c * N + t.n0 + lrow) * Kc;
   const int p = t.m0 + fr;
-  const half_t* brow0 = A + (size_t)min(t.m0 + lrow, t.m_end - 1) * d_ff;
-  const half_t* brow1 = A + (size_t)min(t.m0 + 8 + lrow, t.m_end - 1) * d_ff;
+  int r0 = min(t.m0 + lrow, t.m_end - 1), r1 = min(t.m0 + 8 + lrow, t.m_end - 1);
+  if (gather != nullptr) {
+    r0 = gather[r0];
+    r1 = gather[r1];
+  }
+  const half_t* brow0 = X + (size_t)r0 * Kc;
+  const half_t* brow1 = X + (size_t)r1 * Kc;
   float16v acc[SK_RB];
 #pragma unroll
   for (int rb = 0; rb < SK_RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
-  const int iters = d_ff / 64;
-  skinny_stream(wrow, (size_t)8 * d_ff, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
+  const int iters = Kc / 64;
+  skinny_stream(wrow, (size_t)8 * Kc, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
                 wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
   __syncthreads();  // every ring has been consumed: its space becomes red
   float16v hb;
@@ -367,7 +241,190 @@ __global__ __launch_bounds__(256, SK_OCC) void skinny_down_kernel(const half_t* 
   if (wave < SK_RB && fr < SK_COLS && p < t.m_end) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd)
-      *(half4*)(yb + (size_t)p * d + t.n0 + wave * 32 + 8 * qd + 4 * h) = to_half4(hb, qd);
+      *(half4*)(out + (size_t)p * N + t.n0 + wave * 32 + 8 * qd + 4 * h) = to_half4(hb, qd);
+  }
+}
+
+// ---------------------------------------------------------------- residual-up, GELU, gated sum, V2 product
+// In place on A (which holds Hb on entry), for sorted row p and a chunk of RU_CH columns:
+//   A[p][n] = sum_j g_j GELU(Hb[p][n] + sum_rho U1_{e_j}[rho][n] t1_j[rho])       (Sec. 3.2)
+//   spart[chunk][p][j][rho] = sum_{n in chunk} V2_{e_j}[rho][n] GELU(...)_j[n]
+// with the INT4 factors dequantised on the fly (Sec. 3.4).  A thread owns 8 consecutive
+// columns (one 32-bit word of codes per rank row); the k*r partial dot products of a thread
+// are summed over the wavefront by a halving exchange (64 values on 64 lanes -> lane l ends
+// with the total of value l), then over the 4 wavefronts in fixed order.
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+// The 8 INT4 codes c_0..c_7 of one 32-bit word as f16 pairs WITHOUT their offsets removed.
+// Flipping bit 3 of every nibble turns a two's-complement code c into c + 8 in [0, 16); a
+// nibble masked in place into the mantissa of 1024.0 then reads 1024 + (c + 8) at mantissa
+// bit 0 and 1024 + 16 (c + 8) at mantissa bit 4:
+//   o[0] = 1032 + (c_0, c_4)        o[1] = 16 (72 + (c_1, c_5))
+//   o[2] = 1032 + (c_2, c_6)        o[3] = 16 (72 + (c_3, c_7))
+// The users fold the factor 16 into the other operand and subtract the offsets once per
+// sum (FP32 accumulation keeps that exact enough: the offsets are < 2^11 times the terms).
+constexpr float DQ_OFF_EVEN = 1032.f, DQ_OFF_ODD = 72.f;
+__device__ __forceinline__ unsigned and_or(unsigned a, unsigned mask, unsigned bits) {
+  unsigned r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(bits));
+  return r;
+}
+__device__ __forceinline__ void decode8_raw(unsigned w, half2v (&o)[4]) {
+  const unsigned magic = 0x64006400u;
+  w ^= 0x88888888u;
+  const unsigned w8 = w >> 8;
+  o[0] = __builtin_bit_cast(half2v, and_or(w, 0x000f000fu, magic));
+  o[1] = __builtin_bit_cast(half2v, and_or(w, 0x00f000f0u, magic));
+  o[2] = __builtin_bit_cast(half2v, and_or(w8, 0x000f000fu, magic));
+  o[3] = __builtin_bit_cast(half2v, and_or(w8, 0x00f000f0u, magic));
+}
+
+// The same with the offsets removed exactly (f16 subtraction of representable values):
+// o[0] = (c_0, c_4), o[1] = 16 (c_1, c_5), o[2] = (c_2, c_6), o[3] = 16 (c_3, c_7).
+__device__ __forceinline__ void decode8_x16(unsigned w, half2v (&o)[4]) {
+  decode8_raw(w, o);
+  const half2v even = {(_Float16)1032.f, (_Float16)1032.f}, odd = {(_Float16)1152.f, (_Float16)1152.f};
+  o[0] -= even;
+  o[1] -= odd;
+  o[2] -= even;
+  o[3] -= odd;
+}
+
+constexpr int RU_N = 8;
+constexpr int RU_CH = RU_N * 256;
+static_assert(RU_CH == SKINNY_SN, "s partial chunk");
+
+template <int OFF>
+__device__ __forceinline__ void halving_step(float (&v)[64], int lane) {
+  const bool up = (lane & OFF) != 0;
+#pragma unroll
+  for (int i = 0; i < OFF; ++i) {
+    const float keep = up ? v[i + OFF] : v[i];
+    const float send = up ? v[i] : v[i + OFF];
+    v[i] = keep + __shfl_xor(send, OFF, 64);
+  }
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void skinny_resid_up_kernel(
+    half_t* __restrict__ A, const half_t* __restrict__ t1, const int* __restrict__ perm,
+    const int* __restrict__ expert_idx, const float* __restrict__ gate, const uint8_t* __restrict__ u1_q,
+    const half_t* __restrict__ u1_s, const uint8_t* __restrict__ v2_q, const half_t* __restrict__ v2_s, int T,
+    int d_ff, int k, int q, float* __restrict__ spart) {
+  constexpr int EPG = 64 / R;    // experts per group of 64 (expert, rank row) values
+  __shared__ int srow[8];        // first factor row e_j R of selected expert j
+  __shared__ float st1[256];     // t1_j[rho]
+  __shared__ float sg[8];
+  __shared__ float red[4][64];
+  const int p = blockIdx.x, chunk = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kr = k * R;
+  const int tok = perm[p];
+  if (tid < kr) st1[tid] = (float)t1[(size_t)p * kr + tid];
+  if (tid < k) {
+    srow[tid] = expert_idx[(size_t)tok * k + tid] * R;
+    sg[tid] = gate[(size_t)tok * k + tid];
+  }
+  const int n = chunk * RU_CH + tid * RU_N;
+  const bool in = n < d_ff;
+  const size_t qrow = (size_t)(d_ff / 2), srw = (size_t)(d_ff / q);
+  float hbv[8], av[8];
+  {
+    half8 h8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (in) h8 = *(const half8*)(A + (size_t)p * d_ff + n);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      hbv[i] = (float)h8[i];
+      av[i] = 0.f;
+    }
+  }
+  __syncthreads();
+  for (int j0 = 0; j0 < k; j0 += EPG) {
+    float part[64];
+#pragma unroll
+    for (int jj = 0; jj < EPG; ++jj) {
+      const int j = j0 + jj;
+#pragma unroll
+      for (int rho = 0; rho < R; ++rho) part[jj * R + rho] = 0.f;
+      if (in && j < k) {
+        // the expert's rows are uniform over the workgroup: scalar row bases, one 32-bit
+        // lane offset; every code word and scale is requested before the first is used
+        const size_t row0 = (size_t)__builtin_amdgcn_readfirstlane(srow[j]);
+        const uint8_t* ub = u1_q + row0 * qrow;
+        const uint8_t* vb = v2_q + row0 * qrow;
+        const half_t* usb = u1_s + row0 * srw;
+        const half_t* vsb = v2_s + row0 * srw;
+        const unsigned qoff = (unsigned)n / 2, soff = (unsigned)n / (unsigned)q;
+        unsigned uw[R], vw[R];
+        half_t us[R], vs[R];
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+          uw[rho] = *(const unsigned*)(ub + rho * qrow + qoff);
+          us[rho] = usb[rho * srw + soff];
+        }
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+          vw[rho] = *(const unsigned*)(vb + rho * qrow + qoff);
+          vs[rho] = vsb[rho * srw + soff];
+        }
+        float hj[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) hj[i] = hbv[i];
+        float ssum = 0.f;
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+          const float sc = (float)us[rho] * st1[j * R + rho], sc16 = sc * 0.0625f;
+          ssum += sc;
+          half2v c[4];
+          decode8_raw(uw[rho], c);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float m = (i & 1) ? sc16 : sc;
+            hj[i] = fmaf((float)c[i][0], m, hj[i]);
+            hj[i + 4] = fmaf((float)c[i][1], m, hj[i + 4]);
+          }
+        }
+        const float g = sg[j];
+        half2v g2[4];   // GELU values as f16 pairs (element i, element i + 4), odd i scaled by 1/16
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float off = (i & 1) ? DQ_OFF_ODD : DQ_OFF_EVEN;
+          const float lo = gelu_erf(fmaf(-off, ssum, hj[i])), hi = gelu_erf(fmaf(-off, ssum, hj[i + 4]));
+          av[i] = fmaf(g, lo, av[i]);
+          av[i + 4] = fmaf(g, hi, av[i + 4]);
+          const half2v gg = half2v{(_Float16)lo, (_Float16)hi};
+          g2[i] = (i & 1) ? gg * half2v{(_Float16)0.0625f, (_Float16)0.0625f} : gg;
+        }
+        // the two-element dot product instruction is fed exact codes: its accumulation is
+        // not a correctly rounded FP32 chain, so large offsets must not pass through it
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+          half2v c[4];
+          decode8_x16(vw[rho], c);
+          float dot = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dot = __builtin_amdgcn_fdot2(c[i], g2[i], dot, false);
+          part[jj * R + rho] = (float)vs[rho] * dot;
+        }
+      }
+    }
+    halving_step<32>(part, lane);
+    halving_step<16>(part, lane);
+    halving_step<8>(part, lane);
+    halving_step<4>(part, lane);
+    halving_step<2>(part, lane);
+    halving_step<1>(part, lane);
+    red[wave][lane] = part[0];
+    __syncthreads();
+    if (wave == 0 && j0 * R + lane < kr)
+      spart[((size_t)chunk * T + p) * kr + j0 * R + lane] =
+          ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    __syncthreads();
+  }
+  if (in) {
+    half8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (half_t)av[i];
+    *(half8*)(A + (size_t)p * d_ff + n) = o;
   }
 }
 
@@ -421,32 +478,6 @@ __global__ __launch_bounds__(256) void skinny_combine_kernel(const half_t* __res
   *(half8*)(y + (size_t)t * d + ch * 8) = o;
 }
 
-template <int R, int KMAX>
-hipError_t launch_up_rk(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                        const int* offsets, const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
-                        float* spart, hipStream_t st) {
-  dim3 grid(dm.d_ff / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
-  if (dm.KRp <= 256)
-    hipLaunchKernelGGL((skinny_up_kernel<R, KMAX, 256>), grid, block, 0, st, x, (const half_t*)w.w1_base, w.u1_q,
-                       (const half_t*)w.u1_s, w.v2_q, (const half_t*)w.v2_s, t1, perm, offsets, expert_idx, gate, T,
-                       dm.d, dm.d_ff, dm.K, dm.k, dm.q, dm.KRp, a, spart);
-  else
-    hipLaunchKernelGGL((skinny_up_kernel<R, KMAX, 512>), grid, block, 0, st, x, (const half_t*)w.w1_base, w.u1_q,
-                       (const half_t*)w.u1_s, w.v2_q, (const half_t*)w.v2_s, t1, perm, offsets, expert_idx, gate, T,
-                       dm.d, dm.d_ff, dm.K, dm.k, dm.q, dm.KRp, a, spart);
-  return hipGetLastError();
-}
-
-template <int R>
-hipError_t launch_up_r(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                       const int* offsets, const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
-                       float* spart, hipStream_t st) {
-  if (dm.k <= 1) return launch_up_rk<R, 1>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-  if (dm.k <= 2) return launch_up_rk<R, 2>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-  if (dm.k <= 4) return launch_up_rk<R, 4>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-  return launch_up_rk<R, 8>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-}
-
 }  // namespace
 
 hipError_t launch_skinny_t1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
@@ -456,22 +487,36 @@ hipError_t launch_skinny_t1(const cmoe_dims& dm, const cmoe_weights& w, const ha
   return hipGetLastError();
 }
 
-hipError_t launch_skinny_up(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* offsets, const int* expert_idx, const float* gate, const half_t* t1,
-                            half_t* a, float* spart, hipStream_t st) {
+hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+                            const int* offsets, half_t* hb, hipStream_t st) {
+  dim3 grid(dm.d_ff / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
+  hipLaunchKernelGGL(skinny_base_kernel, grid, block, 0, st, x, perm, (const half_t*)w.w1_base, offsets, dm.d_ff,
+                     dm.d, hb);
+  return hipGetLastError();
+}
+
+hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, int T, const int* perm,
+                                  const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
+                                  float* spart, hipStream_t st) {
+  dim3 grid(T, (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN), block(256);
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, grid, block, 0, st, a, t1, perm, expert_idx, gate, w.u1_q, (const half_t*)w.u1_s,
+                       w.v2_q, (const half_t*)w.v2_s, T, dm.d_ff, dm.k, dm.q, spart);
+  };
   switch (dm.r) {
-    case 4: return launch_up_r<4>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-    case 8: return launch_up_r<8>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-    case 16: return launch_up_r<16>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
-    default: return launch_up_r<32>(dm, w, x, T, perm, offsets, expert_idx, gate, t1, a, spart, st);
+    case 4: go(skinny_resid_up_kernel<4>); break;
+    case 8: go(skinny_resid_up_kernel<8>); break;
+    case 16: go(skinny_resid_up_kernel<16>); break;
+    default: go(skinny_resid_up_kernel<32>); break;
   }
+  return hipGetLastError();
 }
 
 hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                               half_t* y_base_sorted, hipStream_t st) {
   dim3 grid(dm.d / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
-  hipLaunchKernelGGL(skinny_down_kernel, grid, block, 0, st, a, (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff,
-                     y_base_sorted);
+  hipLaunchKernelGGL(skinny_base_kernel, grid, block, 0, st, a, (const int*)nullptr, (const half_t*)w.w2_base,
+                     offsets, dm.d, dm.d_ff, y_base_sorted);
   return hipGetLastError();
 }
 
