@@ -28,6 +28,7 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   L.u2t = take(sizeof(half_t) * dm.G * dm.d * dm.KRp);
   L.t1ext = take(sizeof(half_t) * Tz * dm.k * dm.KRp);
   L.a = take(sizeof(half_t) * Tz * dm.d_ff);
+  L.ures = take(T <= SKINNY_T ? sizeof(float) * Tz * dm.d : 0);
   L.spart = take(sizeof(float) * n_tiles * Tz * dm.k * dm.r);
   L.yb = take(sizeof(half_t) * Tz * dm.d);
   L.sdown = take(sizeof(float) * Tz * dm.k * dm.r);
@@ -260,11 +261,23 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   float* spart = (float*)(ws + L.spart);
   if (T <= SKINNY_T) {
     // few tokens: the layer is bound by streaming the base matrices once
-    CMOE_LAUNCH(TS_T1, launch_skinny_t1(dm, *w, (const half_t*)x, T, perm, expert_idx, t1ext, st));
-    CMOE_LAUNCH(TS_GEMM1_BASE, launch_skinny_hb(dm, *w, (const half_t*)x, T, perm, offsets, a, st));
+    // few tokens: the layer is bound by streaming the base matrices once; the small
+    // per-expert products ride along in the two stream launches
+    const int n_parts = (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN;
+    CMOE_LAUNCH(TS_GEMM1_BASE,
+                launch_skinny_hb(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, t1ext, a, st));
     CMOE_LAUNCH(TS_RESID_UP, launch_skinny_resid_up(dm, *w, T, perm, expert_idx, gate, t1ext, a, spart, st));
-    CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN, s_down, st));
-    CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, st));
+    if (y_fused != nullptr && weights_combine_ok(w)) {
+      float* ures = (float*)(ws + L.ures);
+      CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, perm, expert_idx, gate,
+                                               spart, n_parts, ures, st));
+      CMOE_LAUNCH(TS_COMBINE, launch_skinny_add(dm, (const half_t*)y_base_sorted, ures, perm, T, (half_t*)y_fused, st));
+      *fused = true;
+      return CMOE_OK;
+    }
+    CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, perm, spart, n_parts, s_down, st));
+    CMOE_LAUNCH(TS_GEMM2, launch_skinny_down(dm, *w, a, T, offsets, (half_t*)y_base_sorted, nullptr, nullptr, nullptr,
+                                             nullptr, 0, nullptr, st));
     return CMOE_OK;
   }
   // inside each cluster, order the rows by their selected experts (when the slots fit the

@@ -60,6 +60,7 @@ struct cmoe_ws_layout {
   size_t u2t;         // f16 [G][d][KRp]       dequantised U2, transposed
   size_t t1ext;       // f16 [T][k][KRp]       V1 x, one-hot expanded over the cluster's experts
   size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows
+  size_t ures;        // f32 [T][d]            residual-down term, sorted rows (weight-streaming path only)
   size_t spart;       // f32 [n_parts][T][k][r] partial V2 a per row tile of d_ff
   size_t yb;          // f16 [T][d]            cmoe_forward only: y_base_sorted
   size_t sdown;       // f32 [T][k][r]         cmoe_forward only: s_down
@@ -95,10 +96,10 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         const half_t* v2p, const half_t* t1ext, half_t* a, float* spart, hipStream_t st);
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
                           float* s_down, hipStream_t st);
-hipError_t launch_skinny_t1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* expert_idx, half_t* t1, hipStream_t st);
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* offsets, half_t* hb, hipStream_t st);
+                            const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
+hipError_t launch_skinny_add(const cmoe_dims& dm, const half_t* y_base_sorted, const float* ures, const int* perm,
+                             int T, half_t* y, hipStream_t st);
 hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, int T, const int* perm,
                                   const int* expert_idx, const float* gate, const half_t* t1, half_t* a,
                                   float* spart, hipStream_t st);
@@ -106,7 +107,8 @@ hipError_t launch_skinny_combine(const cmoe_dims& dm, const cmoe_weights& w, con
                                  const float* s_down, const int* inv_perm, const int* expert_idx, const float* gate,
                                  int T, half_t* y, hipStream_t st);
 hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
-                              half_t* y_base_sorted, hipStream_t st);
+                              half_t* y_base_sorted, const int* perm, const int* expert_idx, const float* gate,
+                              const float* spart, int n_parts, float* ures, hipStream_t st);
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                         const int* rowmap, half_t* y_base_sorted, hipStream_t st);
 hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T,

@@ -1,11 +1,10 @@
 // Weight-streaming path of the expert computation for small token counts (Sec. 3.2).
 // With only a handful of tokens per cluster the layer is bound by reading every base
-// matrix once from HBM, so these kernels are built around that stream: a workgroup owns 64
-// weight rows of one cluster, its four wavefronts split the contraction dimension and read
-// their weight fragments straight from global memory in the matrix-core operand layout
-// (each lane 16 bytes, four loads covering one 128-byte line per row), with the cluster's
-// tokens (at most 32 per pass) as the B operand.  INT4 factors are dequantised on the fly
-// (Sec. 3.4); nothing is staged through HBM.
+// matrix once from HBM, so the two shared-base products are pure streams: a workgroup owns
+// 32 weight rows of one cluster and 16 of its tokens, its four wavefronts split the
+// contraction dimension, and both operands travel global -> LDS by DMA into per-wavefront
+// rings.  The per-expert rank-r terms (INT4 factors dequantised on the fly, Sec. 3.4) are
+// small kernels of their own or ride along in the stream launches.
 #include "cmoe_device.h"
 
 namespace {
@@ -134,36 +133,38 @@ __device__ __forceinline__ void skinny_reduce(float* red, int wave, int lane, co
 struct SkinnyTile {
   int c, n0, m0, m_end;
 };
-// grid: x = row block, y = cluster, z = pass over the cluster's tokens (SK_COLS per pass);
-// m_end is the end of the pass
-__device__ __forceinline__ bool skinny_tile(const int* offsets, SkinnyTile& t) {
-  t.c = blockIdx.y;
+// Stream workgroup `id` of a launch of nx row blocks x G clusters x passes (row block
+// fastest); a pass covers SK_COLS tokens of the cluster, m_end is the end of the pass.
+__device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, int G, SkinnyTile& t) {
+  int xb = id % nx;
+  const int yz = id / nx;
+  t.c = yz % G;
+  const int pass = yz / G;
   // Workgroups are dealt round-robin to the 8 XCDs.  The INT4 factor rows are 128-byte
   // lines shared by 8 neighbouring row blocks, so inside every run of 64 blocks the 8
   // workgroups that land on one XCD take 8 neighbouring row blocks: each line is then
-  // fetched into one L2 instead of eight.
-  int xb = blockIdx.x;
-  if ((gridDim.x & 7) == 0 && xb < (int)(gridDim.x & ~63u)) xb = (xb & ~63) + ((xb & 7) << 3) + ((xb >> 3) & 7);
+  // fetched into one L2 instead of eight.  (The caller keeps id congruent to the dispatch
+  // index modulo 8.)
+  if ((nx & 7) == 0 && xb < (nx & ~63)) xb = (xb & ~63) + ((xb & 7) << 3) + ((xb >> 3) & 7);
   t.n0 = xb * SK_ROWS;
   const int lo = offsets[t.c], hi = offsets[t.c + 1];
-  t.m0 = lo + blockIdx.z * SK_COLS;
+  t.m0 = lo + pass * SK_COLS;
   t.m_end = min(hi, t.m0 + SK_COLS);
   return t.m0 < hi;
 }
 
 // ---------------------------------------------------------------- t1 = V1_e x
-// One workgroup per (sorted row p, selected expert j); a wavefront per rank row.
-__global__ __launch_bounds__(1024) void skinny_t1_kernel(const half_t* __restrict__ x, const int* __restrict__ perm,
-                                                        const int* __restrict__ expert_idx,
-                                                        const uint8_t* __restrict__ v1_q,
-                                                        const half_t* __restrict__ v1_s, int d, int q, int r, int k,
-                                                        half_t* __restrict__ t1) {
-  const int p = blockIdx.x / k, j = blockIdx.x % k;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// t1[p][j][:] for sorted row p and its selected expert j, by the calling workgroup: a
+// wavefront per rank row, INT4 codes dequantised on the fly (Sec. 3.4).
+__device__ __forceinline__ void skinny_t1_job(int p, int j, const half_t* __restrict__ x,
+                                              const int* __restrict__ perm, const int* __restrict__ expert_idx,
+                                              const uint8_t* __restrict__ v1_q, const half_t* __restrict__ v1_s,
+                                              int d, int q, int r, int k, half_t* __restrict__ t1) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int tok = perm[p];
   const int e = expert_idx[(size_t)tok * k + j];
   const half_t* xr = x + (size_t)tok * d;
-  for (int rho = wave; rho < r; rho += 16) {
+  for (int rho = wave; rho < r; rho += nw) {
     const size_t row = (size_t)e * r + rho;
     const uint8_t* qr = v1_q + row * (d / 2);
     const half_t* sr = v1_s + row * (d / q);
@@ -197,23 +198,124 @@ __global__ __launch_bounds__(1024) void skinny_t1_kernel(const half_t* __restric
   }
 }
 
+// ---------------------------------------------------------------- residual-down
+// ures[p][n] = sum_j g_j sum_rho U2_{e_j}[rho][n] s_j[rho] for sorted row p and a chunk of
+// 2048 output columns, s_j summed here from its n_parts partials in fixed order.
+__device__ __forceinline__ void skinny_ures_job(int p, int chunk, const int* __restrict__ perm,
+                                                const int* __restrict__ expert_idx, const float* __restrict__ gate,
+                                                const uint8_t* __restrict__ u2_q, const half_t* __restrict__ u2_s,
+                                                const float* __restrict__ spart, int n_parts, int T, int d, int q,
+                                                int r, int k, float* __restrict__ ures) {
+  __shared__ float gs[8 * 32];
+  __shared__ int es[8];
+  const int tid = threadIdx.x;
+  const int tok = perm[p];
+  const int kr = k * r;
+  if (tid < kr) {
+    float sum = 0.f;
+    for (int part = 0; part < n_parts; ++part) sum += spart[((size_t)part * T + p) * kr + tid];
+    gs[tid] = gate[(size_t)tok * k + tid / r] * sum;
+  }
+  if (tid < k) es[tid] = expert_idx[(size_t)tok * k + tid];
+  __syncthreads();
+  const int ch = chunk * 256 + tid;  // 8 output columns
+  if (ch >= d / 8) return;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int j = 0; j < k; ++j) {
+    const size_t row0 = (size_t)es[j] * r;
+    for (int rho0 = 0; rho0 < r; rho0 += 4) {   // r is a multiple of 4: four rows per batch of loads
+      unsigned bytes[4];
+      float sc[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t row = row0 + rho0 + u;
+        bytes[u] = *(const unsigned*)(u2_q + row * (d / 2) + ch * 4);
+        sc[u] = (float)u2_s[row * (d / q) + (ch * 8) / q] * gs[j * r + rho0 + u];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned b = (bytes[u] >> (8 * i)) & 0xffu;
+          acc[2 * i] = fmaf(sc[u], nib_lo(b), acc[2 * i]);
+          acc[2 * i + 1] = fmaf(sc[u], nib_hi(b), acc[2 * i + 1]);
+        }
+    }
+  }
+  float* dst = ures + (size_t)p * d + ch * 8;
+  *(float4v*)dst = float4v{acc[0], acc[1], acc[2], acc[3]};
+  *(float4v*)(dst + 4) = float4v{acc[4], acc[5], acc[6], acc[7]};
+}
+
+// y[perm[p]] = y_base_sorted[p] + ures[p]
+__global__ __launch_bounds__(256) void skinny_add_kernel(const half_t* __restrict__ yb, const float* __restrict__ ures,
+                                                         const int* __restrict__ perm, int d,
+                                                         half_t* __restrict__ y) {
+  const int p = blockIdx.x, ch = blockIdx.y * 256 + threadIdx.x;
+  if (ch >= d / 8) return;
+  const half8 b8 = *(const half8*)(yb + (size_t)p * d + ch * 8);
+  const float* u = ures + (size_t)p * d + ch * 8;
+  const float4v u0 = *(const float4v*)u, u1 = *(const float4v*)(u + 4);
+  half8 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[i] = (half_t)((float)b8[i] + u0[i]);
+    o[i + 4] = (half_t)((float)b8[i + 4] + u1[i]);
+  }
+  *(half8*)(y + (size_t)perm[p] * d + ch * 8) = o;
+}
+
+// Small jobs that ride along with a weight stream as the first workgroups of its grid:
+// they are dispatched first, finish within a few microseconds and leave their slots to
+// the stream, instead of costing a launch of their own on the critical path.
+enum { SIDE_NONE = 0, SIDE_T1 = 1, SIDE_URES = 2 };
+struct SideArgs {
+  const half_t* x;
+  const int* perm;
+  const int* expert_idx;
+  const float* gate;
+  const uint8_t* fq;     // V1 codes (SIDE_T1) or U2 codes (SIDE_URES)
+  const half_t* fs;      // their scales
+  const float* spart;
+  half_t* t1;
+  float* ures;
+  int T, d, q, r, k, n_parts, n_jobs;
+  int n_side;            // workgroups reserved for the jobs (n_jobs rounded up to 8)
+};
+
 // ---------------------------------------------------------------- shared-base products
 // out[p][n] = sum_k W[c][n][k] X[row(p)][k] for the sorted rows p of cluster c (the product
 // the experts of a cluster share, Sec. 3.2): up-projection with W = W1_base, X = x gathered
 // through perm, out = Hb; down-projection with W = W2_base, X = A, out = y_base_sorted.
 // N: rows of W per cluster, Kc: contraction length, gather: row index of X per sorted row
 // or NULL for the identity.
+template <int SIDE>
 __global__ __launch_bounds__(256, SK_OCC) void skinny_base_kernel(const half_t* __restrict__ X,
                                                                   const int* __restrict__ gather,
                                                                   const half_t* __restrict__ W,
                                                                   const int* __restrict__ offsets, int N, int Kc,
-                                                                  half_t* __restrict__ out) {
+                                                                  half_t* __restrict__ out, int nx, int G,
+                                                                  SideArgs sa) {
+  if (SIDE != SIDE_NONE && (int)blockIdx.x < sa.n_side) {
+    const int job = blockIdx.x;
+    if (job >= sa.n_jobs) return;
+    if (SIDE == SIDE_T1) {
+      skinny_t1_job(job / sa.k, job % sa.k, sa.x, sa.perm, sa.expert_idx, sa.fq, sa.fs, sa.d, sa.q, sa.r, sa.k, sa.t1);
+    } else {
+      const int nch = (sa.d + 2047) / 2048;
+      skinny_ures_job(job / nch, job % nch, sa.perm, sa.expert_idx, sa.gate, sa.fq, sa.fs, sa.spart, sa.n_parts, sa.T,
+                      sa.d, sa.q, sa.r, sa.k, sa.ures);
+    }
+    return;
+  }
   constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
   constexpr int RINGS = SK_WAVES * SK_RING;
   __shared__ __attribute__((aligned(1024))) char smem[RED_BYTES > RINGS ? RED_BYTES : RINGS];
   float* red = (float*)smem;
   SkinnyTile t;
-  if (!skinny_tile(offsets, t)) return;
+  if (!skinny_tile(offsets, (int)blockIdx.x - (SIDE != SIDE_NONE ? sa.n_side : 0), nx, G, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 31, h = lane >> 5;
   const int wv = __builtin_amdgcn_readfirstlane(wave);
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
@@ -480,18 +582,33 @@ __global__ __launch_bounds__(256) void skinny_combine_kernel(const half_t* __res
 
 }  // namespace
 
-hipError_t launch_skinny_t1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* expert_idx, half_t* t1, hipStream_t st) {
-  hipLaunchKernelGGL(skinny_t1_kernel, dim3(T * dm.k), dim3(1024), 0, st, x, perm, expert_idx, w.v1_q,
-                     (const half_t*)w.v1_s, dm.d, dm.q, dm.r, dm.k, t1);
-  return hipGetLastError();
-}
-
+// Hb = W1_base(c) x for every sorted row; with t1 != NULL the t1 = V1 x jobs ride along.
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* offsets, half_t* hb, hipStream_t st) {
-  dim3 grid(dm.d_ff / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
-  hipLaunchKernelGGL(skinny_base_kernel, grid, block, 0, st, x, perm, (const half_t*)w.w1_base, offsets, dm.d_ff,
-                     dm.d, hb);
+                            const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st) {
+  const int passes = (T + SK_COLS - 1) / SK_COLS, nx = dm.d_ff / SK_ROWS;
+  const unsigned n_stream = (unsigned)nx * dm.G * passes;
+  dim3 block(256);
+  SideArgs sa{};
+  if (t1 == nullptr) {
+    hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3(n_stream), block, 0, st, x, perm,
+                       (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
+    return hipGetLastError();
+  }
+  sa.x = x;
+  sa.perm = perm;
+  sa.expert_idx = expert_idx;
+  sa.fq = w.v1_q;
+  sa.fs = (const half_t*)w.v1_s;
+  sa.t1 = t1;
+  sa.T = T;
+  sa.d = dm.d;
+  sa.q = dm.q;
+  sa.r = dm.r;
+  sa.k = dm.k;
+  sa.n_jobs = T * dm.k;
+  sa.n_side = (sa.n_jobs + 7) & ~7;
+  hipLaunchKernelGGL(skinny_base_kernel<SIDE_T1>, dim3(n_stream + sa.n_side), block, 0, st, x, perm,
+                     (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
   return hipGetLastError();
 }
 
@@ -512,11 +629,44 @@ hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, in
   return hipGetLastError();
 }
 
+// y_base_sorted = W2_base(c) A; with ures != NULL the residual-down jobs ride along
+// (ures[p] = sum_j g_j U2 s_j from the s partials), to be added by launch_skinny_add.
 hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
-                              half_t* y_base_sorted, hipStream_t st) {
-  dim3 grid(dm.d / SK_ROWS, dm.G, (T + SK_COLS - 1) / SK_COLS), block(256);
-  hipLaunchKernelGGL(skinny_base_kernel, grid, block, 0, st, a, (const int*)nullptr, (const half_t*)w.w2_base,
-                     offsets, dm.d, dm.d_ff, y_base_sorted);
+                              half_t* y_base_sorted, const int* perm, const int* expert_idx, const float* gate,
+                              const float* spart, int n_parts, float* ures, hipStream_t st) {
+  const int passes = (T + SK_COLS - 1) / SK_COLS, nx = dm.d / SK_ROWS;
+  const unsigned n_stream = (unsigned)nx * dm.G * passes;
+  dim3 block(256);
+  SideArgs sa{};
+  if (ures == nullptr) {
+    hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3(n_stream), block, 0, st, a, (const int*)nullptr,
+                       (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
+    return hipGetLastError();
+  }
+  sa.perm = perm;
+  sa.expert_idx = expert_idx;
+  sa.gate = gate;
+  sa.fq = w.u2_q;
+  sa.fs = (const half_t*)w.u2_s;
+  sa.spart = spart;
+  sa.ures = ures;
+  sa.T = T;
+  sa.d = dm.d;
+  sa.q = dm.q;
+  sa.r = dm.r;
+  sa.k = dm.k;
+  sa.n_parts = n_parts;
+  sa.n_jobs = T * ((dm.d + 2047) / 2048);
+  sa.n_side = (sa.n_jobs + 7) & ~7;
+  hipLaunchKernelGGL(skinny_base_kernel<SIDE_URES>, dim3(n_stream + sa.n_side), block, 0, st, a, (const int*)nullptr,
+                     (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
+  return hipGetLastError();
+}
+
+hipError_t launch_skinny_add(const cmoe_dims& dm, const half_t* y_base_sorted, const float* ures, const int* perm,
+                             int T, half_t* y, hipStream_t st) {
+  hipLaunchKernelGGL(skinny_add_kernel, dim3(T, (dm.d / 8 + 255) / 256), dim3(256), 0, st, y_base_sorted, ures, perm,
+                     dm.d, y);
   return hipGetLastError();
 }
 
