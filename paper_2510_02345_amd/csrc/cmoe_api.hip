@@ -21,7 +21,7 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   size_t n_tiles = (T <= SKINNY_T) ? ((size_t)dm.d_ff + SKINNY_SN - 1) / SKINNY_SN
                                    : ((size_t)dm.d_ff + G1_BN - 1) / G1_BN;
   L.blk_counts = take(sizeof(int32_t) * (n_blocks + 1) * (dm.G > 64 ? dm.G : 64));
-  L.sort_i32 = take(sizeof(int32_t) * (8 * Tz + 256));
+  L.sort_i32 = take(sizeof(int32_t) * 2 * Tz);
   L.v1cat = take(sizeof(half_t) * dm.G * dm.KRp * dm.d);
   L.u1t = take(sizeof(half_t) * dm.G * dm.d_ff * dm.KRp);
   L.v2p = take(sizeof(half_t) * dm.G * dm.KRp * dm.d_ff);
@@ -280,19 +280,14 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
                                              nullptr, 0, nullptr, st));
     return CMOE_OK;
   }
-  // inside each cluster, order the rows by their selected experts (when the slots fit the
-  // counting sort's 64 bins); all intermediates live in that refined order, the
-  // down-projection writes its rows back to the caller's cluster-sorted order
-  const int* rperm = perm;
-  const int* rowmap = nullptr;
-  if (dm.G * dm.K <= 64) {
-    int* si = (int*)(ws + L.sort_i32);
-    int* rm = si + 5 * (size_t)T + 128;
-    int* p2 = si + 6 * (size_t)T + 128;
-    CMOE_LAUNCH(TS_PERMUTE, launch_pair_sort(dm, perm, expert_idx, T, si, (int*)(ws + L.blk_counts), rm, p2, st));
-    rperm = p2;
-    rowmap = rm;
-  }
+  // inside each cluster, order the rows by their selected experts; all intermediates live
+  // in that refined order, the down-projection writes its rows back to the caller's
+  // cluster-sorted (or token) order
+  int* rm = (int*)(ws + L.sort_i32);
+  int* p2 = rm + (size_t)T;
+  CMOE_LAUNCH(TS_PERMUTE, launch_pair_sort(dm, perm, offsets, expert_idx, T, rm, p2, st));
+  const int* rperm = p2;
+  const int* rowmap = rm;
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, st));
   CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, rperm, offsets, expert_idx, gate, u1t, v2p,

@@ -53,7 +53,7 @@ struct cmoe_handle {
 // Workspace layout for T tokens (byte offsets, all 256-byte aligned).
 struct cmoe_ws_layout {
   size_t blk_counts;  // int32 [n_blocks][max(G,64)] permute: per-block histogram -> bases
-  size_t sort_i32;    // int32 [6*T + 128]     pair sort scratch, rowmap [T], perm2 [T] at 4T+128, 5T+128
+  size_t sort_i32;    // int32 [2][T]          expert-pair order inside clusters: rowmap, perm2
   size_t v1cat;       // f16 [G][KRp][d]       dequantised V1, rows kk = j*r + rho
   size_t u1t;         // f16 [G][d_ff][KRp]    dequantised U1, transposed
   size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2, columns permuted inside 16-groups
@@ -83,8 +83,8 @@ hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int
                           int* blk_counts, hipStream_t st);
 hipError_t launch_permute_bins(int bins, const int* keys, int T, int* perm, int* inv_perm, int* offsets,
                                int* blk_counts, hipStream_t st);
-hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* expert_idx, int T, int* scratch,
-                            int* blk_counts, int* rowmap, int* perm2, hipStream_t st);
+hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* offsets, const int* expert_idx, int T,
+                            int* rowmap, int* perm2, hipStream_t st);
 hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* v1cat,
                               half_t* u1t, half_t* v2p, hipStream_t st);
 hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,

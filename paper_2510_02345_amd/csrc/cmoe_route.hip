@@ -315,54 +315,88 @@ __global__ void zero_offsets_kernel(int G, int* offsets) {
 }  // namespace
 
 namespace {
-// key[i] = expert_idx[perm[map ? map[i] : i]][col]
-__global__ __launch_bounds__(256) void gather_key_kernel(const int* __restrict__ expert_idx,
-                                                         const int* __restrict__ perm, const int* __restrict__ map,
-                                                         int col, int k, int T, int* __restrict__ key) {
-  int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= T) return;
-  int p = map ? map[i] : i;
-  key[i] = expert_idx[(size_t)perm[p] * k + col];
-}
-// rowmap[i] = perm_a[perm_b[i]] (cluster-sorted row of refined row i), perm2[i] = its token
-__global__ __launch_bounds__(256) void compose_kernel(const int* __restrict__ perm, const int* __restrict__ perm_a,
-                                                      const int* __restrict__ perm_b, int T,
-                                                      int* __restrict__ rowmap, int* __restrict__ perm2) {
-  int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= T) return;
-  int p = perm_a ? perm_a[perm_b[i]] : perm_b[i];
-  rowmap[i] = p;
-  perm2[i] = perm[p];
+// One workgroup per cluster: a stable counting sort of the cluster's rows by the key
+// (first selected expert, second selected expert) taken inside the cluster, or by the
+// first expert alone when K * K keys do not fit the 64 bins.
+//   rowmap[i] = cluster-sorted row of refined row i,  perm2[i] = its token.
+constexpr int PS_THREADS = 1024;
+__global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __restrict__ perm,
+                                                              const int* __restrict__ offsets,
+                                                              const int* __restrict__ expert_idx, int K, int k,
+                                                              int two_keys, int* __restrict__ rowmap,
+                                                              int* __restrict__ perm2) {
+  constexpr int NW = PS_THREADS / 64;
+  __shared__ int binbase[64];
+  __shared__ int wcount[NW][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = blockIdx.x;
+  const int lo = offsets[c], n = offsets[c + 1] - lo;
+  if (n <= 0) return;
+  auto key_of = [&](int i) {
+    const int* e = expert_idx + (size_t)perm[lo + i] * k;
+    const int j0 = e[0] - c * K;
+    return two_keys ? j0 * K + (e[1] - c * K) : j0;
+  };
+  if (tid < 64) binbase[tid] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += PS_THREADS) atomicAdd(&binbase[key_of(i)], 1);
+  __syncthreads();
+  if (wave == 0) {   // exclusive scan of the 64 bin counts
+    const int cnt = binbase[lane];
+    int incl = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += v;
+    }
+    binbase[lane] = incl - cnt;
+  }
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += PS_THREADS) {   // chunks in order keep the sort stable
+    const int i = i0 + tid;
+    const bool in = i < n;
+    const int key = in ? key_of(i) : 0;
+    // lanes of this wavefront holding the same key
+    unsigned long long same = __ballot(in);
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+      const unsigned long long m = __ballot((key >> b) & 1);
+      same &= ((key >> b) & 1) ? m : ~m;
+    }
+    for (int q = lane; q < 64; q += 64) wcount[wave][q] = 0;
+    __syncthreads();
+    const int below = __popcll(same & ((1ull << lane) - 1ull));
+    if (in && below == 0) wcount[wave][key] = __popcll(same);
+    __syncthreads();
+    if (in) {
+      int before = 0;
+      for (int w = 0; w < wave; ++w) before += wcount[w][key];
+      const int pos = lo + binbase[key] + before + below;
+      rowmap[pos] = lo + i;
+      perm2[pos] = perm[lo + i];
+    }
+    __syncthreads();
+    if (tid < 64) {
+      int add = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) add += wcount[w][tid];
+      binbase[tid] += add;
+    }
+    __syncthreads();
+  }
 }
 }  // namespace
 
 // Refines the cluster-sorted order: inside every cluster, rows are ordered by (first
-// selected expert, second selected expert, original order), by two stable counting-sort
-// passes over the global expert slots (least significant key first).  Because the slot of
-// the first expert is cluster-major, cluster boundaries (offsets) do not move.  Rows of a
-// 32-token block then mostly share their experts, so the fused up-projection skips most
-// rank chunks.  scratch: 6 * T + 65 ints.
-hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* expert_idx, int T, int* scratch,
-                            int* blk_counts, int* rowmap, int* perm2, hipStream_t st) {
-  const int E = dm.G * dm.K;
-  int* key = scratch;
-  int* perm_a = scratch + (size_t)T;
-  int* perm_b = scratch + 2 * (size_t)T;
-  int* inv = scratch + 3 * (size_t)T;
-  int* offs = scratch + 4 * (size_t)T;   // E + 1 <= 65 ints
-  dim3 grid((T + 255) / 256), block(256);
-  hipError_t e;
-  const int* first_map = nullptr;
-  if (dm.k >= 2) {
-    hipLaunchKernelGGL(gather_key_kernel, grid, block, 0, st, expert_idx, perm, (const int*)nullptr, 1, dm.k, T, key);
-    e = launch_permute_bins(E, key, T, perm_a, inv, offs, blk_counts, st);
-    if (e != hipSuccess) return e;
-    first_map = perm_a;
-  }
-  hipLaunchKernelGGL(gather_key_kernel, grid, block, 0, st, expert_idx, perm, first_map, 0, dm.k, T, key);
-  e = launch_permute_bins(E, key, T, perm_b, inv, offs, blk_counts, st);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(compose_kernel, grid, block, 0, st, perm, first_map, perm_b, T, rowmap, perm2);
+// selected expert, second selected expert, original order).  Cluster boundaries (offsets)
+// do not move.  Rows of a 32-token block then mostly share their experts, so the fused
+// up-projection skips most rank chunks.
+hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* offsets, const int* expert_idx, int T,
+                            int* rowmap, int* perm2, hipStream_t st) {
+  (void)T;
+  const int two = (dm.k >= 2 && dm.K * dm.K <= 64) ? 1 : 0;
+  hipLaunchKernelGGL(pair_sort_kernel, dim3(dm.G), dim3(PS_THREADS), 0, st, perm, offsets, expert_idx, dm.K, dm.k, two,
+                     rowmap, perm2);
   return hipGetLastError();
 }
 
