@@ -13,6 +13,8 @@
 // leaving registers (its rows become the contraction index).
 #include "cmoe_device.h"
 
+#include <type_traits>
+
 namespace {
 
 // Tile of one workgroup: BN weight rows x BM tokens, WAVES_N x WAVES_M wavefronts, each
@@ -50,6 +52,10 @@ struct GemmArgs {
   const half_t* W2;  // optional: rows >= w_split of the weight operand come from W2 (same ldw)
   int w_split;
   int T_all;         // offsets == NULL: one group holding rows [0, T_all)
+  // A launch covers the slots rel_lo <= rel < rel_hi of every XCD's range.  Slots are
+  // slot_bm rows of one cluster; a tail launch (tail != 0) cuts each of its slots into
+  // slot_bm / BM row tiles of a smaller tile shape.
+  int slot_bm, rel_lo, rel_hi, tail;
 };
 
 struct TileCtx {
@@ -80,8 +86,17 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   // walked over the column tiles in blocks of XSN, so the workgroups resident on one XCD
   // share both operands through that XCD's L2.  With few row tiles (spx == 0) the column
   // tiles are simply dealt across the XCDs.
-  int n_tile, slot;
-  if (g.spx == 0) {
+  int n_tile, slot, sub = 0;
+  if (g.tail) {
+    const int subs = g.slot_bm / TL::BM;
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    n_tile = local % g.n_tiles;
+    const int rest = local / g.n_tiles;
+    sub = rest % subs;
+    const int rel = g.rel_lo + rest / subs;
+    slot = xcd * g.spx + rel;
+    if (rel >= g.rel_hi || slot >= g.m_slots) return;
+  } else if (g.spx == 0) {
     n_tile = blockIdx.x % g.n_tiles;
     slot = blockIdx.x / g.n_tiles;
     if (slot >= g.m_slots) return;
@@ -94,7 +109,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
     const int rel = vg * TL::XSM + r2 / sn;
     slot = xcd * g.spx + rel;
     n_tile = nblk * TL::XSN + r2 % sn;
-    if (r2 / sn >= TL::XSM || rel >= g.spx || slot >= g.m_slots) return;
+    if (r2 / sn >= TL::XSM || rel >= g.rel_hi || slot >= g.m_slots) return;
   }
   // which cluster and row tile the slot is: derived on the device from the cluster
   // offsets, so no host round trip sits between routing and the GEMMs
@@ -106,15 +121,15 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   } else {
     for (; c < g.G; ++c) {
       int lo = g.offsets[c], hi = g.offsets[c + 1];
-      int tiles = (hi - lo + TL::BM - 1) / TL::BM;
+      int tiles = (hi - lo + g.slot_bm - 1) / g.slot_bm;
       if (slot < tiles) {
-        m0 = lo + slot * TL::BM;
+        m0 = lo + slot * g.slot_bm + sub * TL::BM;
         m_end = hi;
         break;
       }
       slot -= tiles;
     }
-    if (c == g.G) return;
+    if (c == g.G || m0 >= m_end) return;
   }
   const int n0 = n_tile * TL::BN;
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
@@ -728,22 +743,55 @@ using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
 using TileUp = TileBig;  // tile of the fused up-projection
 static_assert(TileUp::WN == G1_BN, "workspace sizing assumes one s partial per G1_BN rows");
 
-template <class TL, class Epi>
+// Leftover row tiles of the 256 x 256 schedule: 128 x 128, eight wavefronts (2 x 4, each
+// 64 x 32).  Four of them replace one big tile, so a last round that would occupy a
+// quarter of the CUs fills all of them.
+using TileTail = Tile<128, 128, 2, 4, 4, 1, true, 1, 1>;
+
+// TLT = void: one launch.  Otherwise, when the slots of an XCD do not fill whole rounds of
+// XSM slots and the leftover would leave at least half of the CUs idle, the leftover slots
+// go to a second launch with the smaller tile TLT.
+template <class TL, class Epi, class TLT = void>
 hipError_t launch_gemm(const GemmArgs& g, int T, const Epi& epi, hipStream_t st) {
   GemmArgs ga = g;
   ga.m_slots = (T + TL::BM - 1) / TL::BM + g.G;
-  unsigned n_wg;
+  ga.slot_bm = TL::BM;
+  ga.rel_lo = 0;
+  ga.tail = 0;
+  dim3 block(TL::NT);
   if (ga.m_slots < 32) {
     ga.spx = 0;
-    n_wg = (unsigned)(ga.m_slots * g.n_tiles);
-  } else {
-    ga.spx = (ga.m_slots + 7) / 8;
-    int groups = (ga.spx + TL::XSM - 1) / TL::XSM;
-    n_wg = (unsigned)(8 * groups * TL::XSM * g.n_tiles);
+    ga.rel_hi = ga.m_slots;
+    hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), dim3((unsigned)(ga.m_slots * g.n_tiles)), block, 0, st, ga, epi);
+    return hipGetLastError();
   }
-  dim3 grid(n_wg), block(TL::NT);
-  hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), grid, block, 0, st, ga, epi);
-  return hipGetLastError();
+  ga.spx = (ga.m_slots + 7) / 8;
+  ga.rel_hi = ga.spx;
+  int tail_slots = 0;
+  if constexpr (!std::is_void<TLT>::value) {
+    tail_slots = ga.spx % TL::XSM;
+    // CUs of an XCD the leftover slots would occupy with the big tile: 32 per XCD
+    if (tail_slots * g.n_tiles > 16 || ga.spx < TL::XSM) tail_slots = 0;
+  }
+  ga.rel_hi = ga.spx - tail_slots;
+  const int groups = (ga.rel_hi + TL::XSM - 1) / TL::XSM;
+  hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), dim3((unsigned)(8 * groups * TL::XSM * g.n_tiles)), block, 0, st, ga,
+                     epi);
+  hipError_t e = hipGetLastError();
+  if constexpr (!std::is_void<TLT>::value) {
+    if (e == hipSuccess && tail_slots > 0) {
+      GemmArgs gt = ga;
+      gt.tail = 1;
+      gt.rel_lo = ga.rel_hi;
+      gt.rel_hi = ga.spx;
+      gt.n_tiles = (g.N + TLT::BN - 1) / TLT::BN;
+      const int subs = TL::BM / TLT::BM;
+      hipLaunchKernelGGL((gemm_nt_kernel<TLT, Epi>), dim3((unsigned)(8 * tail_slots * subs * gt.n_tiles)),
+                         dim3(TLT::NT), 0, st, gt, epi);
+      e = hipGetLastError();
+    }
+  }
+  return e;
 }
 
 template <int R, int KMAX>
@@ -813,7 +861,7 @@ hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   EpiStore epi{y_base_sorted, rowmap, dm.d, dm.d};
-  return launch_gemm<TL>(g, T, epi, st);
+  return launch_gemm<TL, EpiStore, TileTail>(g, T, epi, st);
 }
 
 hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* y_base_sorted, const float* s_down,
@@ -854,5 +902,5 @@ hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, cons
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   EpiDownCombine epi{u2t, s_down, rperm, expert_idx, gate, y, dm.k, dm.K, dm.r, dm.KRp, dm.d};
-  return launch_gemm<TL>(g, T, epi, st);
+  return launch_gemm<TL, EpiDownCombine, TileTail>(g, T, epi, st);
 }
