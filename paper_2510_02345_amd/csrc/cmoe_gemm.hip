@@ -318,14 +318,22 @@ struct EpiDownCombine {
   const float* gate;
   half_t* y;             // [T][d], token order
   int k, K, r, KRp, d;
+  // per wavefront: one 32 x 32 output block as f16 (rows padded to 40 elements), so that
+  // four lanes write one token's 64 contiguous bytes
+  static constexpr int OT_LD = 40, OT_BYTES = 32 * OT_LD * 2;
+  template <class TL>
+  static constexpr int panel_bytes() {
+    return 2 * (TL::BN + TL::BM) * (128 + 8) > TL::SMEM_BYTES ? 2 * (TL::BN + TL::BM) * (128 + 8) : TL::SMEM_BYTES;
+  }
   template <class TL>
   static constexpr int smem_bytes() {
-    return 2 * (TL::BN + TL::BM) * (128 + 8) > TL::SMEM_BYTES ? 2 * (TL::BN + TL::BM) * (128 + 8) : TL::SMEM_BYTES;
+    return panel_bytes<TL>() + TL::NWAVES * OT_BYTES;
   }
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
     const int h = t.lane >> 5, ml = t.lane & 31;
     const int ldu = KRp + 8, n_chunks = KRp / 16;
+    half_t* ot = (half_t*)((char*)t.smem + panel_bytes<TL>()) + (t.wm * TL::WAVES_N + t.wn) * (OT_BYTES / 2);
     half_t* sU = t.smem;                 // [BN][ldu]  U2 rows of the tile
     half_t* sS = t.smem + TL::BN * ldu;  // [BM][ldu]  expanded gated s of the tile's tokens
     const half_t* u2c = u2t + (size_t)t.c * d * KRp;
@@ -374,6 +382,13 @@ struct EpiDownCombine {
       unsigned cmask = 0;
       for (int kc = 0; kc < n_chunks; ++kc)
         if (__ballot((mine >> kc) & 1u) != 0ull) cmask |= 1u << kc;
+      // tokens of the rows this lane stores after the transposition (-1: beyond the cluster)
+      int tok_o[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int po = t.m0 + t.wm * TL::WM + b * 32 + (t.lane >> 2) + 16 * i;
+        tok_o[i] = po < t.m_end ? rperm[po] : -1;
+      }
 #pragma unroll
       for (int a = 0; a < TL::NB; ++a) {
         const int nl = t.wn * TL::WN + a * 32;
@@ -384,11 +399,15 @@ struct EpiDownCombine {
           const half8 fb = *(const half8*)(sS + ml_t * ldu + kc * 16 + 8 * h);
           acc[a][b] = mfma16(fa, fb, acc[a][b]);
         }
-        if (valid) {
 #pragma unroll
-          for (int qd = 0; qd < 4; ++qd)
-            *(half4*)(y + (size_t)tok * d + t.n0 + nl + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+        for (int qd = 0; qd < 4; ++qd) *(half4*)(ot + ml * OT_LD + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const half8 v8 = *(const half8*)(ot + ((t.lane >> 2) + 16 * i) * OT_LD + (t.lane & 3) * 8);
+          if (tok_o[i] >= 0) *(half8*)(y + (size_t)tok_o[i] * d + t.n0 + nl + (t.lane & 3) * 8) = v8;
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
       }
     }
   }
@@ -532,11 +551,19 @@ struct EpiFusedUp {
   int T, k, K, KRp, d_ff;
   using FU = FusedUp<R, KMAX>;
 
+  // per wavefront: one 32 x 32 output block as f16, rows padded to 40 elements, to turn
+  // the accumulator layout (a lane holds 4-element pieces of 16 rows) into row-contiguous
+  // 16-byte stores
+  static constexpr int OT_LD = 40, OT_BYTES = 32 * OT_LD * 2;
   template <class TL>
-  static constexpr int smem_bytes() {
+  static constexpr int panel_bytes() {
     return (STAGE && 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8)) > TL::SMEM_BYTES)
                ? 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8))
                : TL::SMEM_BYTES;
+  }
+  template <class TL>
+  static constexpr int smem_bytes() {
+    return panel_bytes<TL>() + TL::NWAVES * OT_BYTES;
   }
 
   template <class TL>
@@ -618,11 +645,20 @@ struct EpiFusedUp {
                        : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s2 + 8 * h);
         };
         FU::block(acc[a][b], tk[b], k, n_chunks, n_pass, h, uf, vf, o, sacc);
-        if (tk[b].valid) {
+        // A[p][nb .. nb + 32) for the block's 32 tokens: through the wavefront's LDS patch
+        // so that four lanes write one token's 64 contiguous bytes
+        half_t* ot = (half_t*)((char*)t.smem + panel_bytes<TL>()) + (t.wm * TL::WAVES_N + t.wn) * (OT_BYTES / 2);
 #pragma unroll
-          for (int qd = 0; qd < 4; ++qd)
-            *(half4*)(A + (size_t)tk[b].p * d_ff + nb + 8 * qd + 4 * h) = to_half4(o, qd);
+        for (int qd = 0; qd < 4; ++qd) *(half4*)(ot + ml * OT_LD + 8 * qd + 4 * h) = to_half4(o, qd);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int tr = (t.lane >> 2) + 16 * i, cq = t.lane & 3;
+          const half8 v8 = *(const half8*)(ot + tr * OT_LD + cq * 8);
+          const int p = t.m0 + t.wm * TL::WM + b * 32 + tr;
+          if (p < t.m_end) *(half8*)(A + (size_t)p * d_ff + nb + cq * 8) = v8;
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
       }
       FU::store_s(tk[b], sacc, spart + (size_t)(t.n_tile * TL::WAVES_N + t.wn) * T * k * R, k, h);
     }
