@@ -106,6 +106,17 @@ SMALL = [
     # more than 128 router rows and more than 64 expert slots: wavefront-per-token router,
     # no secondary expert sort
     ci.small_config("manyexperts", T=400, d=64, d_ff=128, G=20, K=8, r=4, k=2, q=8, seed=51),
+    # weight-streaming path, several 16-token passes per cluster, d_ff not a multiple of the
+    # 2048-column chunk of the per-expert kernel, four experts per token
+    ci.small_config("stream_passes", T=250, d=128, d_ff=2176, G=2, K=8, r=4, k=4, q=32, seed=52),
+    # weight-streaming path with k * r = 256 (four groups of 64 rank values per token)
+    ci.small_config("stream_k8", T=40, d=64, d_ff=128, G=1, K=8, r=32, k=8, q=16, seed=53),
+    # large-T path with K * r = 256: factor panels read from global memory, separate combine
+    ci.small_config("wide_rank", T=600, d=128, d_ff=256, G=2, K=8, r=32, k=2, q=32, seed=54),
+    # the largest supported rank panel, K * r = 512
+    ci.small_config("max_rank", T=300, d=64, d_ff=128, G=1, K=16, r=32, k=2, q=8, seed=55),
+    # exactly at and just above the switch between the two paths
+    ci.small_config("switch_256", T=256, d=64, d_ff=192, G=3, K=4, r=8, k=2, q=8, seed=56),
 ]
 
 
