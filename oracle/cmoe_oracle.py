@@ -226,6 +226,60 @@ def ffn_rewrite(w, x, perm, offsets, expert_idx, gate, K, q):
     return dict(Hb=Hb, t1=t1, A=A, s=s, y_base_sorted=y_base_sorted, y_sorted=y_sorted, y=y)
 
 
+
+# ---------------------------------------------------------------- routing statistics
+# By-products of one routing step that the method's control loops consume: expert loads
+# and their coefficient of variation (Sec. 4, evaluation metrics), the activation
+# centroids of the experts (Sec. 3.1, Eq. 5) and the per-cluster activity that drives
+# offloading and prefetch (Sec. 3.4).
+def expert_loads(expert_idx, E):
+    """n_e = number of (token, slot) assignments to expert e in this step: a token counts
+    once for each of its k selected experts.  int64 [E]."""
+    loads = np.zeros(E, dtype=np.int64)
+    for e in np.asarray(expert_idx).reshape(-1):
+        loads[int(e)] += 1
+    return loads
+
+
+def load_cv(loads):
+    """I_load: standard deviation of the expert loads over their mean (Sec. 4).  The
+    deviation is taken over the E experts as a population (divide by E); 0 if no token."""
+    n = np.asarray(loads, dtype=np.float64)
+    mean = n.sum() / n.size
+    if mean == 0.0:
+        return 0.0
+    var = ((n - mean) ** 2).sum() / n.size
+    return float(np.sqrt(var) / mean)
+
+
+def centroid_ema(mu, x, expert_idx, beta):
+    """Eq. 5: mu_e <- (1 - beta) mu_e + beta xbar_e with xbar_e the mean embedding of the
+    tokens assigned to expert e in this step; experts that received no token keep mu_e."""
+    mu = np.array(mu, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    expert_idx = np.asarray(expert_idx)
+    for e in range(mu.shape[0]):
+        rows = np.nonzero((expert_idx == e).any(axis=1))[0]
+        if rows.size == 0:
+            continue
+        xbar = x[rows].sum(axis=0) / rows.size
+        mu[e] = (1.0 - beta) * mu[e] + beta * xbar
+    return mu
+
+
+def cluster_activity(act, idle, cluster_id, G, lam):
+    """Sec. 3.4: s_g = 1 if cluster g received a token in this step, else 0;
+    act_g <- (1 - lam) act_g + lam s_g (the rolling predictor of a cluster being
+    selected); idle_g = number of consecutive steps without a token (0 after a hit).
+    Returns (act float64 [G], idle int64 [G], tokens per cluster int64 [G])."""
+    counts = np.zeros(G, dtype=np.int64)
+    for c in np.asarray(cluster_id).reshape(-1):
+        counts[int(c)] += 1
+    hit = counts > 0
+    act = (1.0 - lam) * np.asarray(act, dtype=np.float64) + lam * hit.astype(np.float64)
+    idle = np.where(hit, 0, np.asarray(idle, dtype=np.int64) + 1)
+    return act, idle, counts
+
 # ---------------------------------------------------------------- closed forms
 def storage_elements_per_group(d_in, d_out, K, r):
     """Stored elements of one cluster's weight matrix after compression (Sec. 3.2)."""

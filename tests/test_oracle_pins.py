@@ -348,3 +348,81 @@ def test_zipf_config_loads():
     target = 1 / np.arange(1, cfg.G + 1)
     target /= target.sum()
     assert np.abs(load - target).max() < 0.01
+
+
+# ------------------------------------------------------------------ routing statistics
+def test_expert_loads_against_bincount_and_total():
+    rng = np.random.default_rng(7)
+    E, T, k = 24, 500, 3
+    eidx = np.stack([rng.permutation(E)[:k] for _ in range(T)])
+    loads = orc.expert_loads(eidx, E)
+    assert loads.sum() == T * k
+    assert np.array_equal(loads, np.bincount(eidx.reshape(-1), minlength=E))
+    assert np.array_equal(orc.expert_loads(np.zeros((0, k), dtype=np.int64), E), np.zeros(E, dtype=np.int64))
+
+
+def test_load_cv_closed_forms():
+    import statistics
+    # perfectly balanced -> 0; everything on one of E experts -> sqrt(E - 1)
+    assert orc.load_cv([7, 7, 7, 7]) == 0.0
+    for E in (2, 8, 64):
+        one = [0] * E
+        one[3 % E] = 1234
+        assert orc.load_cv(one) == pytest.approx(math.sqrt(E - 1), rel=1e-14)
+    # population standard deviation over the mean, by another routine; scale invariant
+    loads = [3, 9, 4, 0, 11, 5]
+    want = statistics.pstdev(loads) / statistics.mean(loads)
+    assert orc.load_cv(loads) == pytest.approx(want, rel=1e-14)
+    assert orc.load_cv([10 * n for n in loads]) == pytest.approx(want, rel=1e-14)
+    assert orc.load_cv([0, 0, 0]) == 0.0
+
+
+def test_centroid_ema_bruteforce_and_closed_form():
+    rng = np.random.default_rng(11)
+    E, T, k, d, beta = 6, 40, 2, 5, 0.05
+    x = rng.standard_normal((T, d))
+    eidx = np.stack([rng.permutation(E - 1)[:k] for _ in range(T)])   # expert E-1 never selected
+    mu0 = rng.standard_normal((E, d))
+    got = orc.centroid_ema(mu0, x, eidx, beta)
+    # scalar loops: a token counts for each of its k experts
+    for e in range(E):
+        cnt, acc = 0, [0.0] * d
+        for t in range(T):
+            if e in [int(v) for v in eidx[t]]:
+                cnt += 1
+                for i in range(d):
+                    acc[i] += x[t, i]
+        for i in range(d):
+            want = mu0[e, i] if cnt == 0 else (1 - beta) * mu0[e, i] + beta * acc[i] / cnt
+            assert got[e, i] == pytest.approx(want, rel=1e-13, abs=1e-15)
+    assert np.array_equal(got[E - 1], mu0[E - 1])          # no token: unchanged
+    # the same batch n times: mu_n = xbar + (1 - beta)^n (mu_0 - xbar)   (Eq. 5 unrolled)
+    mu, n = mu0.copy(), 25
+    for _ in range(n):
+        mu = orc.centroid_ema(mu, x, eidx, beta)
+    rows = np.nonzero((eidx == 0).any(axis=1))[0]
+    xbar = x[rows].mean(axis=0)
+    assert np.allclose(mu[0], xbar + (1 - beta) ** n * (mu0[0] - xbar), rtol=1e-12, atol=1e-14)
+    # beta = 1 replaces the centroid by the batch mean
+    assert np.allclose(orc.centroid_ema(mu0, x, eidx, 1.0)[0], xbar, rtol=1e-13)
+
+
+def test_cluster_activity_sequence():
+    G, lam = 3, 0.25
+    act, idle = np.zeros(G), np.zeros(G, dtype=np.int64)
+    steps = [[0, 0, 2], [2], [0, 1, 1], []]
+    hits = [[1, 0, 1], [0, 0, 1], [1, 1, 0], [0, 0, 0]]
+    want_idle = [[0, 1, 0], [1, 2, 0], [0, 0, 1], [1, 1, 2]]
+    a = [0.0] * G
+    for cid, h, wi in zip(steps, hits, want_idle):
+        act, idle, counts = orc.cluster_activity(act, idle, np.array(cid, dtype=np.int64), G, lam)
+        a = [(1 - lam) * a[g] + lam * h[g] for g in range(G)]
+        assert np.allclose(act, a, rtol=1e-15)
+        assert list(idle) == wi
+        assert list(counts) == [cid.count(g) for g in range(G)]
+    # a cluster hit every step tends to 1: act_n = 1 - (1 - lam)^n
+    act = np.zeros(1)
+    idle = np.zeros(1, dtype=np.int64)
+    for n in range(1, 9):
+        act, idle, _ = orc.cluster_activity(act, idle, np.array([0]), 1, lam)
+        assert act[0] == pytest.approx(1 - (1 - lam) ** n, rel=1e-14)
