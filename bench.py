@@ -49,6 +49,9 @@ def kernel_work(cfg, kernel, clusters_hit, experts_hit):
     elif kernel == "combine":        # + U2 s, un-permute
         flops = T * 2 * k * r * d
         byts = experts_hit * (r * d // 2 + 2 * r * d // cfg.q) + 2 * T * d * 2
+    elif kernel == "route_stats":    # loads, load CV, centroid EMA (x rows read once per assignment), cluster activity
+        flops = T * k * d
+        byts = T * k * d * 2 + 2 * cfg.E * d * 4 + T * k * 4 + T * 4
     elif kernel == "route":
         flops = T * 2 * d * (cfg.G + cfg.K)
         byts = T * d * 2 + (cfg.G + cfg.E) * d * 2
@@ -57,7 +60,7 @@ def kernel_work(cfg, kernel, clusters_hit, experts_hit):
     return flops, byts
 
 
-def run_config(cfg, steps, warmup, want_traffic=None):
+def run_config(cfg, steps, warmup, want_stats=False):
     import numpy as np
     import torch
 
@@ -87,13 +90,29 @@ def run_config(cfg, steps, warmup, want_traffic=None):
     layer.timing_enable(False)
     per_kernel = {n: (ms / steps) for n, (ms, cnt) in tm.items() if cnt}
 
+    stats_ms = None
+    if want_stats:
+        # the routing statistics by-products on the same routing result
+        E = cfg.G * cfg.K
+        mu = torch.zeros((E, cfg.d), dtype=torch.float32, device="cuda:0")
+        act = torch.zeros((cfg.G,), dtype=torch.float32, device="cuda:0")
+        idle = torch.zeros((cfg.G,), dtype=torch.int32, device="cuda:0")
+        for _ in range(3):
+            layer.route_stats(x, out["perm"], out["offsets"], out["expert_idx"], mu, act, idle)
+        layer.timing_enable(True)
+        for _ in range(steps):
+            layer.route_stats(x, out["perm"], out["offsets"], out["expert_idx"], mu, act, idle)
+        torch.cuda.synchronize()
+        stats_ms = layer.timing_read()["route_stats"][0] / steps
+        layer.timing_enable(False)
+
     eidx = out["expert_idx"].cpu().numpy()
     offs = out["offsets"].cpu().numpy()
     clusters_hit = int((np.diff(offs) > 0).sum())
     experts_hit = int(len(np.unique(eidx)))
     layer.close()
     return dict(ms_per_step=ms_per_step, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
-                experts_hit=experts_hit, inputs=w)
+                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms)
 
 
 def roofline(cfg, res, bound, traffic_table):
@@ -173,7 +192,7 @@ def main():
         del src, dst
 
     cfg = ci.config(args.config)
-    res = run_config(cfg, args.steps, args.warmup)
+    res = run_config(cfg, args.steps, args.warmup, want_stats=True)
     bound = "hbm" if cfg.name == "C4" else "mfma"
     line = {
         "metric": "tokens/s through clustered-MoE FFN layer (1 GPU)",
@@ -188,6 +207,13 @@ def main():
                    "clusters_hit": res["clusters_hit"], "experts_hit": res["experts_hit"]},
         "roofline": roofline(cfg, res, bound, traffic_table),
     }
+    if res["stats_ms"]:
+        _, sb = kernel_work(cfg, "route_stats", res["clusters_hit"], res["experts_hit"])
+        gbs = sb / (res["stats_ms"] * 1e-3) / 1e9
+        line["route_stats"] = {"ms": round(res["stats_ms"], 4), "bound": "hbm", "achieved": round(gbs, 1),
+                               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+                               "note": "by-product entry point (loads, load CV, centroid EMA, cluster activity); "
+                                       "three launches timed together; not part of ms_per_step"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
     del res

@@ -134,6 +134,27 @@ int cmoe_forward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, int32
                  int32_t *inv_perm, int32_t *offsets, void *workspace, size_t workspace_bytes,
                  void *stream);
 
+/* Routing statistics of one step, from the routing and dispatch outputs above
+ * (perm, offsets from cmoe_permute; expert_idx from cmoe_route; all device pointers):
+ *   expert_load  [E] i32   assignments per expert, a token counting once for each of its
+ *                          top_k experts                       (loads of Sec. 4)
+ *   i_load       [1] f32   their coefficient of variation, population standard deviation
+ *                          over the mean, 0 when T = 0         (load-balance metric, Sec. 4)
+ *   mu           [E][d] f32, in/out: mu_e <- (1 - beta) mu_e + beta * mean of the x rows
+ *                          assigned to e; unchanged for an expert without tokens
+ *                                                              (Sec. 3.1, Eq. 5)
+ *   cluster_load [G] i32   tokens per cluster
+ *   cluster_act  [G] f32, in/out: act_g <- (1 - lam) act_g + lam * [cluster_load_g > 0]
+ *   cluster_idle [G] i32, in/out: consecutive steps without a token, 0 after a hit
+ *                                                              (Sec. 3.4)
+ * The caller owns and initialises the in/out state.  Deterministic (fixed summation
+ * order).  Errors as for the other entry points. */
+int cmoe_route_stats(cmoe_handle *h, const cmoe_f16 *x, int32_t T, const int32_t *perm,
+                     const int32_t *offsets, const int32_t *expert_idx, float beta, float lam,
+                     float *mu, float *cluster_act, int32_t *cluster_idle, int32_t *expert_load,
+                     int32_t *cluster_load, float *i_load, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
 /* hipError_t (as int) of the last failed HIP call made through this handle, 0 if none. */
 int cmoe_last_hip_error(const cmoe_handle *h);
 const char *cmoe_status_string(int status);

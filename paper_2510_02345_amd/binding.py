@@ -17,7 +17,8 @@ _lib = None
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
-           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_last_hip_error", "cmoe_status_string",
+           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_stats", "cmoe_last_hip_error",
+           "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
 
 
@@ -58,6 +59,7 @@ def lib():
     L.cmoe_ffn_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_combine.argtypes = [vp, C.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.cmoe_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_route_stats.argtypes = [vp, vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_last_hip_error.argtypes = [vp]
     L.cmoe_status_string.argtypes = [C.c_int]
     L.cmoe_status_string.restype = C.c_char_p
@@ -171,6 +173,21 @@ class Layer:
                                        _ptr(offsets), _ptr(expert_idx), _ptr(gate), T, _ptr(y), _ptr(self.ws),
                                        self.ws.numel(), self._stream()), "cmoe_combine")
         return y
+
+    def route_stats(self, x, perm, offsets, expert_idx, mu, cluster_act, cluster_idle, beta=0.05, lam=0.1):
+        """Updates mu [E][d] f32, cluster_act [G] f32, cluster_idle [G] i32 in place; returns
+        (expert_load [E] i32, cluster_load [G] i32, i_load [1] f32)."""
+        t = self.torch
+        T = x.shape[0]
+        E = self.cfg.G * self.cfg.K
+        load = self._empty((E,), t.int32)
+        cload = self._empty((self.cfg.G,), t.int32)
+        cv = self._empty((1,), t.float32)
+        self._check(lib().cmoe_route_stats(self._h, _ptr(x), T, _ptr(perm), _ptr(offsets), _ptr(expert_idx),
+                                           float(beta), float(lam), _ptr(mu), _ptr(cluster_act), _ptr(cluster_idle),
+                                           _ptr(load), _ptr(cload), _ptr(cv), _ptr(self.ws), self.ws.numel(),
+                                           self._stream()), "cmoe_route_stats")
+        return load, cload, cv
 
     def forward_buffers(self, T):
         t = self.torch

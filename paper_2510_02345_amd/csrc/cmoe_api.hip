@@ -29,6 +29,8 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   L.t1ext = take(sizeof(half_t) * Tz * dm.k * dm.KRp);
   L.a = take(sizeof(half_t) * Tz * dm.d_ff);
   L.ures = take(T <= SKINNY_T ? sizeof(float) * Tz * dm.d : 0);
+  L.stats_part = take(sizeof(float) * stats_partial_slots(dm, T) * dm.K * dm.d);
+  L.stats_cnt = take(sizeof(int32_t) * stats_partial_slots(dm, T) * dm.K);
   L.spart = take(sizeof(float) * n_tiles * Tz * dm.k * dm.r);
   L.yb = take(sizeof(half_t) * Tz * dm.d);
   L.sdown = take(sizeof(float) * Tz * dm.k * dm.r);
@@ -102,7 +104,7 @@ extern "C" const char* cmoe_status_string(int status) {
 // ---------------------------------------------------------------- per-kernel timing
 static const char* const kSlotNames[TS_COUNT] = {"route", "permute", "dequant", "t1", "gemm1_fused",
                                                  "s_reduce", "gemm2", "combine", "gemm1_base",
-                                                 "residual_up"};
+                                                 "residual_up", "route_stats"};
 
 extern "C" const char* cmoe_timing_name(int32_t slot) {
   return (slot >= 0 && slot < TS_COUNT) ? kSlotNames[slot] : "";
@@ -329,6 +331,28 @@ extern "C" int cmoe_combine(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
   CMOE_LAUNCH(TS_COMBINE, launch_combine(dm, u2t, (const half_t*)y_base_sorted, s_down, perm, offsets, expert_idx,
                                          gate, T, (half_t*)y, st));
+  return CMOE_OK;
+}
+
+extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, const int32_t* perm,
+                                const int32_t* offsets, const int32_t* expert_idx, float beta, float lam, float* mu,
+                                float* cluster_act, int32_t* cluster_idle, int32_t* expert_load,
+                                int32_t* cluster_load, float* i_load, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
+  if (!(beta >= 0.f && beta <= 1.f) || !(lam >= 0.f && lam <= 1.f)) return CMOE_ERR_INVALID_ARG;
+  if (!ptr_ok(offsets) || !ptr_ok(mu) || !ptr_ok(cluster_act) || !ptr_ok(cluster_idle) || !ptr_ok(expert_load) ||
+      !ptr_ok(cluster_load) || !ptr_ok(i_load))
+    return CMOE_ERR_INVALID_ARG;
+  if (T > 0 && (!ptr_ok(x) || !ptr_ok(perm) || !ptr_ok(expert_idx))) return CMOE_ERR_INVALID_ARG;
+  int rc = check_ws(h, T, workspace, workspace_bytes);
+  if (rc != CMOE_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  cmoe_ws_layout L = cmoe_layout(h->dm, T);
+  char* ws = (char*)workspace;
+  CMOE_LAUNCH(TS_STATS, launch_route_stats(h->dm, (const half_t*)x, T, perm, offsets, expert_idx, beta, lam, mu,
+                                           cluster_act, cluster_idle, expert_load, cluster_load, i_load,
+                                           (float*)(ws + L.stats_part), (int*)(ws + L.stats_cnt), st));
   return CMOE_OK;
 }
 

@@ -31,6 +31,7 @@ enum cmoe_timing_slot {
   TS_COMBINE,
   TS_GEMM1_BASE,
   TS_RESID_UP,
+  TS_STATS,
   TS_COUNT
 };
 
@@ -61,6 +62,8 @@ struct cmoe_ws_layout {
   size_t t1ext;       // f16 [T][k][KRp]       V1 x, one-hot expanded over the cluster's experts
   size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows
   size_t ures;        // f32 [T][d]            residual-down term, sorted rows (weight-streaming path only)
+  size_t stats_part;  // f32 [slots][K][d]     routing statistics: per-slot sums of x per expert
+  size_t stats_cnt;   // i32 [slots][K]        and their row counts
   size_t spart;       // f32 [n_parts][T][k][r] partial V2 a per row tile of d_ff
   size_t yb;          // f16 [T][d]            cmoe_forward only: y_base_sorted
   size_t sdown;       // f32 [T][k][r]         cmoe_forward only: s_down
@@ -98,6 +101,11 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
                           float* s_down, hipStream_t st);
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                             const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
+size_t stats_partial_slots(const cmoe_dims& dm, int T);
+hipError_t launch_route_stats(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
+                              const int* expert_idx, float beta, float lam, float* mu, float* cluster_act,
+                              int* cluster_idle, int* expert_load, int* cluster_load, float* i_load, float* part,
+                              int* cnt, hipStream_t st);
 hipError_t launch_skinny_add(const cmoe_dims& dm, const half_t* y_base_sorted, const float* ures, const int* perm,
                              int T, half_t* y, hipStream_t st);
 hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, int T, const int* perm,

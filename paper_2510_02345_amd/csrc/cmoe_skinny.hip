@@ -20,7 +20,6 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int SK_ROWS = 32;   // weight rows per workgroup
 constexpr int SK_RB = SK_ROWS / 32;  // 32-row blocks per workgroup
-constexpr int SK_NCH = SK_ROWS / 8;  // 8-row chunks per workgroup
 constexpr int SK_OCC = 3;     // workgroups per CU the LDS budget is sized for
 constexpr int SK_WAVES = 4;   // wavefronts splitting the contraction
 
