@@ -227,6 +227,78 @@ def ffn_rewrite(w, x, perm, offsets, expert_idx, gate, K, q):
 
 
 
+# ---------------------------------------------------------------- compression (Sec. 3.2, 3.4)
+# Construction of the stored form from dense expert matrices W_e [out][in]: the base of a
+# cluster is the mean of its experts (Eq. 6), each expert keeps a rank-r factorisation of
+# its residual (Eq. 7; the truncated SVD is the best one, Sec. 3.2), the factors are
+# quantised to INT4 with one FP16 scale per q codes (Sec. 3.4), and an optional gate zeroes
+# the residual of an expert whose cosine similarity to the base is below a threshold
+# (Sec. 3.4).
+def base_mean(W, G, K):
+    """Eq. 6.  W [G*K][out][in] float16 -> base [G][out][in] float16.  The stored value is an
+    FP16 rounding, so the sum is taken the way the kernel takes it: FP32, experts in index
+    order, divided by K, rounded to nearest even."""
+    W = np.asarray(W)
+    base = np.empty((G,) + W.shape[1:], dtype=np.float16)
+    for c in range(G):
+        acc = np.zeros(W.shape[1:], dtype=np.float32)
+        for j in range(K):
+            acc = acc + W[c * K + j].astype(np.float32)
+        base[c] = (acc / np.float32(K)).astype(np.float16)
+    return base
+
+
+def residual(W_e, base_c):
+    """Delta W_e = W_e - W_base(c) (Eq. 7), float64, against the STORED (FP16) base."""
+    return np.asarray(W_e, dtype=np.float64) - np.asarray(base_c, dtype=np.float64)
+
+
+def truncated_svd_factors(delta, r):
+    """Best rank-r factors of the residual (Sec. 3.2): delta ~ U V with U [out][r] (left
+    singular vectors times singular values) and V [r][in]; also the optimal Frobenius error
+    sqrt(sum_{i > r} sigma_i^2) and the singular values."""
+    u, sv, vt = np.linalg.svd(np.asarray(delta, dtype=np.float64), full_matrices=False)
+    U = u[:, :r] * sv[:r]
+    V = vt[:r]
+    return U, V, float(np.sqrt((sv[r:] ** 2).sum())), sv
+
+
+def quantize_int4_f32(w, q):
+    """Sec. 3.4 quantiser of a factor row block, decisions in FP32 as the kernel takes them:
+    scale = fp16(absmax / 7) per group of q consecutive elements (absmax / 7 in FP32, rounded
+    to nearest even); code = clip(rint(w / scale), -7, 7) with the division in FP32 and ties
+    to even; a group whose scale rounds to 0 gets codes 0.
+    w [..., L] float32 -> (packed uint8 [..., L/2], scales float16 [..., L/q])."""
+    w = np.asarray(w, dtype=np.float32)
+    L = w.shape[-1]
+    g = w.reshape(w.shape[:-1] + (L // q, q))
+    absmax = np.abs(g).max(axis=-1)
+    scale = (absmax / np.float32(7.0)).astype(np.float16)
+    s32 = scale.astype(np.float32)
+    safe = np.where(s32 > 0, s32, np.float32(1.0))
+    codes = np.clip(np.rint(g / safe[..., None]), -7, 7).astype(np.int16)
+    codes = np.where(s32[..., None] > 0, codes, 0).reshape(w.shape)
+    u = (codes & 0xF).astype(np.uint8)
+    return (u[..., 0::2] | (u[..., 1::2] << 4)).astype(np.uint8), scale
+
+
+def cosine_to_base(delta, base_c):
+    """Cosine similarity of vec(Delta W_e) and vec(W_base(c)) (the gate of Sec. 3.4); 0 if
+    either is zero."""
+    a = np.asarray(delta, dtype=np.float64).reshape(-1)
+    b = np.asarray(base_c, dtype=np.float64).reshape(-1)
+    den = np.sqrt((a * a).sum()) * np.sqrt((b * b).sum())
+    return float((a * b).sum() / den) if den > 0 else 0.0
+
+
+def reconstruction_error(W_e, base_c, U, V):
+    """|| W_e - (W_base(c) + U V) ||_F / || W_e ||_F: the relative Frobenius reconstruction
+    error of Sec. 3.2.  U [out][r], V [r][in] are the values the layer would use."""
+    W_e = np.asarray(W_e, dtype=np.float64)
+    diff = W_e - np.asarray(base_c, dtype=np.float64) - np.asarray(U, dtype=np.float64) @ np.asarray(V, dtype=np.float64)
+    return float(np.sqrt((diff * diff).sum()) / np.sqrt((W_e * W_e).sum()))
+
+
 # ---------------------------------------------------------------- routing statistics
 # By-products of one routing step that the method's control loops consume: expert loads
 # and their coefficient of variation (Sec. 4, evaluation metrics), the activation

@@ -426,3 +426,89 @@ def test_cluster_activity_sequence():
     for n in range(1, 9):
         act, idle, _ = orc.cluster_activity(act, idle, np.array([0]), 1, lam)
         assert act[0] == pytest.approx(1 - (1 - lam) ** n, rel=1e-14)
+
+
+# ------------------------------------------------------------------ compression (Sec. 3.2, 3.4)
+def test_base_mean_exact_and_within_half_ulp():
+    # integers: every sum and the division by K = 4 are exact in FP16, so Eq. 6 is hand-checkable
+    W = np.zeros((8, 2, 3), dtype=np.float16)
+    for e in range(8):
+        W[e] = 4 * (e % 4) + np.arange(6).reshape(2, 3) * 8
+    base = orc.base_mean(W, 2, 4)
+    want = 6.0 + np.arange(6).reshape(2, 3) * 8.0          # mean of 0, 4, 8, 12 is 6
+    assert np.array_equal(base[0].astype(np.float64), want) and np.array_equal(base[1], base[0])
+    # random values: the FP16 result is the FP64 mean to within one rounding of the result
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((6, 16, 32)).astype(np.float16)
+    base = orc.base_mean(W, 2, 3).astype(np.float64)
+    exact = W.astype(np.float64).reshape(2, 3, 16, 32).mean(axis=1)
+    ulp = np.spacing(np.abs(exact).astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(base - exact) <= 0.5 * ulp + 1e-6 * ulp + 2.0 ** -24 * np.abs(exact) * 4)
+
+
+def test_truncated_svd_is_eckart_young_optimum():
+    rng = np.random.default_rng(5)
+    out_d, in_d, r = 24, 40, 5
+    delta = rng.standard_normal((out_d, in_d))
+    U, V, err, sv = orc.truncated_svd_factors(delta, r)
+    # the error is the tail of the spectrum, computed by another routine (eigenvalues of D D^T)
+    ev = np.sort(np.linalg.eigvalsh(delta @ delta.T))[::-1]
+    assert err == pytest.approx(math.sqrt(ev[r:].sum()), rel=1e-10)
+    assert np.linalg.norm(delta - U @ V) == pytest.approx(err, rel=1e-10)
+    # no other rank-r product does better: random rank-r factors and a perturbed optimum
+    for _ in range(20):
+        A, B = rng.standard_normal((out_d, r)), rng.standard_normal((r, in_d))
+        coef = np.linalg.lstsq(A, delta, rcond=None)[0]                   # best V for this U
+        assert np.linalg.norm(delta - A @ coef) >= err * (1 - 1e-12)
+        assert np.linalg.norm(delta - (U + 1e-3 * A) @ V) >= err * (1 - 1e-12)
+    # an exactly rank-r matrix is reproduced
+    low = rng.standard_normal((out_d, r)) @ rng.standard_normal((r, in_d))
+    U2, V2, err2, _ = orc.truncated_svd_factors(low, r)
+    assert err2 <= 1e-12 * np.linalg.norm(low) and np.allclose(U2 @ V2, low, atol=1e-12)
+    # rows of V are orthonormal, columns of U orthogonal with the singular values as norms
+    assert np.allclose(V @ V.T, np.eye(r), atol=1e-12)
+    assert np.allclose(np.linalg.norm(U, axis=0), sv[:r], rtol=1e-12)
+
+
+def test_quantiser_fp32_table_and_agreement_with_fp64_form():
+    # one group of 8, absmax 7 -> scale 1: codes are the rounded values, ties to even
+    w = np.array([[7.0, -7.0, 0.5, 1.5, 2.5, -0.5, -1.5, 3.49]], dtype=np.float32)
+    packed, scale = orc.quantize_int4_f32(w, 8)
+    assert scale.tolist() == [[1.0]]
+    assert orc.unpack_int4(packed).tolist() == [[7, -7, 0, 2, 2, 0, -2, 3]]
+    # absmax 3.5 -> scale 0.5: value = code / 2; all-zero group -> scale 0, codes 0
+    w = np.array([[3.5, -3.5, 1.0, 0.25, 0, 0, 0, 0], [0] * 8], dtype=np.float32)
+    packed, scale = orc.quantize_int4_f32(w, 8)
+    assert scale[:, 0].tolist() == [0.5, 0.0]
+    assert orc.unpack_int4(packed).tolist() == [[7, -7, 2, 0, 0, 0, 0, 0], [0] * 8]
+    # dequantised error is at most half a step; same codes as the float64 form used for the
+    # synthetic inputs wherever no value sits within 1e-6 of a rounding boundary
+    rng = np.random.default_rng(9)
+    w = (rng.standard_normal((5, 64)) * 0.02).astype(np.float32)
+    packed, scale = orc.quantize_int4_f32(w, 16)
+    deq = orc.dequant_int4(packed, scale, 16)
+    step = np.repeat(scale.astype(np.float64), 16, axis=-1)
+    assert np.all(np.abs(deq - w) <= 0.5 * step * (1 + 1e-6) + 1e-12)
+    p64, s64 = ci.quantize_int4(w, 16)
+    assert np.array_equal(scale, s64)
+    frac = np.abs(w / np.where(step > 0, step, 1)) % 1.0
+    safe = np.abs(frac - 0.5) > 1e-4
+    assert np.array_equal(orc.unpack_int4(packed)[safe], orc.unpack_int4(p64)[safe])
+
+
+def test_cosine_gate_and_reconstruction_error_closed_forms():
+    a = np.array([[1.0, 0.0], [0.0, 2.0]])
+    assert orc.cosine_to_base(a, 3 * a) == pytest.approx(1.0)
+    assert orc.cosine_to_base(a, -a) == pytest.approx(-1.0)
+    assert orc.cosine_to_base(np.array([[1.0, 0.0]]), np.array([[0.0, 5.0]])) == 0.0
+    assert orc.cosine_to_base(np.zeros((2, 2)), a) == 0.0
+    assert orc.cosine_to_base(np.array([[1.0, 1.0]]), np.array([[1.0, 0.0]])) == pytest.approx(1 / math.sqrt(2))
+    rng = np.random.default_rng(2)
+    W = rng.standard_normal((6, 9))
+    base = rng.standard_normal((6, 9))
+    U, V = rng.standard_normal((6, 2)), rng.standard_normal((2, 9))
+    # zero factors: the error is the residual's share of W; exact factors: zero
+    assert orc.reconstruction_error(W, base, np.zeros((6, 2)), np.zeros((2, 9))) == pytest.approx(
+        np.linalg.norm(W - base) / np.linalg.norm(W), rel=1e-14)
+    assert orc.reconstruction_error(base + U @ V, base, U, V) <= 1e-15
+    assert orc.residual(W.astype(np.float16), base.astype(np.float16)).dtype == np.float64
