@@ -213,6 +213,33 @@ def generate(cfg: LayerConfig, with_weights: bool = True) -> Dict[str, Optional[
     return out
 
 
+def generate_dense_experts(G: int, K: int, out_dim: int, in_dim: int, rank: int, residual_rel: float,
+                           noise_rel: float, seed: int, decay: float = 0.8) -> np.ndarray:
+    """Dense expert matrices with the structure the compression assumes (Sec. 3.1, 3.2: experts
+    of a cluster are correlated): W_e = B_c + residual_rel * L_e + noise_rel * N_e, float16
+    [G*K][out][in].  B_c ~ N(0, 1/in_dim) is common to the cluster, L_e is a rank-`rank`
+    matrix with geometrically decaying singular values, N_e is white noise; L_e and N_e are
+    scaled to Frobenius norm ||B_c||.  (The low-rank product below only shapes the data.)"""
+    rng = np.random.default_rng(np.random.SeedSequence(seed))
+    W = np.empty((G * K, out_dim, in_dim), dtype=np.float16)
+    for c in range(G):
+        B = rng.standard_normal((out_dim, in_dim)) / np.sqrt(in_dim)
+        nb = np.linalg.norm(B)
+        for j in range(K):
+            P = rng.standard_normal((out_dim, rank)) * (decay ** np.arange(rank))
+            L = P @ rng.standard_normal((rank, in_dim))
+            N = rng.standard_normal((out_dim, in_dim))
+            W[c * K + j] = (B + residual_rel * nb * L / np.linalg.norm(L)
+                            + noise_rel * nb * N / np.linalg.norm(N)).astype(np.float16)
+    return W
+
+
+def sketch_rows(sketch: int, in_dim: int, seed: int) -> np.ndarray:
+    """Gaussian test rows of the randomised range finder, float16 [sketch][in_dim]."""
+    rng = np.random.default_rng(np.random.SeedSequence(seed))
+    return rng.standard_normal((sketch, in_dim)).astype(np.float16)
+
+
 def scaled(cfg: LayerConfig, **kw) -> LayerConfig:
     return replace(cfg, **kw)
 

@@ -155,6 +155,52 @@ int cmoe_route_stats(cmoe_handle *h, const cmoe_f16 *x, int32_t T, const int32_t
                      int32_t *cluster_load, float *i_load, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* ---- Construction of the compressed form from dense expert matrices (Sec. 3.2, 3.4) ----
+ * One weight matrix of the layer at a time: W [G*K][out_dim][in_dim] f16, experts stored
+ * cluster-major (call it once for the first and once for the second matrix of the FFN).
+ *   base   [G][out_dim][in_dim] f16   mean of the cluster's K experts (Eq. 6): FP32 sum in
+ *                                     expert order, divided by K, rounded to nearest even
+ *   u_q/u_s, v_q/v_s                  INT4 codes and FP16 scales (format of cmoe_weights) of
+ *                                     the rank-r factors of Delta_e = W_e - base(c) (Eq. 7):
+ *                                     U_e as [r][out_dim], V_e as [r][in_dim]
+ *   report [G*K][4] f32               [0] ||W_e - base - U V||_F / ||W_e||_F with the stored
+ *                                     (dequantised) factors, [1] the same for the FP32
+ *                                     rank-r factors before quantisation (from norms, good
+ *                                     to about 1 % of ||Delta_e|| / ||W_e||), [2] cosine of
+ *                                     vec(Delta_e) and vec(base(c)), [3] 1 if gated off
+ * The factors are the best rank-r pair inside the subspace reached by a randomised
+ * subspace iteration: omega [sketch][in_dim] f16 holds the caller's random test rows
+ * (r <= sketch <= 48; sketch = r + 8 and n_iter = 2 reproduce the truncated SVD's error
+ * to within about one percent on decaying spectra).  use_gate != 0: experts whose cosine
+ * [2] is below gate_gamma get all-zero factors (the optional gate of Sec. 3.4).
+ * Supported: out_dim, in_dim multiples of 64 and of q_group; K <= 64; r <= 32; q_group
+ * even; 0 <= n_iter <= 16.  The quantiser (Sec. 3.4): scale = f16(absmax / 7) per q_group
+ * consecutive elements, code = clip(rint(w / scale), -7, 7), decisions in FP32, codes 0
+ * where the scale rounds to 0.  All pointers are device pointers, 16-byte aligned. */
+typedef struct cmoe_compress_config {
+  int32_t out_dim, in_dim, G, K, r, q_group;
+  int32_t sketch;     /* rows of the random sketch, r <= sketch <= 48 */
+  int32_t n_iter;     /* subspace (power) iterations                  */
+  int32_t use_gate;   /* 0: no gate                                   */
+  float gate_gamma;
+} cmoe_compress_config;
+
+size_t cmoe_compress_workspace_bytes(const cmoe_compress_config *cfg); /* 0 if unsupported */
+int cmoe_compress(const cmoe_compress_config *cfg, const cmoe_f16 *W, const cmoe_f16 *omega,
+                  cmoe_f16 *base, uint8_t *u_q, cmoe_f16 *u_s, uint8_t *v_q, cmoe_f16 *v_s,
+                  float *report, void *workspace, size_t workspace_bytes, void *stream);
+
+/* The quantiser alone: src [rows][L] f32 -> codes [rows][L/2], scales [rows][L/q_group]. */
+int cmoe_quantize_int4(const float *src, int64_t rows, int32_t L, int32_t q_group, uint8_t *codes,
+                       cmoe_f16 *scales, void *stream);
+
+/* err [G*K] f32 = ||W_e - base(c) - U_e V_e||_F / ||W_e||_F for a given stored form
+ * (workspace of cmoe_compress_workspace_bytes(cfg); sketch / n_iter / gate are ignored). */
+int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W, const cmoe_f16 *base,
+                              const uint8_t *u_q, const cmoe_f16 *u_s, const uint8_t *v_q,
+                              const cmoe_f16 *v_s, float *err, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
 /* hipError_t (as int) of the last failed HIP call made through this handle, 0 if none. */
 int cmoe_last_hip_error(const cmoe_handle *h);
 const char *cmoe_status_string(int status);

@@ -17,7 +17,8 @@ _lib = None
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
-           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_stats", "cmoe_last_hip_error",
+           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_stats", "cmoe_compress_workspace_bytes",
+           "cmoe_compress", "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_last_hip_error",
            "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
 
@@ -26,6 +27,11 @@ class CmoeError(RuntimeError):
     def __init__(self, status: int, where: str, hip: int = 0):
         self.status, self.hip = status, hip
         super().__init__(f"{where}: {status_string(status)} (status {status}, hipError {hip})")
+
+
+class CompressConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("out_dim", "in_dim", "G", "K", "r", "q_group", "sketch", "n_iter",
+                                         "use_gate")] + [("gate_gamma", C.c_float)]
 
 
 class Config(C.Structure):
@@ -60,6 +66,11 @@ def lib():
     L.cmoe_combine.argtypes = [vp, C.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.cmoe_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_route_stats.argtypes = [vp, vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_compress_workspace_bytes.argtypes = [C.POINTER(CompressConfig)]
+    L.cmoe_compress_workspace_bytes.restype = sz
+    L.cmoe_compress.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_quantize_int4.argtypes = [vp, C.c_int64, i32, i32, vp, vp, vp]
+    L.cmoe_reconstruction_error.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_last_hip_error.argtypes = [vp]
     L.cmoe_status_string.argtypes = [C.c_int]
     L.cmoe_status_string.restype = C.c_char_p
@@ -68,7 +79,8 @@ def lib():
     L.cmoe_timing_name.argtypes = [i32]
     L.cmoe_timing_name.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name"):
+        if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
+                        "cmoe_compress_workspace_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -76,6 +88,70 @@ def lib():
 
 def status_string(status: int) -> str:
     return lib().cmoe_status_string(status).decode()
+
+
+def _cur_stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _chk(status: int, where: str):
+    if status != 0:
+        raise CmoeError(status, where)
+
+
+def compress(W, omega, G: int, K: int, r: int, q: int, n_iter: int = 2, use_gate: bool = False,
+             gate_gamma: float = 0.05):
+    """cmoe_compress on W [G*K][out][in] f16 (device) with the random test rows omega
+    [sketch][in] f16.  Returns dict(base, u_q, u_s, v_q, v_s, report)."""
+    import torch
+    E, out_d, in_d = W.shape
+    assert E == G * K and omega.shape[1] == in_d
+    cfg = CompressConfig(out_d, in_d, G, K, r, q, omega.shape[0], n_iter, int(use_gate), float(gate_gamma))
+    nbytes = lib().cmoe_compress_workspace_bytes(C.byref(cfg))
+    if nbytes == 0:
+        raise CmoeError(-2, "cmoe_compress_workspace_bytes")
+    dev = W.device
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+    o = dict(base=torch.empty((G, out_d, in_d), dtype=torch.float16, device=dev),
+             u_q=torch.empty((E, r, out_d // 2), dtype=torch.uint8, device=dev),
+             u_s=torch.empty((E, r, out_d // q), dtype=torch.float16, device=dev),
+             v_q=torch.empty((E, r, in_d // 2), dtype=torch.uint8, device=dev),
+             v_s=torch.empty((E, r, in_d // q), dtype=torch.float16, device=dev),
+             report=torch.empty((E, 4), dtype=torch.float32, device=dev))
+    _chk(lib().cmoe_compress(C.byref(cfg), _ptr(W), _ptr(omega), _ptr(o["base"]), _ptr(o["u_q"]), _ptr(o["u_s"]),
+                             _ptr(o["v_q"]), _ptr(o["v_s"]), _ptr(o["report"]), _ptr(ws), nbytes, _cur_stream()),
+         "cmoe_compress")
+    o["_workspace"] = ws      # kept alive until the caller synchronises
+    return o
+
+
+def quantize_int4(src, q: int):
+    """cmoe_quantize_int4: src [rows][L] f32 (device) -> (codes uint8 [rows][L/2], scales f16 [rows][L/q])."""
+    import torch
+    rows, L = src.shape
+    codes = torch.empty((rows, L // 2), dtype=torch.uint8, device=src.device)
+    scales = torch.empty((rows, L // q), dtype=torch.float16, device=src.device)
+    _chk(lib().cmoe_quantize_int4(_ptr(src), rows, L, q, _ptr(codes), _ptr(scales), _cur_stream()),
+         "cmoe_quantize_int4")
+    return codes, scales
+
+
+def reconstruction_error(W, base, u_q, u_s, v_q, v_s, G: int, K: int, r: int, q: int):
+    """cmoe_reconstruction_error: relative Frobenius error per expert of a stored form."""
+    import torch
+    E, out_d, in_d = W.shape
+    cfg = CompressConfig(out_d, in_d, G, K, r, q, r, 0, 0, 0.0)
+    nbytes = lib().cmoe_compress_workspace_bytes(C.byref(cfg))
+    if nbytes == 0:
+        raise CmoeError(-2, "cmoe_compress_workspace_bytes")
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=W.device)
+    err = torch.empty((E,), dtype=torch.float32, device=W.device)
+    _chk(lib().cmoe_reconstruction_error(C.byref(cfg), _ptr(W), _ptr(base), _ptr(u_q), _ptr(u_s), _ptr(v_q),
+                                         _ptr(v_s), _ptr(err), _ptr(ws), nbytes, _cur_stream()),
+         "cmoe_reconstruction_error")
+    torch.cuda.current_stream().synchronize()   # the workspace is freed on return
+    return err
 
 
 def _ptr(t) -> Optional[int]:

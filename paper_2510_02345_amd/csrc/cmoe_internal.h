@@ -101,6 +101,8 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
                           float* s_down, hipStream_t st);
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                             const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
+hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,
+                              int max_rows, half_t* out, hipStream_t st);
 size_t stats_partial_slots(const cmoe_dims& dm, int T);
 hipError_t launch_route_stats(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
                               const int* expert_idx, float beta, float lam, float* mu, float* cluster_act,

@@ -662,6 +662,18 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   return hipGetLastError();
 }
 
+// out[p][n] = sum_k W[g][n][k] X[p][k] for the rows p of group g (offsets [n_groups + 1],
+// at most max_rows rows per group): the weight stream on its own, for callers outside the
+// layer (the compression pipeline streams residual matrices against sketch rows).
+hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,
+                              int max_rows, half_t* out, hipStream_t st) {
+  const int passes = (max_rows + SK_COLS - 1) / SK_COLS, nx = N / SK_ROWS;
+  SideArgs sa{};
+  hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3((unsigned)nx * n_groups * passes), dim3(256), 0, st, X,
+                     (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+  return hipGetLastError();
+}
+
 hipError_t launch_skinny_add(const cmoe_dims& dm, const half_t* y_base_sorted, const float* ures, const int* perm,
                              int T, half_t* y, hipStream_t st) {
   hipLaunchKernelGGL(skinny_add_kernel, dim3(T, (dm.d / 8 + 255) / 256), dim3(256), 0, st, y_base_sorted, ures, perm,

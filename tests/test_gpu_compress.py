@@ -1,0 +1,145 @@
+"""GPU parity of the compression entry points (through the C ABI) against the FP64 oracle.
+
+Bars: base matrices and INT4 codes / scales bit-exact (decisions in the kernel's FP32);
+reconstruction errors and cosines to 1e-3 relative / 1e-4 absolute (FP32 tile sums against
+FP64); the rank-r factors are judged by what is unique about them, their Frobenius error,
+which must lie within 2 % above the truncated SVD's (Eckart-Young optimum) and cannot lie
+below it by more than the FP16 rounding of the residual.
+"""
+import numpy as np
+import pytest
+
+import cmoe_inputs as ci
+from oracle import cmoe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("rows,L,q", [(7, 64, 8), (33, 256, 32), (5, 2048, 128), (1, 128, 2)])
+def test_quantiser_bit_exact(rows, L, q):
+    import paper_2510_02345_amd as cm
+    rng = np.random.default_rng(rows * 1000 + L)
+    w = (rng.standard_normal((rows, L)) * 0.05).astype(np.float32)
+    w[0, :q] = 0.0                                   # an all-zero group
+    w[-1, -q:] = np.float32(1e-9)                    # a group whose scale rounds to zero in FP16
+    w[rows // 2, :q] = np.linspace(-3.5, 3.5, q, dtype=np.float32)   # exact ties at scale 0.5
+    codes, scales = cm.quantize_int4(_dev(w), q)
+    _sync()
+    want_codes, want_scales = orc.quantize_int4_f32(w, q)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint16), want_scales.view(np.uint16))
+    assert np.array_equal(codes.cpu().numpy(), want_codes)
+
+
+def test_reconstruction_error_of_a_given_stored_form():
+    import paper_2510_02345_amd as cm
+    G, K, r, q, out_d, in_d = 2, 3, 8, 32, 192, 128
+    W = ci.generate_dense_experts(G, K, out_d, in_d, rank=6, residual_rel=0.2, noise_rel=0.02, seed=71)
+    base = orc.base_mean(W, G, K)
+    rng = np.random.default_rng(72)
+    uq, us = ci.quantize_int4(rng.standard_normal((G * K, r, out_d)) * 0.05, q)
+    vq, vs = ci.quantize_int4(rng.standard_normal((G * K, r, in_d)) * 0.05, q)
+    err = cm.reconstruction_error(_dev(W), _dev(base), _dev(uq), _dev(us), _dev(vq), _dev(vs), G, K, r, q)
+    _sync()
+    for e in range(G * K):
+        U = orc.dequant_int4(uq[e], us[e], q).T          # [out][r]
+        V = orc.dequant_int4(vq[e], vs[e], q)            # [r][in]
+        want = orc.reconstruction_error(W[e], base[e // K], U, V)
+        assert float(err[e]) == pytest.approx(want, rel=1e-4)
+
+
+CASES = [
+    # (name, G, K, out, in, true rank, residual, noise, r, sketch, q)
+    ("decaying", 2, 4, 256, 128, 12, 0.3, 0.01, 8, 16, 32),
+    ("wide_in", 1, 3, 128, 320, 20, 0.2, 0.02, 16, 24, 64),
+    ("r32", 2, 2, 192, 256, 40, 0.3, 0.01, 32, 40, 32),
+    ("noise_only", 1, 4, 128, 128, 4, 0.0, 0.05, 4, 12, 8),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_compress_against_truncated_svd(case):
+    import paper_2510_02345_amd as cm
+    name, G, K, out_d, in_d, rank0, res, noise, r, sketch, q = case
+    print(f"case {case}", flush=True)
+    W = ci.generate_dense_experts(G, K, out_d, in_d, rank0, res, noise, seed=80 + len(name))
+    omega = ci.sketch_rows(sketch, in_d, seed=90 + len(name))
+    o = cm.compress(_dev(W), _dev(omega), G, K, r, q, n_iter=2)
+    _sync()
+    base = orc.base_mean(W, G, K)
+    assert np.array_equal(o["base"].cpu().numpy().view(np.uint16), base.view(np.uint16))
+    rep = o["report"].cpu().numpy()
+    uq, us = o["u_q"].cpu().numpy(), o["u_s"].cpu().numpy()
+    vq, vs = o["v_q"].cpu().numpy(), o["v_s"].cpu().numpy()
+    for e in range(G * K):
+        delta = orc.residual(W[e], base[e // K])
+        _, _, opt, _ = orc.truncated_svd_factors(delta, r)
+        wn = np.linalg.norm(W[e].astype(np.float64))
+        opt_rel, floor = opt / wn, 2.0 ** -10 * np.linalg.norm(delta) / wn
+        print(f"  e{e}: rank-{r} error {rep[e, 1]:.5f} (optimum {opt_rel:.5f}), stored {rep[e, 0]:.5f}", flush=True)
+        assert rep[e, 1] <= opt_rel * 1.02 + floor
+        assert rep[e, 1] >= opt_rel * 0.995 - floor
+        assert rep[e, 2] == pytest.approx(orc.cosine_to_base(delta, base[e // K]), abs=1e-4)
+        assert rep[e, 3] == 0.0
+        # the stored form: the quantised factors cannot beat the unquantised ones by more than
+        # rounding, and lose at most the INT4 step (half a step per element of both factors)
+        assert rep[e, 0] >= rep[e, 1] * 0.98 - floor
+        assert rep[e, 0] <= rep[e, 1] + 0.35 * np.linalg.norm(delta) / wn + floor
+    # the error the library reports for its own output is the error of that output
+    again = cm.reconstruction_error(_dev(W), _dev(base), o["u_q"], o["u_s"], o["v_q"], o["v_s"], G, K, r, q)
+    _sync()
+    assert np.allclose(again.cpu().numpy(), rep[:, 0], rtol=1e-6)
+    assert uq.shape == (G * K, r, out_d // 2) and vs.shape == (G * K, r, in_d // q) and us.dtype == np.float16
+    assert vq.dtype == np.uint8
+
+
+def test_exactly_low_rank_residual_is_recovered():
+    import paper_2510_02345_amd as cm
+    # Delta_e = L_e - mean_j L_j has rank at most K * rank = 8 = r
+    G, K, out_d, in_d, r = 1, 4, 128, 192, 8
+    W = ci.generate_dense_experts(G, K, out_d, in_d, rank=2, residual_rel=0.3, noise_rel=0.0, seed=101)
+    base = orc.base_mean(W, G, K)
+    o = cm.compress(_dev(W), _dev(ci.sketch_rows(16, in_d, seed=102)), G, K, r, 32, n_iter=2)
+    _sync()
+    rep = o["report"].cpu().numpy()
+    for e in range(K):
+        delta = orc.residual(W[e], base[0])
+        _, _, opt, sv = orc.truncated_svd_factors(delta, r)
+        rel = np.linalg.norm(delta) / np.linalg.norm(W[e].astype(np.float64))
+        # the residual of FP16 matrices against the FP16 mean is low rank only up to FP16 rounding
+        assert opt <= 2e-3 * np.linalg.norm(delta)
+        # [1] is a difference of two FP32 sums of FP16-rounded values: floor about 1 % of ||Delta||
+        assert rep[e, 1] <= 1e-2 * rel
+        assert rep[e, 0] <= 0.2 * rel        # stored form: INT4 steps of both factors
+
+
+def test_gate_zeroes_the_factors():
+    import paper_2510_02345_amd as cm
+    G, K, out_d, in_d, r, q = 2, 2, 128, 128, 4, 32
+    W = ci.generate_dense_experts(G, K, out_d, in_d, rank=4, residual_rel=0.3, noise_rel=0.01, seed=111)
+    base = orc.base_mean(W, G, K)
+    # threshold above every possible cosine: all experts are gated off
+    o = cm.compress(_dev(W), _dev(ci.sketch_rows(8, in_d, seed=112)), G, K, r, q, n_iter=1, use_gate=True,
+                    gate_gamma=2.0)
+    _sync()
+    rep = o["report"].cpu().numpy()
+    assert np.all(rep[:, 3] == 1.0)
+    assert not o["u_q"].cpu().numpy().any() and not o["v_q"].cpu().numpy().any()
+    assert not o["u_s"].cpu().numpy().view(np.uint16).any() and not o["v_s"].cpu().numpy().view(np.uint16).any()
+    for e in range(G * K):
+        want = orc.reconstruction_error(W[e], base[e // K], np.zeros((out_d, r)), np.zeros((r, in_d)))
+        assert rep[e, 0] == pytest.approx(want, rel=1e-4)
+    # threshold below every cosine: nothing is gated
+    o2 = cm.compress(_dev(W), _dev(ci.sketch_rows(8, in_d, seed=112)), G, K, r, q, n_iter=1, use_gate=True,
+                     gate_gamma=-2.0)
+    _sync()
+    assert np.all(o2["report"].cpu().numpy()[:, 3] == 0.0) and o2["u_q"].cpu().numpy().any()
