@@ -213,6 +213,15 @@ __global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__
     for (int idx = t; idx < l * l; idx += 64) V[idx / l][idx % l] = (idx / l == idx % l) ? 1.0 : 0.0;
     __syncthreads();
     for (int sweep = 0; sweep < 12; ++sweep) {
+      // converged when every off-diagonal element is negligible against the diagonal
+      // (every lane evaluates the same test on the same values)
+      double offmax = 0.0, diagmax = 0.0;
+      for (int i = 0; i < l; ++i)
+        for (int j2 = 0; j2 < l; ++j2) {
+          const double a = fabs(A[i][j2]);
+          if (i == j2) diagmax = fmax(diagmax, a); else offmax = fmax(offmax, a);
+        }
+      if (offmax <= 1e-10 * diagmax) break;
       for (int p = 0; p < l - 1; ++p)
         for (int q2 = p + 1; q2 < l; ++q2) {
           const double apq = A[p][q2], app = A[p][p], aqq = A[q2][q2];
