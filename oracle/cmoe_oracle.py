@@ -101,6 +101,56 @@ def route(x, router_cluster, router_expert, K, k, cluster_bias=None):
     return cluster_id, expert_idx, gate, z, l
 
 
+def route_multi(x, router_cluster, router_expert, K, k, top_g=1, temperature=1.0, scale_by_cluster_prob=False,
+                cluster_bias=None):
+    """Routing variants of Sec. 3.3 / 3.5: the top_g most probable clusters are kept (Eq. 9,
+    "Top-g_1 groups"), each contributes its own top-k experts (Eq. 10), and both softmaxes
+    take logits divided by the router temperature (Sec. 3.5).
+
+    Cluster weight w_a: p_g of Eq. 9 itself when scale_by_cluster_prob, else p_g renormalised
+    over the selected clusters (1 for top_g = 1).  gate[t][a][j] = w_a * softmax over the k
+    selected in-cluster logits / temperature.  Selection does not depend on the temperature.
+    Returns cluster_ids [T][top_g] int32 (descending probability, lowest index on ties),
+    expert_idx [T][top_g][k] int32, gate [T][top_g][k] float64, p [T][G] float64."""
+    X = x.astype(np.float64)
+    U = router_cluster.astype(np.float64)
+    V = router_expert.astype(np.float64)
+    T, G = X.shape[0], U.shape[0]
+    z = X @ U.T
+    if cluster_bias is not None:
+        z = z + cluster_bias.astype(np.float64)[None, :]
+    zt = z / temperature
+    pe = np.exp(zt - zt.max(axis=1, keepdims=True))
+    p = pe / pe.sum(axis=1, keepdims=True)
+    cluster_ids = np.argsort(-z, axis=1, kind="stable")[:, :top_g].astype(np.int32)
+    psel = np.take_along_axis(p, cluster_ids.astype(np.int64), axis=1)
+    wgt = psel if scale_by_cluster_prob else psel / psel.sum(axis=1, keepdims=True)
+    expert_idx = np.empty((T, top_g, k), dtype=np.int32)
+    gate = np.empty((T, top_g, k), dtype=np.float64)
+    for a in range(top_g):
+        for c in range(G):
+            rows = np.nonzero(cluster_ids[:, a] == c)[0]
+            if len(rows) == 0:
+                continue
+            l = X[rows] @ V[c * K:(c + 1) * K].T
+            order = np.argsort(-l, axis=1, kind="stable")[:, :k]
+            lsel = np.take_along_axis(l, order, axis=1) / temperature
+            ex = np.exp(lsel - lsel[:, :1])
+            gate[rows, a] = wgt[rows, a][:, None] * ex / ex.sum(axis=1, keepdims=True)
+            expert_idx[rows, a] = c * K + order
+    return cluster_ids, expert_idx, gate, p
+
+
+def forward_naive_multi(w, x, K, k, q, top_g=1, temperature=1.0, scale_by_cluster_prob=False):
+    """The layer with the routing variants: the dense FFNs of all top_g * k selected experts,
+    mixed with the gates of route_multi."""
+    cluster_ids, expert_idx, gate, _ = route_multi(x, w["router_cluster"], w["router_expert"], K, k, top_g,
+                                                   temperature, scale_by_cluster_prob, w.get("cluster_bias"))
+    T = x.shape[0]
+    y = ffn_naive(w, x, expert_idx.reshape(T, top_g * k), gate.reshape(T, top_g * k), K, q)
+    return dict(cluster_ids=cluster_ids, expert_idx=expert_idx, gate=gate, y=y)
+
+
 def permute(cluster_id, G):
     """Stable counting sort of token indices by cluster (the single-device part of
     group-level dispatch, Sec. 3.3).  Returns offsets [G+1], perm [T], inv_perm [T]."""

@@ -512,3 +512,71 @@ def test_cosine_gate_and_reconstruction_error_closed_forms():
         np.linalg.norm(W - base) / np.linalg.norm(W), rel=1e-14)
     assert orc.reconstruction_error(base + U @ V, base, U, V) <= 1e-15
     assert orc.residual(W.astype(np.float16), base.astype(np.float16)).dtype == np.float64
+
+
+# ------------------------------------------------------------------ routing variants (Sec. 3.3, 3.5)
+def test_route_multi_reduces_to_route():
+    cfg = ci.small_config("rm", T=80, d=32, d_ff=32, G=4, K=4, r=4, k=2, q=8, seed=21)
+    w = ci.generate(cfg)
+    cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k)
+    cids, eidx2, gate2, p = orc.route_multi(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k)
+    assert np.array_equal(cids[:, 0], cid) and np.array_equal(eidx2[:, 0], eidx)
+    assert np.allclose(gate2[:, 0], gate, rtol=1e-14)
+    assert np.allclose(p.sum(axis=1), 1.0, rtol=1e-14)
+
+
+@pytest.mark.parametrize("top_g,tau,scale", [(2, 1.0, False), (3, 0.7, True), (1, 0.7, True), (4, 2.0, False)])
+def test_route_multi_bruteforce(top_g, tau, scale):
+    cfg = ci.small_config("rmb", T=30, d=16, d_ff=32, G=4, K=3, r=4, k=2, q=8, seed=22)
+    w = ci.generate(cfg)
+    x = w["x"].astype(np.float64)
+    rc, re = w["router_cluster"].astype(np.float64), w["router_expert"].astype(np.float64)
+    cids, eidx, gate, _ = orc.route_multi(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, top_g, tau,
+                                          scale)
+    for t in range(cfg.T):
+        z = [sum(rc[g][i] * x[t][i] for i in range(cfg.d)) for g in range(cfg.G)]
+        pz = [math.exp(v / tau) for v in z]
+        pz = [v / sum(pz) for v in pz]
+        sel = sorted(range(cfg.G), key=lambda g: (-z[g], g))[:top_g]
+        assert list(cids[t]) == sel
+        wsum = sum(pz[g] for g in sel)
+        got_total = 0.0
+        for a, c in enumerate(sel):
+            l = [sum(re[c * cfg.K + j][i] * x[t][i] for i in range(cfg.d)) for j in range(cfg.K)]
+            top = sorted(range(cfg.K), key=lambda j: (-l[j], j))[:cfg.k]
+            assert list(eidx[t, a]) == [c * cfg.K + j for j in top]
+            ex = [math.exp(l[j] / tau) for j in top]
+            wa = pz[c] if scale else pz[c] / wsum
+            for jj in range(cfg.k):
+                assert gate[t, a, jj] == pytest.approx(wa * ex[jj] / sum(ex), rel=1e-12)
+            got_total += float(gate[t, a].sum())
+        assert got_total == pytest.approx(wsum if scale else 1.0, rel=1e-12)
+
+
+def test_route_multi_temperature_and_full_fanout():
+    cfg = ci.small_config("rmt", T=50, d=32, d_ff=32, G=3, K=4, r=4, k=2, q=8, seed=23)
+    w = ci.generate(cfg)
+    a1 = orc.route_multi(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, 2, 1.0)
+    a2 = orc.route_multi(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, 2, 1e6)
+    # the temperature never changes which clusters / experts are selected; a very large one
+    # flattens the weights: 1 / top_g per cluster, 1 / k inside it
+    assert np.array_equal(a1[0], a2[0]) and np.array_equal(a1[1], a2[1])
+    assert np.allclose(a2[2], 1.0 / (2 * cfg.k), rtol=1e-4)
+    # all clusters selected and scaled by their probability: the weights sum to one
+    full = orc.route_multi(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, cfg.G, 0.7, True)
+    assert np.allclose(full[2].sum(axis=(1, 2)), 1.0, rtol=1e-13)
+
+
+def test_forward_multi_is_sum_of_selected_dense_ffns():
+    cfg = ci.small_config("fm", T=6, d=16, d_ff=32, G=3, K=2, r=4, k=1, q=8, seed=24)
+    w = ci.generate(cfg)
+    out = orc.forward_naive_multi(w, w["x"], cfg.K, cfg.k, cfg.q, top_g=2, temperature=0.7, scale_by_cluster_prob=True)
+    f = None
+    for t in range(cfg.T):
+        acc = np.zeros(cfg.d)
+        for a in range(2):
+            e = int(out["expert_idx"][t, a, 0])
+            W1, W2 = orc.expert_weights(w, e, cfg.K, cfg.q, f)
+            h = W1 @ w["x"][t].astype(np.float64)
+            acc += out["gate"][t, a, 0] * (W2 @ np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in h]))
+        assert np.allclose(out["y"][t], acc, rtol=1e-12, atol=1e-14)
