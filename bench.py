@@ -106,13 +106,26 @@ def run_config(cfg, steps, warmup, want_stats=False):
         stats_ms = layer.timing_read()["route_stats"][0] / steps
         layer.timing_enable(False)
 
+    multi_ms = None
+    if want_stats:
+        # routing variant: two clusters per token, temperature, cluster-probability scaling
+        om = layer.forward_multi(x, 2, 0.7, True)
+        torch.cuda.synchronize()
+        del om
+        t0 = time.perf_counter()
+        for _ in range(max(steps // 2, 3)):
+            om = layer.forward_multi(x, 2, 0.7, True)
+        torch.cuda.synchronize()
+        multi_ms = (time.perf_counter() - t0) / max(steps // 2, 3) * 1e3
+        del om
+
     eidx = out["expert_idx"].cpu().numpy()
     offs = out["offsets"].cpu().numpy()
     clusters_hit = int((np.diff(offs) > 0).sum())
     experts_hit = int(len(np.unique(eidx)))
     layer.close()
     return dict(ms_per_step=ms_per_step, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
-                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms)
+                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms)
 
 
 def roofline(cfg, res, bound, traffic_table):
@@ -255,6 +268,13 @@ def main():
                                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
                                "note": "by-product entry point (loads, load CV, centroid EMA, cluster activity); "
                                        "three launches timed together; not part of ms_per_step"}
+    if res["multi_ms"]:
+        line["forward_multi"] = {"ms": round(res["multi_ms"], 4), "top_g": 2, "temperature": 0.7,
+                                 "scale_by_cluster_prob": True,
+                                 "tokens_per_s": round(cfg.T / (res["multi_ms"] * 1e-3), 1),
+                                 "vs_two_single_cluster_steps": round(res["multi_ms"] / (2 * res["ms_per_step"]), 3),
+                                 "note": "cmoe_forward_multi, workspace allocated per call by the binding (inside "
+                                         "the timed region); 2 T virtual tokens through the same kernels"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
     del res

@@ -155,6 +155,35 @@ int cmoe_route_stats(cmoe_handle *h, const cmoe_f16 *x, int32_t T, const int32_t
                      int32_t *cluster_load, float *i_load, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* ---- Routing variants (Sec. 3.3 "Top-g_1 groups", Sec. 3.5 router temperature) ----
+ * top_g clusters are kept per token (1 <= top_g <= min(G, 8), listed by descending
+ * probability, lowest index on ties) and each contributes its own top_k experts.  Both
+ * softmaxes (Eq. 9, Eq. 10) take logits divided by temperature (> 0); the selection does
+ * not depend on it.  The mixing weight of expert j of the a-th selected cluster is
+ *   gate[t][a][j] = w_a * softmax_j(l_sel / temperature),
+ *   w_a = p_g of Eq. 9 when scale_by_cluster_prob != 0, else p_g renormalised over the
+ *         selected clusters (1 for top_g = 1: then this is cmoe_route with a temperature).
+ * A (token, selected cluster) pair is a "virtual token" vt = t * top_g + a: cluster_id
+ * [T*top_g], expert_idx [T*top_g][top_k], gate [T*top_g][top_k], and perm / inv_perm
+ * [T*top_g] of cmoe_forward_multi are indexed by vt; the permutation is the stable sort of
+ * the virtual tokens by cluster, the shared-base products are computed once per virtual
+ * token, and y[t] is the sum of its top_g virtual tokens' outputs. */
+typedef struct cmoe_route_options {
+  int32_t top_g;
+  float temperature;
+  int32_t scale_by_cluster_prob;
+} cmoe_route_options;
+
+int cmoe_route_multi(cmoe_handle *h, const cmoe_weights *w, const cmoe_route_options *opt,
+                     const cmoe_f16 *x, int32_t T, int32_t *cluster_id, int32_t *expert_idx,
+                     float *gate, void *stream);
+/* Workspace of cmoe_forward_multi for up to T_max tokens (0 for a bad handle or top_g). */
+size_t cmoe_workspace_bytes_multi(const cmoe_handle *h, int32_t T_max, int32_t top_g);
+int cmoe_forward_multi(cmoe_handle *h, const cmoe_weights *w, const cmoe_route_options *opt,
+                       const cmoe_f16 *x, int32_t T, cmoe_f16 *y, int32_t *cluster_id,
+                       int32_t *expert_idx, float *gate, int32_t *perm, int32_t *inv_perm,
+                       int32_t *offsets, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- Construction of the compressed form from dense expert matrices (Sec. 3.2, 3.4) ----
  * One weight matrix of the layer at a time: W [G*K][out_dim][in_dim] f16, experts stored
  * cluster-major (call it once for the first and once for the second matrix of the FFN).

@@ -17,7 +17,7 @@ _lib = None
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
-           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_stats", "cmoe_compress_workspace_bytes",
+           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi", "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes",
            "cmoe_compress", "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_last_hip_error",
            "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
@@ -32,6 +32,10 @@ class CmoeError(RuntimeError):
 class CompressConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("out_dim", "in_dim", "G", "K", "r", "q_group", "sketch", "n_iter",
                                          "use_gate")] + [("gate_gamma", C.c_float)]
+
+
+class RouteOptions(C.Structure):
+    _fields_ = [("top_g", C.c_int32), ("temperature", C.c_float), ("scale_by_cluster_prob", C.c_int32)]
 
 
 class Config(C.Structure):
@@ -66,6 +70,11 @@ def lib():
     L.cmoe_combine.argtypes = [vp, C.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.cmoe_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_route_stats.argtypes = [vp, vp, i32, vp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_route_multi.argtypes = [vp, C.POINTER(Weights), C.POINTER(RouteOptions), vp, i32, vp, vp, vp, vp]
+    L.cmoe_workspace_bytes_multi.argtypes = [vp, i32, i32]
+    L.cmoe_workspace_bytes_multi.restype = sz
+    L.cmoe_forward_multi.argtypes = [vp, C.POINTER(Weights), C.POINTER(RouteOptions), vp, i32, vp, vp, vp, vp, vp, vp,
+                                     vp, vp, sz, vp]
     L.cmoe_compress_workspace_bytes.argtypes = [C.POINTER(CompressConfig)]
     L.cmoe_compress_workspace_bytes.restype = sz
     L.cmoe_compress.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -80,7 +89,7 @@ def lib():
     L.cmoe_timing_name.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
-                        "cmoe_compress_workspace_bytes"):
+                        "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -249,6 +258,39 @@ class Layer:
                                        _ptr(offsets), _ptr(expert_idx), _ptr(gate), T, _ptr(y), _ptr(self.ws),
                                        self.ws.numel(), self._stream()), "cmoe_combine")
         return y
+
+    def route_multi(self, x, top_g=1, temperature=1.0, scale_by_cluster_prob=False):
+        """cmoe_route_multi: (cluster_id [T][top_g], expert_idx [T][top_g][k], gate [T][top_g][k])."""
+        t = self.torch
+        T, k = x.shape[0], self.cfg.top_k
+        opt = RouteOptions(top_g, temperature, int(scale_by_cluster_prob))
+        cid = self._empty((T, top_g), t.int32)
+        eidx = self._empty((T, top_g, k), t.int32)
+        gate = self._empty((T, top_g, k), t.float32)
+        self._check(lib().cmoe_route_multi(self._h, C.byref(self.w), C.byref(opt), _ptr(x), T, _ptr(cid), _ptr(eidx),
+                                           _ptr(gate), self._stream()), "cmoe_route_multi")
+        return cid, eidx, gate
+
+    def forward_multi(self, x, top_g=1, temperature=1.0, scale_by_cluster_prob=False):
+        """cmoe_forward_multi; allocates its own workspace.  Returns a dict like forward(), with the
+        routing outputs per (token, selected cluster) and perm / inv_perm over the virtual tokens."""
+        t = self.torch
+        T, k = x.shape[0], self.cfg.top_k
+        opt = RouteOptions(top_g, temperature, int(scale_by_cluster_prob))
+        nbytes = lib().cmoe_workspace_bytes_multi(self._h, T, top_g)
+        if nbytes == 0:
+            raise CmoeError(-1, "cmoe_workspace_bytes_multi")
+        ws = self._empty((nbytes,), t.uint8)
+        o = dict(y=self._empty((T, self.cfg.d), t.float16), cluster_id=self._empty((T, top_g), t.int32),
+                 expert_idx=self._empty((T, top_g, k), t.int32), gate=self._empty((T, top_g, k), t.float32),
+                 perm=self._empty((T * top_g,), t.int32), inv_perm=self._empty((T * top_g,), t.int32),
+                 offsets=self._empty((self.cfg.G + 1,), t.int32))
+        self._check(lib().cmoe_forward_multi(self._h, C.byref(self.w), C.byref(opt), _ptr(x), T, _ptr(o["y"]),
+                                             _ptr(o["cluster_id"]), _ptr(o["expert_idx"]), _ptr(o["gate"]),
+                                             _ptr(o["perm"]), _ptr(o["inv_perm"]), _ptr(o["offsets"]), _ptr(ws),
+                                             nbytes, self._stream()), "cmoe_forward_multi")
+        o["_workspace"] = ws
+        return o
 
     def route_stats(self, x, perm, offsets, expert_idx, mu, cluster_act, cluster_idle, beta=0.05, lam=0.1):
         """Updates mu [E][d] f32, cluster_act [G] f32, cluster_idle [G] i32 in place; returns

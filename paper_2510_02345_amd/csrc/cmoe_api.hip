@@ -334,6 +334,75 @@ extern "C" int cmoe_combine(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
   return CMOE_OK;
 }
 
+static bool route_opt_ok(const cmoe_handle* h, const cmoe_route_options* o) {
+  return o != nullptr && o->top_g >= 1 && o->top_g <= 8 && o->top_g <= h->dm.G && o->temperature > 0.f &&
+         o->temperature < 1e30f;
+}
+static size_t rep_bytes(const cmoe_dims& dm, size_t Tv) { return align_up(sizeof(half_t) * Tv * dm.d, 256); }
+
+extern "C" int cmoe_route_multi(cmoe_handle* h, const cmoe_weights* w, const cmoe_route_options* opt,
+                                const cmoe_f16* x, int32_t T, int32_t* cluster_id, int32_t* expert_idx, float* gate,
+                                void* stream) {
+  if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
+  if (!route_opt_ok(h, opt) || !weights_route_ok(w)) return CMOE_ERR_INVALID_ARG;
+  if (T == 0) return CMOE_OK;
+  if (!ptr_ok(x) || !ptr_ok(cluster_id) || !ptr_ok(expert_idx) || !ptr_ok(gate)) return CMOE_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  CMOE_LAUNCH(TS_ROUTE, launch_route_multi(h->dm, *w, (const half_t*)x, T, opt->top_g, opt->temperature,
+                                           opt->scale_by_cluster_prob != 0, cluster_id, expert_idx, gate, st));
+  return CMOE_OK;
+}
+
+extern "C" size_t cmoe_workspace_bytes_multi(const cmoe_handle* h, int32_t T_max, int32_t top_g) {
+  if (!handle_ok(h) || T_max < 0 || top_g < 1 || top_g > 8 || top_g > h->dm.G) return 0;
+  if ((int64_t)T_max * top_g > INT32_MAX) return 0;
+  const int Tv = T_max * top_g;
+  return align_up(cmoe_layout(h->dm, Tv).total, 256) + 2 * rep_bytes(h->dm, (size_t)Tv);
+}
+
+extern "C" int cmoe_forward_multi(cmoe_handle* h, const cmoe_weights* w, const cmoe_route_options* opt,
+                                  const cmoe_f16* x, int32_t T, cmoe_f16* y, int32_t* cluster_id,
+                                  int32_t* expert_idx, float* gate, int32_t* perm, int32_t* inv_perm,
+                                  int32_t* offsets, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
+  if (!route_opt_ok(h, opt) || !weights_route_ok(w) || !weights_ffn_ok(w) || !weights_combine_ok(w))
+    return CMOE_ERR_INVALID_ARG;
+  if ((int64_t)T * opt->top_g > INT32_MAX) return CMOE_ERR_UNSUPPORTED;
+  if (!ptr_ok(offsets)) return CMOE_ERR_INVALID_ARG;
+  if (T > 0 && (!ptr_ok(x) || !ptr_ok(y) || !ptr_ok(cluster_id) || !ptr_ok(expert_idx) || !ptr_ok(gate) ||
+                !ptr_ok(perm) || !ptr_ok(inv_perm)))
+    return CMOE_ERR_INVALID_ARG;
+  const int g1 = opt->top_g, Tv = T * g1;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return CMOE_ERR_WORKSPACE;
+  const size_t base_bytes = align_up(cmoe_layout(h->dm, Tv).total, 256), rb = rep_bytes(h->dm, (size_t)Tv);
+  if (workspace_bytes < base_bytes + 2 * rb) return CMOE_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const cmoe_dims& dm = h->dm;
+  char* ws = (char*)workspace;
+  half_t* xrep = (half_t*)(ws + base_bytes);
+  half_t* yrep = (half_t*)(ws + base_bytes + rb);
+  int rc = cmoe_route_multi(h, w, opt, x, T, cluster_id, expert_idx, gate, stream);
+  if (rc != CMOE_OK) return rc;
+  // from here on the virtual tokens are ordinary tokens of the single-cluster path
+  rc = cmoe_permute(h, cluster_id, Tv, perm, inv_perm, offsets, workspace, base_bytes, stream);
+  if (rc != CMOE_OK || T == 0) return rc;
+  CMOE_LAUNCH(TS_ROUTE, launch_repeat_rows((const half_t*)x, T, g1, dm.d, xrep, st));
+  cmoe_ws_layout L = cmoe_layout(dm, Tv);
+  cmoe_f16* yb = (cmoe_f16*)(ws + L.yb);
+  float* s_down = (float*)(ws + L.sdown);
+  bool fused = false;
+  rc = ffn_impl(h, w, (const cmoe_f16*)xrep, Tv, perm, offsets, expert_idx, gate, yb, s_down, (cmoe_f16*)yrep, &fused,
+                workspace, base_bytes, stream);
+  if (rc != CMOE_OK) return rc;
+  if (!fused) {
+    rc = cmoe_combine(h, w, yb, s_down, perm, inv_perm, offsets, expert_idx, gate, Tv, (cmoe_f16*)yrep, workspace,
+                      base_bytes, stream);
+    if (rc != CMOE_OK) return rc;
+  }
+  CMOE_LAUNCH(TS_COMBINE, launch_sum_groups(yrep, T, g1, dm.d, (half_t*)y, st));
+  return CMOE_OK;
+}
+
 extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, const int32_t* perm,
                                 const int32_t* offsets, const int32_t* expert_idx, float beta, float lam, float* mu,
                                 float* cluster_act, int32_t* cluster_idle, int32_t* expert_load,

@@ -101,6 +101,11 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
                           float* s_down, hipStream_t st);
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
                             const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
+hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
+                              float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
+                              hipStream_t st);
+hipError_t launch_repeat_rows(const half_t* x, int T, int top_g, int d, half_t* xrep, hipStream_t st);
+hipError_t launch_sum_groups(const half_t* yrep, int T, int top_g, int d, half_t* y, hipStream_t st);
 hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,
                               int max_rows, half_t* out, hipStream_t st);
 size_t stats_partial_slots(const cmoe_dims& dm, int T);

@@ -106,6 +106,139 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void route_kernel(
   }
 }
 
+// ---------------------------------------------------------------- routing variants
+// Top-g clusters per token (Sec. 3.3, "Top-g_1 groups"), router temperature (Sec. 3.5) and
+// optional scaling by the cluster probability of Eq. 9.  One wavefront per token; lane g
+// keeps z_g, lane j keeps l_j.  Outputs are laid out per (token, selected cluster) pair
+// a = 0..top_g-1, i.e. as top_g "virtual tokens" per token:
+//   cluster_id [T][top_g], expert_idx [T][top_g][k], gate [T][top_g][k]
+// gate = w_a * softmax(l_sel / tau), w_a = p_g (scaled) or p_g / sum of the selected p_g.
+template <int MAXC>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void route_multi_kernel(
+    const half_t* __restrict__ x, const half_t* __restrict__ rc, const half_t* __restrict__ re,
+    const float* __restrict__ bias, int T, int d, int G, int K, int k, int top_g, float inv_tau, int scale,
+    int* __restrict__ cluster_id, int* __restrict__ expert_idx, float* __restrict__ gate) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * ROUTE_WAVES + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const int nchunk = d >> 3;
+  half8 xv[MAXC];
+#pragma unroll
+  for (int i = 0; i < MAXC; ++i) {
+    int ch = lane + 64 * i;
+    xv[i] = (ch < nchunk) ? *(const half8*)(x + (size_t)t * d + ch * 8) : half8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  auto dot = [&](const half_t* v) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+      int ch = lane + 64 * i;
+      if (ch < nchunk) acc = dot8(xv[i], *(const half8*)(v + ch * 8), acc);
+    }
+    return wave_sum(acc);
+  };
+  auto wave_max = [&](float m) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    return m;
+  };
+  // Eq. 9 with temperature: p_g = softmax(z / tau)
+  float zmine = -INFINITY;
+  for (int g = 0; g < G; ++g) {
+    float z = dot(rc + (size_t)g * d);
+    if (bias != nullptr) z += bias[g];
+    if (lane == g) zmine = z;
+  }
+  const float zmax = wave_max(zmine);
+  const float ez = (lane < G) ? expf((zmine - zmax) * inv_tau) : 0.f;
+  const float pz = ez / wave_sum(ez);
+  // the top_g clusters: rounds of (largest logit, lowest lane)
+  int sel_c[8];
+  float sel_p[8];
+  float psum = 0.f;
+  float zrem = zmine;
+#pragma unroll
+  for (int a = 0; a < 8; ++a) {
+    sel_c[a] = 0;
+    sel_p[a] = 0.f;
+    if (a < top_g) {
+      const float m = wave_max(zrem);
+      const int g = __ffsll((long long)__ballot(zrem == m)) - 1;
+      sel_c[a] = g;
+      sel_p[a] = __shfl(pz, g, 64);
+      psum += sel_p[a];
+      if (lane == g) zrem = -INFINITY;
+    }
+  }
+#pragma unroll
+  for (int a = 0; a < 8; ++a) {
+    if (a >= top_g) continue;
+    const int c = sel_c[a];
+    const float wa = scale ? sel_p[a] : sel_p[a] / psum;
+    float mine = -INFINITY;
+    for (int j = 0; j < K; ++j) {
+      const float l = dot(re + (size_t)(c * K + j) * d);
+      if (lane == j) mine = l;
+    }
+    float sel_l[8];
+    int sel_j[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      sel_l[b] = 0.f;
+      sel_j[b] = 0;
+      if (b < k) {
+        const float m = wave_max(mine);
+        const int j = __ffsll((long long)__ballot(mine == m)) - 1;
+        sel_l[b] = m;
+        sel_j[b] = j;
+        if (lane == j) mine = -INFINITY;
+      }
+    }
+    if (lane == 0) {
+      const size_t vt = (size_t)t * top_g + a;
+      cluster_id[vt] = c;
+      float den = 0.f, ex[8];
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        ex[b] = (b < k) ? expf((sel_l[b] - sel_l[0]) * inv_tau) : 0.f;
+        den += ex[b];
+      }
+#pragma unroll
+      for (int b = 0; b < 8; ++b)
+        if (b < k) {
+          expert_idx[vt * k + b] = c * K + sel_j[b];
+          gate[vt * k + b] = wa * (ex[b] / den);
+        }
+    }
+  }
+}
+
+// xrep[vt][:] = x[vt / top_g][:]
+__global__ __launch_bounds__(256) void repeat_rows_kernel(const half_t* __restrict__ x, int top_g, int d,
+                                                          half_t* __restrict__ xrep) {
+  const int vt = blockIdx.y, col = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (col >= d) return;
+  *(half8*)(xrep + (size_t)vt * d + col) = *(const half8*)(x + (size_t)(vt / top_g) * d + col);
+}
+// y[t][:] = sum_a yrep[t top_g + a][:] (FP32, a ascending)
+__global__ __launch_bounds__(256) void sum_groups_kernel(const half_t* __restrict__ yrep, int top_g, int d,
+                                                         half_t* __restrict__ y) {
+  const int t = blockIdx.y, col = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (col >= d) return;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int a = 0; a < top_g; ++a) {
+    const half8 v = *(const half8*)(yrep + ((size_t)t * top_g + a) * d + col);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += (float)v[i];
+  }
+  half8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (half_t)acc[i];
+  *(half8*)(y + (size_t)t * d + col) = o;
+}
+
 // ---------------------------------------------------------------- permutation
 // Pass 1: per-block histogram of cluster ids (LDS integer atomics: order-independent).
 __global__ __launch_bounds__(PERMUTE_BLOCK) void permute_hist_kernel(const int* __restrict__ cluster_id, int T, int G,
@@ -462,5 +595,34 @@ hipError_t launch_permute_bins(int bins, const int* cluster_id, int T, int* perm
   hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(64), 0, st, n_blocks, dm.G, blk_counts, offsets);
   hipLaunchKernelGGL(permute_rank_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
                      blk_counts, perm, inv_perm);
+  return hipGetLastError();
+}
+
+hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
+                              float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
+                              hipStream_t st) {
+  dim3 grid((T + ROUTE_WAVES - 1) / ROUTE_WAVES), block(ROUTE_WAVES * 64);
+  const half_t* rc = (const half_t*)w.router_cluster;
+  const half_t* re = (const half_t*)w.router_expert;
+  const int chunks_per_lane = (dm.d / 8 + 63) / 64;
+  const float inv_tau = 1.f / temperature;
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, grid, block, 0, st, x, rc, re, w.cluster_bias, T, dm.d, dm.G, dm.K, dm.k, top_g, inv_tau,
+                       scale, cluster_id, expert_idx, gate);
+  };
+  if (chunks_per_lane <= 2) go(route_multi_kernel<2>);
+  else if (chunks_per_lane <= 4) go(route_multi_kernel<4>);
+  else if (chunks_per_lane <= 8) go(route_multi_kernel<8>);
+  else go(route_multi_kernel<16>);
+  return hipGetLastError();
+}
+
+hipError_t launch_repeat_rows(const half_t* x, int T, int top_g, int d, half_t* xrep, hipStream_t st) {
+  hipLaunchKernelGGL(repeat_rows_kernel, dim3((d / 8 + 255) / 256, T * top_g), dim3(256), 0, st, x, top_g, d, xrep);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_groups(const half_t* yrep, int T, int top_g, int d, half_t* y, hipStream_t st) {
+  hipLaunchKernelGGL(sum_groups_kernel, dim3((d / 8 + 255) / 256, T), dim3(256), 0, st, yrep, top_g, d, y);
   return hipGetLastError();
 }

@@ -1,0 +1,114 @@
+"""GPU parity of the routing variants (cmoe_route_multi, cmoe_forward_multi, through the C ABI)
+against the FP64 oracle.  Bars as for the single-cluster path: indices and the permutation of
+the virtual tokens bit-exact, gates to 1e-5, outputs max|y - y_ref| <= 1e-2 RMS and mean
+relative error <= 2e-3.  Tokens whose cluster or expert ranking hinges on a logit gap below
+1e-3 are removed from the inputs first (the generator conditions only the single-cluster
+decision)."""
+import numpy as np
+import pytest
+
+import cmoe_inputs as ci
+from oracle import cmoe_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+MAX_OVER_RMS = 1e-2
+MEAN_REL = 2e-3
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _well_separated(w, cfg, top_g, margin=1e-3):
+    """Rows of x whose top_g + 1 cluster logits and, inside every selected cluster, top k + 1
+    expert logits are pairwise at least `margin` apart (FP64)."""
+    x = w["x"].astype(np.float64)
+    z = x @ w["router_cluster"].astype(np.float64).T
+    zs = -np.sort(-z, axis=1)[:, :min(top_g + 1, cfg.G)]
+    ok = np.all(zs[:, :-1] - zs[:, 1:] >= margin, axis=1) if zs.shape[1] > 1 else np.ones(len(x), bool)
+    order = np.argsort(-z, axis=1, kind="stable")[:, :top_g]
+    re = w["router_expert"].astype(np.float64)
+    for a in range(top_g):
+        for c in range(cfg.G):
+            rows = np.nonzero(order[:, a] == c)[0]
+            if len(rows) == 0:
+                continue
+            l = -np.sort(-(x[rows] @ re[c * cfg.K:(c + 1) * cfg.K].T), axis=1)[:, :min(cfg.k + 1, cfg.K)]
+            if l.shape[1] > 1:
+                ok[rows] &= np.all(l[:, :-1] - l[:, 1:] >= margin, axis=1)
+    return np.nonzero(ok)[0]
+
+
+CASES = [
+    # (config, top_g, temperature, scale_by_cluster_prob)
+    (ci.small_config("m_big", T=900, d=128, d_ff=256, G=4, K=4, r=8, k=2, q=32, seed=201), 2, 1.0, False),
+    (ci.small_config("m_big_scaled", T=700, d=128, d_ff=256, G=3, K=4, r=8, k=2, q=32, seed=202), 3, 0.7, True),
+    (ci.small_config("m_stream", T=60, d=64, d_ff=128, G=4, K=2, r=4, k=1, q=16, seed=203), 2, 0.7, False),
+    (ci.small_config("m_temp_only", T=300, d=64, d_ff=128, G=2, K=4, r=4, k=2, q=8, seed=204), 1, 0.5, True),
+]
+
+
+@pytest.mark.parametrize("cfg,top_g,tau,scale", CASES, ids=[c[0].name for c in CASES])
+def test_route_and_forward_multi(cfg, top_g, tau, scale):
+    import torch
+    import paper_2510_02345_amd as cm
+    print(f"case {cfg} top_g={top_g} tau={tau} scale={scale}", flush=True)
+    w = ci.generate(cfg)
+    keep = _well_separated(w, cfg, top_g)
+    assert len(keep) >= 0.8 * cfg.T
+    w["x"] = np.ascontiguousarray(w["x"][keep])
+    T = len(keep)
+    ref = orc.forward_naive_multi(w, w["x"], cfg.K, cfg.k, cfg.q, top_g, tau, scale)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, T * top_g)
+    x = _dev(w["x"])
+    cid, eidx, gate = layer.route_multi(x, top_g, tau, scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(cid.cpu().numpy(), ref["cluster_ids"])
+    assert np.array_equal(eidx.cpu().numpy(), ref["expert_idx"])
+    assert np.allclose(gate.cpu().numpy(), ref["gate"], rtol=1e-5, atol=1e-7)
+    out = layer.forward_multi(x, top_g, tau, scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["cluster_ids"])
+    assert np.array_equal(out["expert_idx"].cpu().numpy(), ref["expert_idx"])
+    offsets, perm, inv = orc.permute(ref["cluster_ids"].reshape(-1), cfg.G)       # virtual tokens
+    assert np.array_equal(out["offsets"].cpu().numpy(), offsets)
+    assert np.array_equal(out["perm"].cpu().numpy(), perm)
+    assert np.array_equal(out["inv_perm"].cpu().numpy(), inv)
+    y = out["y"].cpu().numpy()
+    m = orc.error_metrics(y, ref["y"])
+    print(f"forward_multi: max/rms={m['max_over_rms']:.3e} mean_rel={m['mean_rel']:.3e}", flush=True)
+    assert np.all(np.isfinite(y.astype(np.float64)))
+    assert m["max_over_rms"] <= MAX_OVER_RMS and m["mean_rel"] <= MEAN_REL
+    layer.close()
+
+
+def test_top_g_one_equals_forward():
+    import torch
+    import paper_2510_02345_amd as cm
+    cfg = ci.small_config("m_same", T=500, d=128, d_ff=256, G=3, K=4, r=8, k=2, q=32, seed=205)
+    w = ci.generate(cfg)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T)
+    x = _dev(w["x"])
+    a = layer.forward(x)
+    b = layer.forward_multi(x, 1, 1.0, False)
+    torch.cuda.synchronize()
+    assert torch.equal(a["expert_idx"], b["expert_idx"][:, 0])
+    assert torch.allclose(a["gate"], b["gate"][:, 0], rtol=1e-6, atol=1e-7)
+    assert torch.equal(a["perm"], b["perm"])
+    ya, yb = a["y"].float().cpu().numpy(), b["y"].float().cpu().numpy()
+    assert orc.error_metrics(yb, ya)["max_over_rms"] <= 2e-3     # two FP16 roundings apart at most
+    layer.close()
+
+
+def test_route_multi_rejects_bad_options():
+    import paper_2510_02345_amd as cm
+    cfg = ci.small_config("m_bad", T=8, d=64, d_ff=64, G=2, K=2, r=4, k=1, q=8, seed=206)
+    w = ci.generate(cfg)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T)
+    x = _dev(w["x"])
+    for bad in ((3, 1.0), (0, 1.0), (1, 0.0), (1, -1.0)):       # top_g > G, top_g < 1, temperature <= 0
+        with pytest.raises(cm.CmoeError):
+            layer.route_multi(x, bad[0], bad[1], False)
+    layer.close()
