@@ -916,7 +916,8 @@ hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* 
 // Matrix-core router for large T (G + G*K logits per token fit one 128-row tile).
 hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
                              int* expert_idx, float* gate, hipStream_t st) {
-  using TL = TileMain;
+  // 128-token tiles: twice the workgroups of TileMain for this short, x-streaming launch
+  using TL = Tile<128, 128, 1, 4, 3, 2, false, 8, 8>;
   const int rows = dm.G + dm.G * dm.K;
   GemmArgs g{(const half_t*)w.router_cluster, 0, dm.d, rows, x, dm.d, nullptr, dm.d, nullptr, 1, 1, 0, 0,
              (const half_t*)w.router_expert, dm.G, T};
