@@ -93,3 +93,45 @@ def test_timing_names():
     L = cm.lib()
     names = [L.cmoe_timing_name(i).decode() for i in range(8)]
     assert names[0] == "route" and "gemm1_fused" in names and L.cmoe_timing_name(99) == b""
+
+
+def test_new_entry_points_reject_bad_arguments_without_touching_the_gpu():
+    rc, h = _create()
+    L = cm.lib()
+    fake = 0x1000
+    w2 = B.Weights(*([fake] * 13))
+    # routing statistics: EMA rates outside [0, 1], missing state, workspace
+    args = [h, fake, 8, fake, fake, fake]
+    tail = [fake, fake, fake, fake, fake, fake]
+    assert L.cmoe_route_stats(*args, 1.5, 0.1, *tail, fake, 1 << 30, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route_stats(*args, 0.05, -0.1, *tail, fake, 1 << 30, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route_stats(*args, 0.05, 0.1, None, fake, fake, fake, fake, fake, fake, 1 << 30, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route_stats(*args, 0.05, 0.1, *tail, fake, 16, None) == B.ERR_WORKSPACE
+    # routing variants: top_g beyond G or 8, non-positive temperature
+    for top_g, tau in ((0, 1.0), (3, 1.0), (9, 1.0), (1, 0.0), (2, -1.0)):
+        opt = B.RouteOptions(top_g, tau, 0)
+        assert L.cmoe_route_multi(h, C.byref(w2), C.byref(opt), fake, 4, fake, fake, fake, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_route_multi(h, C.byref(w2), None, fake, 4, fake, fake, fake, None) == B.ERR_INVALID_ARG
+    ok = B.RouteOptions(2, 0.7, 1)
+    assert L.cmoe_route_multi(h, C.byref(w2), C.byref(ok), fake, 0, fake, fake, fake, None) == B.OK   # T = 0 no-op
+    assert L.cmoe_workspace_bytes_multi(h, 1024, 3) == 0 and L.cmoe_workspace_bytes_multi(h, 1024, 0) == 0
+    assert L.cmoe_workspace_bytes_multi(h, 1024, 2) > L.cmoe_workspace_bytes(h, 2048)
+    assert L.cmoe_forward_multi(h, C.byref(w2), C.byref(ok), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake,
+                                16, None) == B.ERR_WORKSPACE
+    L.cmoe_destroy(h)
+    # compression: shapes outside the supported set give no workspace size and are refused
+    good = B.CompressConfig(256, 128, 2, 4, 8, 32, 16, 2, 0, 0.0)
+    assert L.cmoe_compress_workspace_bytes(C.byref(good)) > 2 * 8 * 256 * 128 * 2        # Delta and its transpose
+    for bad in (B.CompressConfig(250, 128, 2, 4, 8, 32, 16, 2, 0, 0.0),      # out_dim not a multiple of 64
+                B.CompressConfig(256, 128, 2, 4, 8, 48, 16, 2, 0, 0.0),      # q_group does not divide
+                B.CompressConfig(256, 128, 2, 4, 8, 32, 4, 2, 0, 0.0),       # sketch narrower than r
+                B.CompressConfig(256, 128, 2, 4, 8, 32, 64, 2, 0, 0.0),      # sketch wider than 48
+                B.CompressConfig(256, 128, 2, 4, 40, 32, 48, 2, 0, 0.0)):    # r > 32
+        assert L.cmoe_compress_workspace_bytes(C.byref(bad)) == 0
+        assert L.cmoe_compress(C.byref(bad), fake, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 40,
+                               None) == B.ERR_UNSUPPORTED
+    assert L.cmoe_compress(C.byref(good), None, fake, fake, fake, fake, fake, fake, fake, fake, 1 << 40,
+                           None) == B.ERR_INVALID_ARG
+    assert L.cmoe_compress(C.byref(good), fake, fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == B.ERR_WORKSPACE
+    assert L.cmoe_quantize_int4(fake, 4, 64, 24, fake, fake, None) == B.ERR_INVALID_ARG    # q does not divide L
+    assert L.cmoe_quantize_int4(fake, 0, 64, 8, fake, fake, None) == B.OK                  # no rows: no-op
