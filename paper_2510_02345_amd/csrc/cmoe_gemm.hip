@@ -769,12 +769,12 @@ __global__ __launch_bounds__(CB_WAVES * 64) void combine_kernel(
   }
 }
 
-// Fused up-projection: 128 weight rows x 256 tokens per workgroup, four wavefronts side by
-// side along the tokens (each 128 x 64), two workgroups per CU so that one's epilogue
-// (VALU-heavy) overlaps the other's main loop (matrix core).
+// Products with at most 128 weight rows (t1 = V1 x over the cluster's rank rows): 128 x 256
+// per workgroup, four wavefronts side by side along the tokens (each 128 x 64), two
+// workgroups per CU.
 using TileMain = Tile<128, 256, 1, 4, 3, 2, false, 8, 8>;
-// Plain down-projection: 256 x 256 per workgroup, eight wavefronts (2 x 4, each 128 x 64)
-// in ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
+// The two big products: 256 x 256 per workgroup, eight wavefronts (2 x 4, each 128 x 64) in
+// ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
 using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
 using TileUp = TileBig;  // tile of the fused up-projection
 static_assert(TileUp::WN == G1_BN, "workspace sizing assumes one s partial per G1_BN rows");

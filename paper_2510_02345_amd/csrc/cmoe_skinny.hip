@@ -33,7 +33,7 @@ __device__ __forceinline__ void wait_vm() {
 }
 
 constexpr int SK_COLS = 16;                         // tokens per pass over a cluster
-constexpr int SK_A_BYTES = SK_ROWS * 128;           // 64 weight rows x 64 elements
+constexpr int SK_A_BYTES = SK_ROWS * 128;           // weight rows x 64 elements
 constexpr int SK_B_BYTES = SK_COLS * 128;           // 16 token rows x 64 elements
 constexpr int SK_STAGE = SK_A_BYTES + SK_B_BYTES;   // one wavefront stage
 constexpr int SK_RING = 2 * SK_STAGE;               // two stages per wavefront

@@ -117,6 +117,11 @@ SMALL = [
     ci.small_config("max_rank", T=300, d=64, d_ff=128, G=1, K=16, r=32, k=2, q=8, seed=55),
     # exactly at and just above the switch between the two paths
     ci.small_config("switch_256", T=256, d=64, d_ff=192, G=3, K=4, r=8, k=2, q=8, seed=56),
+    # the widest supported model dimension and cluster count, both paths
+    ci.small_config("max_d_big", T=300, d=8192, d_ff=128, G=64, K=2, r=4, k=2, q=128, seed=57),
+    ci.small_config("max_d_stream", T=50, d=8192, d_ff=128, G=64, K=2, r=4, k=2, q=128, seed=58),
+    # k = 8 of K = 32 experts per cluster (the largest top-k), large-T path
+    ci.small_config("k8_of_32", T=400, d=64, d_ff=128, G=2, K=32, r=4, k=8, q=8, seed=59),
 ]
 
 
