@@ -568,7 +568,7 @@ struct EpiFusedUp {
 
   template <class TL>
   __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
-    static_assert(TL::WN == G1_BN, "one s partial per wavefront row range of G1_BN rows");
+    static_assert(TL::BN == G1_BN && TL::WAVES_N == 2, "one s partial per tile of G1_BN rows, summed over its two wavefront columns");
     const int h = t.lane >> 5, ml = t.lane & 31;
     const half_t* u1c = u1t + (size_t)t.c * d_ff * KRp;
     const half_t* v2c = v2p + (size_t)t.c * KRp * d_ff;
@@ -660,7 +660,27 @@ struct EpiFusedUp {
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
       }
-      FU::store_s(tk[b], sacc, spart + (size_t)(t.n_tile * TL::WAVES_N + t.wn) * T * k * R, k, h);
+      // the two wavefronts that share these tokens (wn = 0, 1) add their partial s through
+      // LDS, one expert slot at a time, in the patches of the output transposition (free
+      // once every wavefront has left the loop above); wn = 0 stores the tile's partial
+      float* xs = (float*)((char*)t.smem + panel_bytes<TL>()) + t.wm * (16 * 64);
+      static_assert(TL::NWAVES * OT_BYTES >= TL::WAVES_M * 16 * 64 * 4, "exchange area");
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) {
+        if (j >= k) continue;
+        if (t.wn == 1) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) xs[v * 64 + t.lane] = sacc[j][v];
+        }
+        __syncthreads();
+        if (t.wn == 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sacc[j][v] += xs[v * 64 + t.lane];
+        }
+        __syncthreads();
+      }
+      if (t.wn == 0) FU::store_s(tk[b], sacc, spart + (size_t)t.n_tile * T * k * R, k, h);
     }
   }
 };
@@ -777,7 +797,7 @@ using TileMain = Tile<128, 256, 1, 4, 3, 2, false, 8, 8>;
 // ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
 using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
 using TileUp = TileBig;  // tile of the fused up-projection
-static_assert(TileUp::WN == G1_BN, "workspace sizing assumes one s partial per G1_BN rows");
+static_assert(TileUp::BN == G1_BN, "workspace sizing assumes one s partial per G1_BN rows");
 
 // Leftover row tiles of the 256 x 256 schedule: 128 x 128, eight wavefronts (2 x 4, each
 // 64 x 32).  Four of them replace one big tile, so a last round that would occupy a

@@ -71,7 +71,7 @@ struct cmoe_ws_layout {
 };
 
 static const int PERMUTE_BLOCK = 1024;  // tokens per workgroup in the permutation kernels
-static const int G1_BN = 128;           // rows of d_ff per workgroup tile in the fused up-projection
+static const int G1_BN = 256;           // rows of d_ff per workgroup tile (= per s partial) in the fused up-projection
 static const int SKINNY_T = 256;        // at most this many tokens: weight-streaming kernels
 static const int SKINNY_SN = 2048;      // columns of d_ff per s partial in the weight-streaming path
 
