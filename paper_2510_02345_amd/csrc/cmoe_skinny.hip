@@ -32,12 +32,18 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-constexpr int SK_COLS = 16;                         // tokens per pass over a cluster
+constexpr int SK_COLS = 16;                         // tokens per pass over a cluster (layer path)
 constexpr int SK_A_BYTES = SK_ROWS * 128;           // weight rows x 64 elements
-constexpr int SK_B_BYTES = SK_COLS * 128;           // 16 token rows x 64 elements
-constexpr int SK_STAGE = SK_A_BYTES + SK_B_BYTES;   // one wavefront stage
-constexpr int SK_RING = 2 * SK_STAGE;               // two stages per wavefront
-constexpr int SK_DMA = (SK_ROWS + SK_COLS) / 8;     // 1-KiB loads per stage (8 rows x 128 B each)
+// Ring geometry of one wavefront for COLS token rows per pass (16, or 32 when the caller
+// has more than 16 rows per group: all 32 accumulator columns are then distinct).
+template <int COLS>
+struct SkRing {
+  static constexpr int B_BYTES = COLS * 128;            // token rows x 64 elements
+  static constexpr int STAGE = SK_A_BYTES + B_BYTES;    // one wavefront stage
+  static constexpr int RING = 2 * STAGE;                // two stages per wavefront
+  static constexpr int DMA = (SK_ROWS + COLS) / 8;      // 1-KiB loads per stage (8 rows x 128 B each)
+  static constexpr int OCC = COLS == 16 ? SK_OCC : 2;   // workgroups per CU that fit the LDS
+};
 
 // acc[rb] += sum_k W[row(rb)][k] X[col][k] over the 64-element steps [it0, it1) of this
 // wavefront.  Both operands stream global -> LDS one step ahead of the matrix-core work,
@@ -45,12 +51,14 @@ constexpr int SK_DMA = (SK_ROWS + SK_COLS) / 8;     // 1-KiB loads per stage (8 
 // barrier is needed, only vmcnt), chunks XOR-swizzled with (row >> 1) & 7.
 //   wrow / brow: the lane's row (lane / 8) of the first 8-row group of the weight / token
 //                tile at step 0, WITHOUT the chunk offset (the swizzle depends on the row);
-//                w_stride / b_stride: elements between 8-row groups (token rows beyond the
-//                pass are clamped by the caller through brow1)
-// Accumulator columns 16..31 repeat columns 0..15.
-__device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_stride, const half_t* brow0,
-                                              const half_t* brow1, char* ring, unsigned ring_lds, int lane, int it0,
-                                              int it1, float16v (&acc)[SK_RB]) {
+//                w_stride: elements between 8-row groups; brow[i]: the lane's row of token
+//                row group i (rows beyond the pass are clamped by the caller)
+// With COLS = 16 accumulator columns 16..31 repeat columns 0..15.
+template <int COLS>
+__device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_stride,
+                                              const half_t* const (&brow)[COLS / 8], char* ring, unsigned ring_lds,
+                                              int lane, int it0, int it1, float16v (&acc)[SK_RB]) {
+  using RG = SkRing<COLS>;
   if (it0 >= it1) return;
   const int fr = lane & 31, h = lane >> 5;
   int offa[SK_RB][4], offb[4];
@@ -61,22 +69,23 @@ __device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_strid
       const int row = rb * 32 + fr;
       offa[rb][s] = row * 128 + (((2 * s + h) ^ ((row >> 1) & 7)) << 4);
     }
-    const int brow = fr & (SK_COLS - 1);
-    offb[s] = SK_A_BYTES + brow * 128 + (((2 * s + h) ^ ((brow >> 1) & 7)) << 4);
+    const int br = fr & (COLS - 1);
+    offb[s] = SK_A_BYTES + br * 128 + (((2 * s + h) ^ ((br >> 1) & 7)) << 4);
   }
   // lane l of load i fills row 8i + l/8, chunk position l%8, with source chunk position ^ swizzle(row)
   const int lrow = lane >> 3, lpos = lane & 7;
   const int c0 = (lpos ^ (lrow >> 1)) << 3, c1 = (lpos ^ (lrow >> 1) ^ 4) << 3;  // even / odd groups
   auto issue = [&](int it, int stage) {
-    const unsigned dst = ring_lds + stage * SK_STAGE;
+    const unsigned dst = ring_lds + stage * RG::STAGE;
 #pragma unroll
     for (int i = 0; i < SK_ROWS / 8; ++i)
       dma16(wrow + ((i & 1) ? c1 : c0) + (size_t)i * w_stride + (size_t)it * 64, dst + i * 1024);
-    dma16(brow0 + c0 + (size_t)it * 64, dst + SK_A_BYTES);
-    dma16(brow1 + c1 + (size_t)it * 64, dst + SK_A_BYTES + 1024);
+#pragma unroll
+    for (int i = 0; i < COLS / 8; ++i)
+      dma16(brow[i] + ((i & 1) ? c1 : c0) + (size_t)it * 64, dst + SK_A_BYTES + i * 1024);
   };
   auto compute = [&](int stage) {
-    const char* sb = ring + stage * SK_STAGE;
+    const char* sb = ring + stage * RG::STAGE;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       half8 fa[SK_RB];
@@ -92,7 +101,7 @@ __device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_strid
   for (int it = it0; it < it1; it += 2) {
     if (it + 1 < it1) {
       issue(it + 1, 1);
-      wait_vm<SK_DMA>();
+      wait_vm<RG::DMA>();
     } else {
       wait_vm<0>();
     }
@@ -100,7 +109,7 @@ __device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_strid
     if (it + 1 < it1) {
       if (it + 2 < it1) {
         issue(it + 2, 0);
-        wait_vm<SK_DMA>();
+        wait_vm<RG::DMA>();
       } else {
         wait_vm<0>();
       }
@@ -133,8 +142,8 @@ struct SkinnyTile {
   int c, n0, m0, m_end;
 };
 // Stream workgroup `id` of a launch of nx row blocks x G clusters x passes (row block
-// fastest); a pass covers SK_COLS tokens of the cluster, m_end is the end of the pass.
-__device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, int G, SkinnyTile& t) {
+// fastest); a pass covers `cols` tokens of the cluster, m_end is the end of the pass.
+__device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, int G, int cols, SkinnyTile& t) {
   int xb = id % nx;
   const int yz = id / nx;
   t.c = yz % G;
@@ -147,8 +156,8 @@ __device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, 
   if ((nx & 7) == 0 && xb < (nx & ~63)) xb = (xb & ~63) + ((xb & 7) << 3) + ((xb >> 3) & 7);
   t.n0 = xb * SK_ROWS;
   const int lo = offsets[t.c], hi = offsets[t.c + 1];
-  t.m0 = lo + pass * SK_COLS;
-  t.m_end = min(hi, t.m0 + SK_COLS);
+  t.m0 = lo + pass * cols;
+  t.m_end = min(hi, t.m0 + cols);
   return t.m0 < hi;
 }
 
@@ -290,8 +299,8 @@ struct SideArgs {
 // through perm, out = Hb; down-projection with W = W2_base, X = A, out = y_base_sorted.
 // N: rows of W per cluster, Kc: contraction length, gather: row index of X per sorted row
 // or NULL for the identity.
-template <int SIDE>
-__global__ __launch_bounds__(256, SK_OCC) void skinny_base_kernel(const half_t* __restrict__ X,
+template <int SIDE, int COLS>
+__global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(const half_t* __restrict__ X,
                                                                   const int* __restrict__ gather,
                                                                   const half_t* __restrict__ W,
                                                                   const int* __restrict__ offsets, int N, int Kc,
@@ -310,36 +319,37 @@ __global__ __launch_bounds__(256, SK_OCC) void skinny_base_kernel(const half_t* 
     return;
   }
   constexpr int RED_BYTES = SK_WAVES * SK_RB * 16 * 64 * 4;
-  constexpr int RINGS = SK_WAVES * SK_RING;
+  using RG = SkRing<COLS>;
+  constexpr int RINGS = SK_WAVES * RG::RING;
   __shared__ __attribute__((aligned(1024))) char smem[RED_BYTES > RINGS ? RED_BYTES : RINGS];
   float* red = (float*)smem;
   SkinnyTile t;
-  if (!skinny_tile(offsets, (int)blockIdx.x - (SIDE != SIDE_NONE ? sa.n_side : 0), nx, G, t)) return;
+  if (!skinny_tile(offsets, (int)blockIdx.x - (SIDE != SIDE_NONE ? sa.n_side : 0), nx, G, COLS, t)) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, fr = lane & 31, h = lane >> 5;
   const int wv = __builtin_amdgcn_readfirstlane(wave);
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
   const int lrow = lane >> 3;
   const half_t* wrow = W + ((size_t)t.c * N + t.n0 + lrow) * Kc;
   const int p = t.m0 + fr;
-  int r0 = min(t.m0 + lrow, t.m_end - 1), r1 = min(t.m0 + 8 + lrow, t.m_end - 1);
-  if (gather != nullptr) {
-    r0 = gather[r0];
-    r1 = gather[r1];
+  const half_t* brow[COLS / 8];
+#pragma unroll
+  for (int i = 0; i < COLS / 8; ++i) {
+    int r = min(t.m0 + 8 * i + lrow, t.m_end - 1);
+    if (gather != nullptr) r = gather[r];
+    brow[i] = X + (size_t)r * Kc;
   }
-  const half_t* brow0 = X + (size_t)r0 * Kc;
-  const half_t* brow1 = X + (size_t)r1 * Kc;
   float16v acc[SK_RB];
 #pragma unroll
   for (int rb = 0; rb < SK_RB; ++rb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
   const int iters = Kc / 64;
-  skinny_stream(wrow, (size_t)8 * Kc, brow0, brow1, smem + wv * SK_RING, smem_lds + wv * SK_RING, lane,
+  skinny_stream<COLS>(wrow, (size_t)8 * Kc, brow, smem + wv * RG::RING, smem_lds + wv * RG::RING, lane,
                 wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
   __syncthreads();  // every ring has been consumed: its space becomes red
   float16v hb;
   skinny_reduce(red, wave, lane, acc, hb);
-  if (wave < SK_RB && fr < SK_COLS && p < t.m_end) {
+  if (wave < SK_RB && fr < COLS && p < t.m_end) {
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd)
       *(half4*)(out + (size_t)p * N + t.n0 + wave * 32 + 8 * qd + 4 * h) = to_half4(hb, qd);
@@ -589,7 +599,7 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
   dim3 block(256);
   SideArgs sa{};
   if (t1 == nullptr) {
-    hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3(n_stream), block, 0, st, x, perm,
+    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, x, perm,
                        (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
     return hipGetLastError();
   }
@@ -606,7 +616,7 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
   sa.k = dm.k;
   sa.n_jobs = T * dm.k;
   sa.n_side = (sa.n_jobs + 7) & ~7;
-  hipLaunchKernelGGL(skinny_base_kernel<SIDE_T1>, dim3(n_stream + sa.n_side), block, 0, st, x, perm,
+  hipLaunchKernelGGL((skinny_base_kernel<SIDE_T1, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, x, perm,
                      (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
   return hipGetLastError();
 }
@@ -638,7 +648,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   dim3 block(256);
   SideArgs sa{};
   if (ures == nullptr) {
-    hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3(n_stream), block, 0, st, a, (const int*)nullptr,
+    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, a, (const int*)nullptr,
                        (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
     return hipGetLastError();
   }
@@ -657,7 +667,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   sa.n_parts = n_parts;
   sa.n_jobs = T * ((dm.d + 2047) / 2048);
   sa.n_side = (sa.n_jobs + 7) & ~7;
-  hipLaunchKernelGGL(skinny_base_kernel<SIDE_URES>, dim3(n_stream + sa.n_side), block, 0, st, a, (const int*)nullptr,
+  hipLaunchKernelGGL((skinny_base_kernel<SIDE_URES, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, a, (const int*)nullptr,
                      (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
   return hipGetLastError();
 }
@@ -667,10 +677,16 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
 // layer (the compression pipeline streams residual matrices against sketch rows).
 hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,
                               int max_rows, half_t* out, hipStream_t st) {
-  const int passes = (max_rows + SK_COLS - 1) / SK_COLS, nx = N / SK_ROWS;
+  const int nx = N / SK_ROWS;
   SideArgs sa{};
-  hipLaunchKernelGGL(skinny_base_kernel<SIDE_NONE>, dim3((unsigned)nx * n_groups * passes), dim3(256), 0, st, X,
-                     (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+  if (max_rows > 16) {
+    const int passes = (max_rows + 31) / 32;
+    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, 32>), dim3((unsigned)nx * n_groups * passes), dim3(256), 0, st, X,
+                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+  } else {
+    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, 16>), dim3((unsigned)nx * n_groups), dim3(256), 0, st, X,
+                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+  }
   return hipGetLastError();
 }
 
