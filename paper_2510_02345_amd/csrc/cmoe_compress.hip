@@ -19,84 +19,88 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr int CP_LMAX = 48;   // widest sketch
 
-// ---------------------------------------------------------------- Eq. 6
-// base[c][i] = f16( (sum_j f32(W[cK + j][i])) / K ), experts in index order.
-__global__ __launch_bounds__(256) void cmp_mean_kernel(const half_t* __restrict__ W, int K, size_t mat_elems,
-                                                       half_t* __restrict__ base) {
-  const int c = blockIdx.y;
-  const size_t i8 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
-  if (i8 >= mat_elems) return;
-  float acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  for (int j = 0; j < K; ++j) {
-    const half8 v = *(const half8*)(W + ((size_t)c * K + j) * mat_elems + i8);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] += (float)v[i];
-  }
-  const float kf = (float)K;
-  half8 o;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) o[i] = (half_t)(acc[i] / kf);
-  *(half8*)(base + (size_t)c * mat_elems + i8) = o;
-}
-
-// ---------------------------------------------------------------- residual, its transpose, norms
-// One 64 x 64 tile of expert e: D = f16(W - base), DT = D^T, and the tile's share of
-// sum D^2, sum D base, sum base^2, sum W^2 (FP32, fixed order) -> part[e][tile][4].
-__global__ __launch_bounds__(256) void cmp_residual_kernel(const half_t* __restrict__ W,
-                                                           const half_t* __restrict__ base, int K, int out_d,
-                                                           int in_d, half_t* __restrict__ D,
+// ---------------------------------------------------------------- base, residuals, their transposes, norms
+// One 64 x 64 tile of cluster c: the base tile (Eq. 6: FP32 sum of the K experts in index
+// order, divided by K, rounded to FP16), then for each expert e of the cluster
+// D = f16(W_e - base), DT = D^T, and the tile's share of sum D^2, sum D base, sum base^2,
+// sum W_e^2 (FP32, fixed order) -> part[e][tile][4].  The experts' tiles are read twice,
+// the second time from cache.
+__global__ __launch_bounds__(256) void cmp_residual_kernel(const half_t* __restrict__ W, int K, int out_d, int in_d,
+                                                           half_t* __restrict__ base, half_t* __restrict__ D,
                                                            half_t* __restrict__ DT, float* __restrict__ part) {
   __shared__ half_t tile[64][72];
   __shared__ float red[4][4];
-  const int e = blockIdx.z, c = e / K;
+  const int c = blockIdx.z;
   const int o0 = blockIdx.y * 64, i0 = blockIdx.x * 64;
   const int tid = threadIdx.x;
   const size_t me = (size_t)out_d * in_d;
-  float s_dd = 0.f, s_db = 0.f, s_bb = 0.f, s_ww = 0.f;
+  const size_t tix = (size_t)blockIdx.y * gridDim.x + blockIdx.x, nt = (size_t)gridDim.x * gridDim.y;
+  size_t off[2];
+  float bsum[2][8];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int row = (tid >> 3) + 32 * u, ch = tid & 7;   // 8 columns per thread
-    const size_t off = (size_t)(o0 + row) * in_d + i0 + ch * 8;
-    const half8 w8 = *(const half8*)(W + (size_t)e * me + off);
-    const half8 b8 = *(const half8*)(base + (size_t)c * me + off);
-    half8 d8;
+    off[u] = (size_t)(o0 + row) * in_d + i0 + ch * 8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float w = (float)w8[i], b = (float)b8[i];
-      d8[i] = (half_t)(w - b);
-      const float dv = (float)d8[i];
-      s_dd = fmaf(dv, dv, s_dd);
-      s_db = fmaf(dv, b, s_db);
-      s_bb = fmaf(b, b, s_bb);
-      s_ww = fmaf(w, w, s_ww);
-    }
-    *(half8*)(D + (size_t)e * me + off) = d8;
-    *(half8*)(&tile[row][ch * 8]) = d8;
+    for (int i = 0; i < 8; ++i) bsum[u][i] = 0.f;
   }
-  __syncthreads();
+  for (int j = 0; j < K; ++j)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const half8 w8 = *(const half8*)(W + ((size_t)c * K + j) * me + off[u]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) bsum[u][i] += (float)w8[i];
+    }
+  const float kf = (float)K;
+  half8 b8[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int irow = (tid >> 3) + 32 * u, ch = tid & 7;   // row of the transposed tile
-    half8 t8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) t8[i] = tile[ch * 8 + i][irow];
-    *(half8*)(DT + (size_t)e * me + (size_t)(i0 + irow) * out_d + o0 + ch * 8) = t8;
+    for (int i = 0; i < 8; ++i) b8[u][i] = (half_t)(bsum[u][i] / kf);
+    *(half8*)(base + (size_t)c * me + off[u]) = b8[u];
   }
-  // workgroup sums in a fixed order: lanes by halving, then the four wavefronts
-  float v[4] = {s_dd, s_db, s_bb, s_ww};
+  for (int j = 0; j < K; ++j) {
+    const int e = c * K + j;
+    float s_dd = 0.f, s_db = 0.f, s_bb = 0.f, s_ww = 0.f;
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+    for (int u = 0; u < 2; ++u) {
+      const int row = (tid >> 3) + 32 * u, ch = tid & 7;
+      const half8 w8 = *(const half8*)(W + (size_t)e * me + off[u]);
+      half8 d8;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v[a] += __shfl_xor(v[a], off, 64);
-  if ((tid & 63) == 0)
+      for (int i = 0; i < 8; ++i) {
+        const float w = (float)w8[i], b = (float)b8[u][i];
+        d8[i] = (half_t)(w - b);
+        const float dv = (float)d8[i];
+        s_dd = fmaf(dv, dv, s_dd);
+        s_db = fmaf(dv, b, s_db);
+        s_bb = fmaf(b, b, s_bb);
+        s_ww = fmaf(w, w, s_ww);
+      }
+      *(half8*)(D + (size_t)e * me + off[u]) = d8;
+      *(half8*)(&tile[row][ch * 8]) = d8;
+    }
+    __syncthreads();
 #pragma unroll
-    for (int a = 0; a < 4; ++a) red[tid >> 6][a] = v[a];
-  __syncthreads();
-  if (tid < 4) {
-    const size_t t = (size_t)blockIdx.y * gridDim.x + blockIdx.x, nt = (size_t)gridDim.x * gridDim.y;
-    part[((size_t)e * nt + t) * 4 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+    for (int u = 0; u < 2; ++u) {
+      const int irow = (tid >> 3) + 32 * u, ch = tid & 7;   // row of the transposed tile
+      half8 t8;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t8[i] = tile[ch * 8 + i][irow];
+      *(half8*)(DT + (size_t)e * me + (size_t)(i0 + irow) * out_d + o0 + ch * 8) = t8;
+    }
+    // workgroup sums in a fixed order: lanes by halving, then the four wavefronts
+    float v[4] = {s_dd, s_db, s_bb, s_ww};
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int o2 = 32; o2 > 0; o2 >>= 1) v[a] += __shfl_xor(v[a], o2, 64);
+    if ((tid & 63) == 0)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) red[tid >> 6][a] = v[a];
+    __syncthreads();   // also: every thread has read the transposed tile
+    if (tid < 4) part[((size_t)e * nt + tix) * 4 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+    __syncthreads();
   }
 }
 
@@ -534,7 +538,6 @@ extern "C" int cmoe_compress(const cmoe_compress_config* cfg, const cmoe_f16* W,
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
   const int E = c.G * c.K, l = c.sketch, out_d = c.out_dim, in_d = c.in_dim;
-  const size_t me = (size_t)out_d * in_d;
   const int tx = in_d / 64, ty = out_d / 64;
   half_t* D = (half_t*)(ws + L.D);
   half_t* DT = (half_t*)(ws + L.DT);
@@ -548,11 +551,9 @@ extern "C" int cmoe_compress(const cmoe_compress_config* cfg, const cmoe_f16* W,
   float* UF = (float*)(ws + L.UF);
   float* VF = (float*)(ws + L.VF);
 
-  // Eq. 6, then the residuals (and their transposes) against the stored base
-  hipLaunchKernelGGL(cmp_mean_kernel, dim3((unsigned)((me / 8 + 255) / 256), c.G), dim3(256), 0, st, (const half_t*)W,
-                     c.K, me, (half_t*)base);
-  hipLaunchKernelGGL(cmp_residual_kernel, dim3(tx, ty, E), dim3(256), 0, st, (const half_t*)W, (const half_t*)base,
-                     c.K, out_d, in_d, D, DT, (float*)(ws + L.part));
+  // Eq. 6 and the residuals (and their transposes) against the stored base
+  hipLaunchKernelGGL(cmp_residual_kernel, dim3(tx, ty, c.G), dim3(256), 0, st, (const half_t*)W, c.K, out_d, in_d,
+                     (half_t*)base, D, DT, (float*)(ws + L.part));
   hipLaunchKernelGGL(cmp_stats_kernel, dim3(E), dim3(256), 0, st, (const float*)(ws + L.part), tx * ty, stats);
   hipLaunchKernelGGL(cmp_offsets_kernel, dim3((E + 256) / 256), dim3(256), 0, st, E, l, offs);
   hipLaunchKernelGGL(cmp_tile_rows_kernel, dim3((in_d / 8 + 255) / 256, E * l), dim3(256), 0, st, (const half_t*)omega,
