@@ -210,6 +210,20 @@ def ffn_naive(w, x, expert_idx, gate, K, q):
     return y
 
 
+def ffn_dense(W1, W2, x, expert_idx, gate):
+    """The uncompressed layer the method starts from: y[t] = sum_j gate[t][j] W2_e GELU(W1_e x[t])
+    with dense expert matrices W1 [E][d_ff][d], W2 [E][d][d_ff]."""
+    X = x.astype(np.float64)
+    y = np.zeros((X.shape[0], W2.shape[1]), dtype=np.float64)
+    for e in np.unique(expert_idx):
+        A, B = W1[int(e)].astype(np.float64), W2[int(e)].astype(np.float64)
+        for j in range(expert_idx.shape[1]):
+            rows = np.nonzero(expert_idx[:, j] == e)[0]
+            if len(rows):
+                y[rows] += gate[rows, j][:, None] * (gelu(X[rows] @ A.T) @ B.T)
+    return y
+
+
 def forward_naive(w, x, K, k, q):
     """The layer by its definition: route, then the selected experts' dense FFNs."""
     G = w["router_cluster"].shape[0]

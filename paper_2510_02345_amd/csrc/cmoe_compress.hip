@@ -183,16 +183,20 @@ __global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__
   __syncthreads();
   float* cf = coef + (size_t)e * CP_LMAX * CP_LMAX;
   if (MODE == 0) {
+    // The sketch may be rank deficient (a residual of rank below l).  A pivot below tau,
+    // which is far above the rounding noise of the FP16 rows and their FP32 Gram sums, marks
+    // a row the earlier rows already span: it gets a huge pivot, so that its output row is
+    // (numerically) zero instead of amplified noise and the rows after it do not see it.
+    __shared__ double tau_s;
     if (t == 0) {
       double tr = 0.0;
       for (int i = 0; i < l; ++i) tr += A[i][i];
-      const double shift = 1e-6 * tr / l + 1e-30;
-      for (int i = 0; i < l; ++i) A[i][i] += shift;
+      tau_s = 1e-5 * tr / l + 1e-290;
     }
     __syncthreads();
     // Cholesky A = L L^T, column by column; lane i owns row i
     for (int j = 0; j < l; ++j) {
-      if (t == 0) A[j][j] = sqrt(fmax(A[j][j], 1e-300));
+      if (t == 0) A[j][j] = A[j][j] > tau_s ? sqrt(A[j][j]) : 1e150;
       __syncthreads();
       if (t > j && t < l) A[t][j] /= A[j][j];
       __syncthreads();

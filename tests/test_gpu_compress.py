@@ -143,3 +143,45 @@ def test_gate_zeroes_the_factors():
                      gate_gamma=-2.0)
     _sync()
     assert np.all(o2["report"].cpu().numpy()[:, 3] == 0.0) and o2["u_q"].cpu().numpy().any()
+
+
+def test_compressed_layer_runs_forward_close_to_the_dense_layer():
+    """Dense experts -> cmoe_compress (both matrices) -> cmoe_forward, against the dense layer
+    evaluated by the oracle.  The compressed layer is an approximation: the bar is the size of
+    the compression error, far below what a mis-oriented or mis-laid-out factor would give."""
+    import torch
+    import paper_2510_02345_amd as cm
+    G, K, d, d_ff, r, q, k, T = 2, 4, 128, 256, 8, 32, 2, 300
+    E = G * K
+    W1 = ci.generate_dense_experts(G, K, d_ff, d, rank=1, residual_rel=0.5, noise_rel=0.0, seed=121)
+    W2 = ci.generate_dense_experts(G, K, d, d_ff, rank=1, residual_rel=0.5, noise_rel=0.0, seed=122)
+    cfg = ci.small_config("e2e", T=T, d=d, d_ff=d_ff, G=G, K=K, r=r, k=k, q=q, seed=123)
+    w = ci.generate(cfg)                     # routers and tokens (with the routing margin) from here
+    c1 = cm.compress(_dev(W1), _dev(ci.sketch_rows(16, d, seed=124)), G, K, r, q, n_iter=2)
+    c2 = cm.compress(_dev(W2), _dev(ci.sketch_rows(16, d_ff, seed=125)), G, K, r, q, n_iter=2)
+    _sync()
+    # residuals of rank <= K = 4 under a sketch of 16 rows: the orthonormalisation must cope with
+    # a rank-deficient sketch for every expert alike
+    for c in (c1, c2):
+        err = c["report"][:, 0].cpu().numpy()
+        assert err.max() < 0.08 and err.max() <= 1.2 * np.median(err)
+    weights = dict(router_cluster=w["router_cluster"], router_expert=w["router_expert"], cluster_bias=None,
+                   w1_base=c1["base"], w2_base=c2["base"],
+                   v1_q=c1["v_q"], v1_s=c1["v_s"], u1_q=c1["u_q"], u1_s=c1["u_s"],
+                   v2_q=c2["v_q"], v2_s=c2["v_s"], u2_q=c2["u_q"], u2_s=c2["u_s"])
+    layer = cm.Layer(d, d_ff, G, K, r, k, q, weights, T)
+    out = layer.forward(_dev(w["x"]))
+    _sync()
+    cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], K, k)
+    assert np.array_equal(out["expert_idx"].cpu().numpy(), eidx)
+    y_dense = orc.ffn_dense(W1, W2, w["x"], eidx, gate)
+    y = out["y"].float().cpu().numpy().astype(np.float64)
+    rel = np.linalg.norm(y - y_dense) / np.linalg.norm(y_dense)
+    # without the residuals (base only) the output is far off: the factors carry real weight
+    y_base = orc.ffn_dense(np.repeat(orc.base_mean(W1, G, K), K, axis=0), np.repeat(orc.base_mean(W2, G, K), K, axis=0),
+                           w["x"], eidx, gate)
+    rel_base = np.linalg.norm(y_base - y_dense) / np.linalg.norm(y_dense)
+    print(f"compressed vs dense layer: {rel:.4f}; base only: {rel_base:.4f}", flush=True)
+    assert rel_base > 0.2
+    assert rel < 0.08
+    layer.close()

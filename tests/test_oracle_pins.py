@@ -580,3 +580,14 @@ def test_forward_multi_is_sum_of_selected_dense_ffns():
             h = W1 @ w["x"][t].astype(np.float64)
             acc += out["gate"][t, a, 0] * (W2 @ np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in h]))
         assert np.allclose(out["y"][t], acc, rtol=1e-12, atol=1e-14)
+
+
+def test_ffn_dense_equals_compressed_form_with_exact_factors():
+    # dense experts built FROM a compressed layer reproduce that layer's output exactly
+    cfg = ci.small_config("fd", T=12, d=16, d_ff=32, G=2, K=2, r=4, k=2, q=8, seed=25)
+    w = ci.generate(cfg)
+    W1 = np.stack([orc.expert_weights(w, e, cfg.K, cfg.q)[0] for e in range(cfg.E)])
+    W2 = np.stack([orc.expert_weights(w, e, cfg.K, cfg.q)[1] for e in range(cfg.E)])
+    ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    y = orc.ffn_dense(W1, W2, w["x"], ref["expert_idx"], ref["gate"])
+    assert np.allclose(y, ref["y"], rtol=1e-12, atol=1e-14)
