@@ -185,3 +185,16 @@ def test_compressed_layer_runs_forward_close_to_the_dense_layer():
     assert rel_base > 0.2
     assert rel < 0.08
     layer.close()
+
+
+def test_single_expert_clusters_have_no_residual():
+    # K = 1: the base is the expert itself (Eq. 6), the residual is exactly zero
+    import paper_2510_02345_amd as cm
+    G, K, out_d, in_d, r, q = 3, 1, 128, 64, 4, 16
+    W = ci.generate_dense_experts(G, K, out_d, in_d, rank=2, residual_rel=0.3, noise_rel=0.01, seed=131)
+    o = cm.compress(_dev(W), _dev(ci.sketch_rows(8, in_d, seed=132)), G, K, r, q, n_iter=1)
+    _sync()
+    assert np.array_equal(o["base"].cpu().numpy().view(np.uint16), W.view(np.uint16))
+    rep = o["report"].cpu().numpy()
+    assert np.all(np.isfinite(rep)) and np.all(rep[:, :3] == 0.0)
+    assert not o["u_q"].cpu().numpy().any() and not o["v_q"].cpu().numpy().any()
