@@ -290,14 +290,15 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   CMOE_LAUNCH(TS_PERMUTE, launch_pair_sort(dm, perm, offsets, expert_idx, T, rm, p2, st));
   const int* rperm = p2;
   const int* rowmap = rm;
-  CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, st));
+  // when the combine is fused into the down-projection its U2 panel joins the same launch
+  const bool fuse = y_fused != nullptr && dm.KRp <= 128 && weights_combine_ok(w);
+  half_t* u2t = fuse ? (half_t*)(ws + L.u2t) : nullptr;
+  CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, u2t, st));
   CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, rperm, offsets, expert_idx, gate, u1t, v2p,
                                      t1ext, a, spart, st));
   CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
-  if (y_fused != nullptr && dm.KRp <= 128 && weights_combine_ok(w)) {
-    half_t* u2t = (half_t*)(ws + L.u2t);
-    CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
+  if (fuse) {
     CMOE_LAUNCH(TS_GEMM2, launch_gemm2_combine(dm, *w, a, T, offsets, rperm, u2t, s_down, expert_idx, gate,
                                                (half_t*)y_fused, st));
     *fused = true;

@@ -13,15 +13,13 @@ __device__ __forceinline__ float nib_hi(unsigned b) { return (float)((int)(b << 
 // zero.  With PERMUTE16, positions inside every aligned group of 16 are reordered as
 // n = 8a + 4h + i  ->  8h + 4a + i, which is the order in which one lane of a 32x32
 // accumulator block holds its rows (used for the V2 panel, see the fused up-projection).
+// Block (bx, kk, c) of a grid ((L / 8 + 255) / 256, KRp, G).
 template <bool PERMUTE16>
-__global__ __launch_bounds__(256) void dequant_rows_kernel(const uint8_t* __restrict__ qv,
-                                                           const half_t* __restrict__ sv, int L, int q, int K,
-                                                           int r, int KRp, const int* __restrict__ offsets,
-                                                           half_t* __restrict__ out) {
-  const int c = blockIdx.z;
+__device__ __forceinline__ void dequant_rows(int bx, int kk, int c, const uint8_t* __restrict__ qv,
+                                             const half_t* __restrict__ sv, int L, int q, int K, int r, int KRp,
+                                             const int* __restrict__ offsets, half_t* __restrict__ out) {
   if (offsets[c + 1] == offsets[c]) return;
-  const int kk = blockIdx.y;
-  const int n8 = (blockIdx.x * 256 + threadIdx.x) * 8;  // 8 consecutive output positions
+  const int n8 = (bx * 256 + threadIdx.x) * 8;  // 8 consecutive output positions
   if (n8 >= L) return;
   half8 o = {0, 0, 0, 0, 0, 0, 0, 0};
   if (kk < K * r) {
@@ -57,63 +55,115 @@ __global__ __launch_bounds__(256) void dequant_rows_kernel(const uint8_t* __rest
 }
 
 // Transposed panel: out[c][n][kk] = factor[c*K + kk/r][kk%r][n] (kk >= K*r zero).
-// A thread produces 8 consecutive kk for two adjacent n (one source byte per kk).
-__global__ __launch_bounds__(256) void dequant_transpose_kernel(const uint8_t* __restrict__ qv,
-                                                                const half_t* __restrict__ sv, int L, int q, int K,
-                                                                int r, int KRp, const int* __restrict__ offsets,
-                                                                half_t* __restrict__ out) {
-  const int c = blockIdx.y;
+// A block takes 64 consecutive n of one cluster and all KRp rank rows: every row's 32 code
+// bytes are read as two 16-byte words, dequantised into an LDS tile [64 n][KRp], and the
+// tile leaves as whole 16-byte pieces of the n-major rows.  KRp <= 512.
+// Block (bx, c) of a grid (L / 64, G).
+constexpr int DT_N = 64;
+__device__ __forceinline__ void dequant_transpose(int bx, int c, const uint8_t* __restrict__ qv,
+                                                  const half_t* __restrict__ sv, int L, int q, int K, int r, int KRp,
+                                                  const int* __restrict__ offsets, half_t* __restrict__ out,
+                                                  half_t* __restrict__ tile) {
   if (offsets[c + 1] == offsets[c]) return;
-  const int chunks = KRp / 8;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  const int kc = (int)(gid % chunks);
-  const long n2 = gid / chunks;  // pair index: n = 2*n2, 2*n2+1
-  if (n2 * 2 >= L) return;
-  half8 o0 = {0, 0, 0, 0, 0, 0, 0, 0}, o1 = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int kk = kc * 8 + i;
-    if (kk < K * r) {
+  const int n0 = bx * DT_N, ld = KRp + 8, KR = K * r;
+  // two threads per rank row: 32 n (16 code bytes) each
+  for (int idx = threadIdx.x; idx < KRp * 2; idx += 256) {
+    const int kk = idx >> 1, half = idx & 1;
+    uint4 w4 = {0u, 0u, 0u, 0u};
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (kk < KR) {
       const size_t row = (size_t)(c * K) * r + kk;
-      unsigned b = qv[row * (L / 2) + n2];
-      float s = (float)sv[row * (L / q) + (2 * n2) / q];  // q even: both nibbles share the group
-      o0[i] = (half_t)(s * nib_lo(b));
-      o1[i] = (half_t)(s * nib_hi(b));
+      w4 = *(const uint4*)(qv + row * (L / 2) + (n0 + 32 * half) / 2);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) sc[g] = (float)sv[row * (L / q) + (n0 + 32 * half + 8 * g) / q];
     }
+    const unsigned w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const unsigned bq = (w[g] >> (8 * i)) & 0xffu;
+        const int n = 32 * half + 8 * g + 2 * i;
+        tile[n * ld + kk] = (half_t)(sc[g] * nib_lo(bq));
+        tile[(n + 1) * ld + kk] = (half_t)(sc[g] * nib_hi(bq));
+      }
   }
-  half_t* dst = out + ((size_t)c * L + 2 * n2) * KRp + kc * 8;
-  *(half8*)dst = o0;
-  *(half8*)(dst + KRp) = o1;
+  __syncthreads();
+  const int cpr = KRp / 8;   // 16-byte pieces per output row
+  for (int idx = threadIdx.x; idx < DT_N * cpr; idx += 256) {
+    const int n = idx / cpr, ch = idx % cpr;
+    *(half8*)(out + ((size_t)c * L + n0 + n) * KRp + ch * 8) = *(const half8*)(tile + n * ld + ch * 8);
+  }
+}
+
+// All panels of a call in ONE launch: the jobs' blocks are laid end to end in a linear grid.
+struct DequantJob {
+  const uint8_t* qv;
+  const half_t* sv;
+  half_t* out;
+  int L, kind;          // kind 0: rows, 1: rows with the 16-group permutation, 2: transposed
+  unsigned nx, first;   // blocks per (kk, c) or per c; first linear block of the job
+};
+struct DequantJobs {
+  DequantJob j[4];
+  int n;
+};
+__global__ __launch_bounds__(256) void dequant_kernel(DequantJobs jobs, int q, int K, int r, int KRp, int G,
+                                                      const int* __restrict__ offsets) {
+  __shared__ __attribute__((aligned(16))) half_t tile[DT_N * (512 + 8)];
+  int ji = 0;
+  for (int i = 1; i < jobs.n; ++i)
+    if (blockIdx.x >= jobs.j[i].first) ji = i;
+  const DequantJob& jb = jobs.j[ji];
+  const unsigned local = blockIdx.x - jb.first;
+  if (jb.kind == 2) {
+    dequant_transpose((int)(local % jb.nx), (int)(local / jb.nx), jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out,
+                      tile);
+  } else {
+    const int bx = (int)(local % jb.nx), kk = (int)((local / jb.nx) % KRp), c = (int)(local / jb.nx / KRp);
+    if (jb.kind == 1) dequant_rows<true>(bx, kk, c, jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out);
+    else dequant_rows<false>(bx, kk, c, jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out);
+  }
+}
+
+void add_job(DequantJobs& js, unsigned& total, const cmoe_dims& dm, const uint8_t* qv, const void* sv, half_t* out,
+             int L, int kind) {
+  DequantJob& jb = js.j[js.n++];
+  jb.qv = qv;
+  jb.sv = (const half_t*)sv;
+  jb.out = out;
+  jb.L = L;
+  jb.kind = kind;
+  jb.first = total;
+  if (kind == 2) {
+    jb.nx = (unsigned)(L / DT_N);
+    total += jb.nx * dm.G;
+  } else {
+    jb.nx = (unsigned)((L / 8 + 255) / 256);
+    total += jb.nx * dm.KRp * dm.G;
+  }
 }
 
 }  // namespace
 
+// v1cat, u1t, v2p, and u2t when it is not NULL.
 hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* v1cat,
-                              half_t* u1t, half_t* v2p, hipStream_t st) {
-  {
-    dim3 grid((dm.d / 8 + 255) / 256, dm.KRp, dm.G);
-    hipLaunchKernelGGL(dequant_rows_kernel<false>, grid, dim3(256), 0, st, w.v1_q, (const half_t*)w.v1_s, dm.d,
-                       dm.q, dm.K, dm.r, dm.KRp, offsets, v1cat);
-  }
-  {
-    dim3 grid((dm.d_ff / 8 + 255) / 256, dm.KRp, dm.G);
-    hipLaunchKernelGGL(dequant_rows_kernel<true>, grid, dim3(256), 0, st, w.v2_q, (const half_t*)w.v2_s, dm.d_ff,
-                       dm.q, dm.K, dm.r, dm.KRp, offsets, v2p);
-  }
-  {
-    long threads = (long)(dm.d_ff / 2) * (dm.KRp / 8);
-    dim3 grid((unsigned)((threads + 255) / 256), dm.G);
-    hipLaunchKernelGGL(dequant_transpose_kernel, grid, dim3(256), 0, st, w.u1_q, (const half_t*)w.u1_s, dm.d_ff,
-                       dm.q, dm.K, dm.r, dm.KRp, offsets, u1t);
-  }
+                              half_t* u1t, half_t* v2p, half_t* u2t, hipStream_t st) {
+  DequantJobs js{};
+  unsigned total = 0;
+  add_job(js, total, dm, w.u1_q, w.u1_s, u1t, dm.d_ff, 2);
+  add_job(js, total, dm, w.v2_q, w.v2_s, v2p, dm.d_ff, 1);
+  add_job(js, total, dm, w.v1_q, w.v1_s, v1cat, dm.d, 0);
+  if (u2t != nullptr) add_job(js, total, dm, w.u2_q, w.u2_s, u2t, dm.d, 2);
+  hipLaunchKernelGGL(dequant_kernel, dim3(total), dim3(256), 0, st, js, dm.q, dm.K, dm.r, dm.KRp, dm.G, offsets);
   return hipGetLastError();
 }
 
 hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,
                              hipStream_t st) {
-  long threads = (long)(dm.d / 2) * (dm.KRp / 8);
-  dim3 grid((unsigned)((threads + 255) / 256), dm.G);
-  hipLaunchKernelGGL(dequant_transpose_kernel, grid, dim3(256), 0, st, w.u2_q, (const half_t*)w.u2_s, dm.d, dm.q,
-                     dm.K, dm.r, dm.KRp, offsets, u2t);
+  DequantJobs js{};
+  unsigned total = 0;
+  add_job(js, total, dm, w.u2_q, w.u2_s, u2t, dm.d, 2);
+  hipLaunchKernelGGL(dequant_kernel, dim3(total), dim3(256), 0, st, js, dm.q, dm.K, dm.r, dm.KRp, dm.G, offsets);
   return hipGetLastError();
 }

@@ -89,7 +89,7 @@ hipError_t launch_permute_bins(int bins, const int* keys, int T, int* perm, int*
 hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* offsets, const int* expert_idx, int T,
                             int* rowmap, int* perm2, hipStream_t st);
 hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* v1cat,
-                              half_t* u1t, half_t* v2p, hipStream_t st);
+                              half_t* u1t, half_t* v2p, half_t* u2t, hipStream_t st);
 hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,
                              hipStream_t st);
 hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
