@@ -222,6 +222,8 @@ def main():
     ap.add_argument("--no-weight-bound", action="store_true", help="skip the weight-bound (C4) leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compress", action="store_true", help="skip the compression-pipeline leg")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the routing-statistics and routing-variant legs (profiling runs of the layer alone)")
     ap.add_argument("--cpu-sample", type=int, default=1024)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one 256 MiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 "
@@ -252,7 +254,7 @@ def main():
         del src, dst
 
     cfg = ci.config(args.config)
-    res = run_config(cfg, args.steps, args.warmup, want_stats=True)
+    res = run_config(cfg, args.steps, args.warmup, want_stats=not args.no_variants)
     bound = "hbm" if cfg.name == "C4" else "mfma"
     line = {
         "metric": "tokens/s through clustered-MoE FFN layer (1 GPU)",
