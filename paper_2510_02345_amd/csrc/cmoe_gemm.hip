@@ -491,6 +491,102 @@ struct EpiRoute {
   }
 };
 
+// The routing variants on the same accumulators: top_g clusters per token (descending
+// logit, lowest index on ties), each with its own top-k experts; both softmaxes take
+// logits * inv_tau; gate = w_a * softmax(l_sel * inv_tau) with w_a = p_g (scale) or p_g
+// renormalised over the selected clusters.  Outputs per virtual token tok * top_g + a.
+struct EpiRouteMulti {
+  const float* bias;
+  int* cluster_id;
+  int* expert_idx;
+  float* gate;
+  int G, K, k, top_g;
+  float inv_tau;
+  int scale;
+  template <class TL>
+  static constexpr int smem_bytes() {
+    return EpiRoute::smem_bytes<TL>();
+  }
+  template <class TL>
+  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+    constexpr int LD = TL::BN + 1;
+    float* lg = (float*)t.smem;  // [BM tokens][BN + 1 logits]
+    const int h = t.lane >> 5, ml = t.lane & 31;
+    __syncthreads();  // the stage buffers are free
+#pragma unroll
+    for (int b = 0; b < TL::MB; ++b) {
+      const int m = t.wm * TL::WM + b * 32 + ml;
+#pragma unroll
+      for (int a = 0; a < TL::NB; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          lg[m * LD + t.wn * TL::WN + a * 32 + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[a][b][v];
+    }
+    __syncthreads();
+    for (int m = t.tid; m < TL::BM; m += TL::NT) {
+      const int tok = t.m0 + m;
+      if (tok >= t.m_end) continue;
+      float* row = lg + m * LD;
+      float zmax = -INFINITY;
+      for (int g = 0; g < G; ++g) {
+        row[g] += bias ? bias[g] : 0.f;
+        zmax = fmaxf(zmax, row[g]);
+      }
+      float zden = 0.f;
+      for (int g = 0; g < G; ++g) zden += expf((row[g] - zmax) * inv_tau);
+      unsigned long long ctaken = 0ull;  // G <= 64
+      int selc[8];
+      float selp[8];
+      float psum = 0.f;
+      for (int a = 0; a < top_g; ++a) {
+        float bz = -INFINITY;
+        int bg = 0;
+        for (int g = 0; g < G; ++g)
+          if (!((ctaken >> g) & 1ull) && row[g] > bz) {
+            bz = row[g];
+            bg = g;
+          }
+        ctaken |= 1ull << bg;
+        selc[a] = bg;
+        selp[a] = expf((bz - zmax) * inv_tau) / zden;
+        psum += selp[a];
+      }
+      for (int a = 0; a < top_g; ++a) {
+        const int c = selc[a];
+        const float wa = scale ? selp[a] : selp[a] / psum;
+        const float* l = row + G + c * K;
+        unsigned long long taken = 0ull;  // K <= 32
+        float sel[8];
+        int selj[8];
+        for (int b = 0; b < k; ++b) {
+          float bl = -INFINITY;
+          int bj = 0;
+          for (int j = 0; j < K; ++j)
+            if (!((taken >> j) & 1ull) && l[j] > bl) {
+              bl = l[j];
+              bj = j;
+            }
+          taken |= 1ull << bj;
+          sel[b] = bl;
+          selj[b] = bj;
+        }
+        const float lmax = sel[0];
+        float den = 0.f;
+        for (int b = 0; b < k; ++b) {
+          sel[b] = expf((sel[b] - lmax) * inv_tau);
+          den += sel[b];
+        }
+        const size_t vt = (size_t)tok * top_g + a;
+        cluster_id[vt] = c;
+        for (int b = 0; b < k; ++b) {
+          expert_idx[vt * k + b] = c * K + selj[b];
+          gate[vt * k + b] = wa * (sel[b] / den);
+        }
+      }
+    }
+  }
+};
+
 // ---------------------------------------------------------------- epilogue: t1 = V1_{e_j} x
 // acc rows are kk = j_local * r + rho over ALL experts of the cluster; for the token's
 // j-th selected expert only its r rows are kept:  t1[p][j][rho] = acc[(e_j - c*K)*r + rho].
@@ -947,6 +1043,22 @@ hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const h
   ga.spx = 0;
   dim3 grid((unsigned)ga.m_slots), block(TL::NT);
   hipLaunchKernelGGL((gemm_nt_kernel<TL, EpiRoute>), grid, block, 0, st, ga, epi);
+  return hipGetLastError();
+}
+
+// The same product with the routing variants decided in the epilogue.
+hipError_t launch_route_multi_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
+                                   float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
+                                   hipStream_t st) {
+  using TL = Tile<128, 128, 1, 4, 3, 2, false, 8, 8>;
+  const int rows = dm.G + dm.G * dm.K;
+  GemmArgs ga{(const half_t*)w.router_cluster, 0, dm.d, rows, x, dm.d, nullptr, dm.d, nullptr, 1, 1, 0, 0,
+              (const half_t*)w.router_expert, dm.G, T};
+  EpiRouteMulti epi{w.cluster_bias, cluster_id, expert_idx, gate, dm.G, dm.K, dm.k, top_g, 1.f / temperature, scale};
+  ga.m_slots = (T + TL::BM - 1) / TL::BM;
+  ga.spx = 0;
+  dim3 grid((unsigned)ga.m_slots), block(TL::NT);
+  hipLaunchKernelGGL((gemm_nt_kernel<TL, EpiRouteMulti>), grid, block, 0, st, ga, epi);
   return hipGetLastError();
 }
 

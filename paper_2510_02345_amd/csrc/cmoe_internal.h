@@ -104,6 +104,9 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
 hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
                               float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
                               hipStream_t st);
+hipError_t launch_route_multi_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
+                                   float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
+                                   hipStream_t st);
 hipError_t launch_repeat_rows(const half_t* x, int T, int top_g, int d, half_t* xrep, hipStream_t st);
 hipError_t launch_sum_groups(const half_t* yrep, int T, int top_g, int d, half_t* y, hipStream_t st);
 hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,

@@ -601,6 +601,10 @@ hipError_t launch_permute_bins(int bins, const int* cluster_id, int T, int* perm
 hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
                               float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
                               hipStream_t st) {
+  // many tokens and all router rows in one 128-row tile: matrix-core product, decision in
+  // its epilogue (as for the single-cluster router)
+  if (T > SKINNY_T && dm.G + dm.G * dm.K <= 128)
+    return launch_route_multi_mfma(dm, w, x, T, top_g, temperature, scale, cluster_id, expert_idx, gate, st);
   dim3 grid((T + ROUTE_WAVES - 1) / ROUTE_WAVES), block(ROUTE_WAVES * 64);
   const half_t* rc = (const half_t*)w.router_cluster;
   const half_t* re = (const half_t*)w.router_expert;
