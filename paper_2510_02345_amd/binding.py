@@ -17,9 +17,9 @@ _lib = None
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
-           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi", "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes",
-           "cmoe_compress", "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_last_hip_error",
-           "cmoe_status_string",
+           "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi",
+           "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes", "cmoe_compress",
+           "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_last_hip_error", "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
 
 
