@@ -167,7 +167,8 @@ int cmoe_route_stats(cmoe_handle *h, const cmoe_f16 *x, int32_t T, const int32_t
  * [T*top_g], expert_idx [T*top_g][top_k], gate [T*top_g][top_k], and perm / inv_perm
  * [T*top_g] of cmoe_forward_multi are indexed by vt; the permutation is the stable sort of
  * the virtual tokens by cluster, the shared-base products are computed once per virtual
- * token, and y[t] is the sum of its top_g virtual tokens' outputs. */
+ * token (which reads row vt / top_g of x: x is not replicated), and y[t] is the sum of its
+ * top_g virtual tokens' outputs. */
 typedef struct cmoe_route_options {
   int32_t top_g;
   float temperature;

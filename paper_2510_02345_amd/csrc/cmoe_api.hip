@@ -227,20 +227,20 @@ extern "C" int cmoe_permute(cmoe_handle* h, const int32_t* cluster_id, int32_t T
 // *fused tells the caller whether that happened.
 static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T, const int32_t* perm,
                     const int32_t* offsets, const int32_t* expert_idx, const float* gate, cmoe_f16* y_base_sorted,
-                    float* s_down, cmoe_f16* y_fused, bool* fused, void* workspace, size_t workspace_bytes,
+                    float* s_down, cmoe_f16* y_fused, bool* fused, int x_div, void* workspace, size_t workspace_bytes,
                     void* stream);
 
 extern "C" int cmoe_ffn_forward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T,
                                 const int32_t* perm, const int32_t* offsets, const int32_t* expert_idx,
                                 const float* gate, cmoe_f16* y_base_sorted, float* s_down, void* workspace,
                                 size_t workspace_bytes, void* stream) {
-  return ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, y_base_sorted, s_down, nullptr, nullptr, workspace,
+  return ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, y_base_sorted, s_down, nullptr, nullptr, 1, workspace,
                   workspace_bytes, stream);
 }
 
 static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, int32_t T, const int32_t* perm,
                     const int32_t* offsets, const int32_t* expert_idx, const float* gate, cmoe_f16* y_base_sorted,
-                    float* s_down, cmoe_f16* y_fused, bool* fused, void* workspace, size_t workspace_bytes,
+                    float* s_down, cmoe_f16* y_fused, bool* fused, int x_div, void* workspace, size_t workspace_bytes,
                     void* stream) {
   if (fused) *fused = false;
   if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
@@ -267,7 +267,7 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
     // per-expert products ride along in the two stream launches
     const int n_parts = (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN;
     CMOE_LAUNCH(TS_GEMM1_BASE,
-                launch_skinny_hb(dm, *w, (const half_t*)x, T, perm, offsets, expert_idx, t1ext, a, st));
+                launch_skinny_hb(dm, *w, (const half_t*)x, x_div, T, perm, offsets, expert_idx, t1ext, a, st));
     CMOE_LAUNCH(TS_RESID_UP, launch_skinny_resid_up(dm, *w, T, perm, expert_idx, gate, t1ext, a, spart, st));
     if (y_fused != nullptr && weights_combine_ok(w)) {
       float* ures = (float*)(ws + L.ures);
@@ -294,8 +294,8 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   const bool fuse = y_fused != nullptr && dm.KRp <= 128 && weights_combine_ok(w);
   half_t* u2t = fuse ? (half_t*)(ws + L.u2t) : nullptr;
   CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, u2t, st));
-  CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
-  CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, T, rperm, offsets, expert_idx, gate, u1t, v2p,
+  CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
+  CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, gate, u1t, v2p,
                                      t1ext, a, spart, st));
   CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
   if (fuse) {
@@ -339,6 +339,7 @@ static bool route_opt_ok(const cmoe_handle* h, const cmoe_route_options* o) {
   return o != nullptr && o->top_g >= 1 && o->top_g <= 8 && o->top_g <= h->dm.G && o->temperature > 0.f &&
          o->temperature < 1e30f;
 }
+// y of the virtual tokens, summed per token at the end
 static size_t rep_bytes(const cmoe_dims& dm, size_t Tv) { return align_up(sizeof(half_t) * Tv * dm.d, 256); }
 
 extern "C" int cmoe_route_multi(cmoe_handle* h, const cmoe_weights* w, const cmoe_route_options* opt,
@@ -358,7 +359,7 @@ extern "C" size_t cmoe_workspace_bytes_multi(const cmoe_handle* h, int32_t T_max
   if (!handle_ok(h) || T_max < 0 || top_g < 1 || top_g > 8 || top_g > h->dm.G) return 0;
   if ((int64_t)T_max * top_g > INT32_MAX) return 0;
   const int Tv = T_max * top_g;
-  return align_up(cmoe_layout(h->dm, Tv).total, 256) + 2 * rep_bytes(h->dm, (size_t)Tv);
+  return align_up(cmoe_layout(h->dm, Tv).total, 256) + rep_bytes(h->dm, (size_t)Tv);
 }
 
 extern "C" int cmoe_forward_multi(cmoe_handle* h, const cmoe_weights* w, const cmoe_route_options* opt,
@@ -376,24 +377,23 @@ extern "C" int cmoe_forward_multi(cmoe_handle* h, const cmoe_weights* w, const c
   const int g1 = opt->top_g, Tv = T * g1;
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return CMOE_ERR_WORKSPACE;
   const size_t base_bytes = align_up(cmoe_layout(h->dm, Tv).total, 256), rb = rep_bytes(h->dm, (size_t)Tv);
-  if (workspace_bytes < base_bytes + 2 * rb) return CMOE_ERR_WORKSPACE;
+  if (workspace_bytes < base_bytes + rb) return CMOE_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const cmoe_dims& dm = h->dm;
   char* ws = (char*)workspace;
-  half_t* xrep = (half_t*)(ws + base_bytes);
-  half_t* yrep = (half_t*)(ws + base_bytes + rb);
+  half_t* yrep = (half_t*)(ws + base_bytes);
   int rc = cmoe_route_multi(h, w, opt, x, T, cluster_id, expert_idx, gate, stream);
   if (rc != CMOE_OK) return rc;
   // from here on the virtual tokens are ordinary tokens of the single-cluster path
   rc = cmoe_permute(h, cluster_id, Tv, perm, inv_perm, offsets, workspace, base_bytes, stream);
   if (rc != CMOE_OK || T == 0) return rc;
-  CMOE_LAUNCH(TS_ROUTE, launch_repeat_rows((const half_t*)x, T, g1, dm.d, xrep, st));
   cmoe_ws_layout L = cmoe_layout(dm, Tv);
   cmoe_f16* yb = (cmoe_f16*)(ws + L.yb);
   float* s_down = (float*)(ws + L.sdown);
   bool fused = false;
-  rc = ffn_impl(h, w, (const cmoe_f16*)xrep, Tv, perm, offsets, expert_idx, gate, yb, s_down, (cmoe_f16*)yrep, &fused,
-                workspace, base_bytes, stream);
+  // virtual token vt reads row vt / top_g of x
+  rc = ffn_impl(h, w, x, Tv, perm, offsets, expert_idx, gate, yb, s_down, (cmoe_f16*)yrep, &fused, g1, workspace,
+                base_bytes, stream);
   if (rc != CMOE_OK) return rc;
   if (!fused) {
     rc = cmoe_combine(h, w, yb, s_down, perm, inv_perm, offsets, expert_idx, gate, Tv, (cmoe_f16*)yrep, workspace,
@@ -446,7 +446,7 @@ extern "C" int cmoe_forward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
   rc = cmoe_permute(h, cluster_id, T, perm, inv_perm, offsets, workspace, workspace_bytes, stream);
   if (rc != CMOE_OK || T == 0) return rc;
   bool fused = false;
-  rc = ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, yb, s_down, y, &fused, workspace, workspace_bytes,
+  rc = ffn_impl(h, w, x, T, perm, offsets, expert_idx, gate, yb, s_down, y, &fused, 1, workspace, workspace_bytes,
                 stream);
   if (rc != CMOE_OK || fused) return rc;
   return cmoe_combine(h, w, yb, s_down, perm, inv_perm, offsets, expert_idx, gate, T, y, workspace, workspace_bytes,

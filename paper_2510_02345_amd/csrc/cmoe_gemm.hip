@@ -56,6 +56,7 @@ struct GemmArgs {
   // slot_bm rows of one cluster; a tail launch (tail != 0) cuts each of its slots into
   // slot_bm / BM row tiles of a smaller tile shape.
   int slot_bm, rel_lo, rel_hi, tail;
+  int x_div;         // row of X = gather[p] / x_div (several sorted rows may share one row of X); 0 = 1
 };
 
 struct TileCtx {
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
       base = (g.W2 != nullptr && n >= g.w_split) ? g.W2 + (size_t)(n - g.w_split) * g.ldw : Wc + (size_t)n * g.ldw;
     } else {
       const int p = min(m0 + row - TL::BN, m_end - 1);
-      base = g.X + (size_t)(g.gather ? g.gather[p] : p) * g.ldx;
+      base = g.X + (size_t)(g.gather ? (g.x_div > 1 ? g.gather[p] / g.x_div : g.gather[p]) : p) * g.ldx;
     }
     gsrc[i] = base + chunk * 8;
   }
@@ -971,21 +972,24 @@ hipError_t launch_gemm1_r(const cmoe_dims& dm, const GemmArgs& g, int T, const i
 
 }  // namespace
 
-hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
+hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int x_div, int T, const int* perm, const int* offsets,
                      const int* expert_idx, const half_t* v1cat, half_t* t1, hipStream_t st) {
   using TL = TileMain;
   GemmArgs g{v1cat, (long)dm.KRp * dm.d, dm.d, dm.KRp, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.KRp + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  g.x_div = x_div;
   EpiT1 epi{t1, perm, expert_idx, dm.k, dm.K, dm.r, dm.KRp};
   return launch_gemm<TL>(g, T, epi, st);
 }
 
-hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T,
+                        const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
                         const half_t* v2p, const half_t* t1, half_t* a, float* spart, hipStream_t st) {
   using TL = TileUp;
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  g.x_div = x_div;
   switch (dm.r) {
     case 4: return launch_gemm1_r<4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
     case 8: return launch_gemm1_r<8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);

@@ -92,14 +92,14 @@ hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const 
                               half_t* u1t, half_t* v2p, half_t* u2t, hipStream_t st);
 hipError_t launch_dequant_u2(const cmoe_dims& dm, const cmoe_weights& w, const int* offsets, half_t* u2t,
                              hipStream_t st);
-hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int T, const int* perm, const int* offsets,
+hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int x_div, int T, const int* perm, const int* offsets,
                      const int* expert_idx, const half_t* v1cat, half_t* t1ext, hipStream_t st);
-hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T, const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
                         const half_t* v2p, const half_t* t1ext, half_t* a, float* spart, hipStream_t st);
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
                           float* s_down, hipStream_t st);
-hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
+hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T, const int* perm,
                             const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
 hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
                               float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
@@ -107,7 +107,6 @@ hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const 
 hipError_t launch_route_multi_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
                                    float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
                                    hipStream_t st);
-hipError_t launch_repeat_rows(const half_t* x, int T, int top_g, int d, half_t* xrep, hipStream_t st);
 hipError_t launch_sum_groups(const half_t* yrep, int T, int top_g, int d, half_t* y, hipStream_t st);
 hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offsets, int n_groups, int N, int Kc,
                               int max_rows, half_t* out, hipStream_t st);

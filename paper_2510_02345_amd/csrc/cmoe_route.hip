@@ -213,13 +213,6 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void route_multi_kernel(
   }
 }
 
-// xrep[vt][:] = x[vt / top_g][:]
-__global__ __launch_bounds__(256) void repeat_rows_kernel(const half_t* __restrict__ x, int top_g, int d,
-                                                          half_t* __restrict__ xrep) {
-  const int vt = blockIdx.y, col = (blockIdx.x * 256 + threadIdx.x) * 8;
-  if (col >= d) return;
-  *(half8*)(xrep + (size_t)vt * d + col) = *(const half8*)(x + (size_t)(vt / top_g) * d + col);
-}
 // y[t][:] = sum_a yrep[t top_g + a][:] (FP32, a ascending)
 __global__ __launch_bounds__(256) void sum_groups_kernel(const half_t* __restrict__ yrep, int top_g, int d,
                                                          half_t* __restrict__ y) {
@@ -618,11 +611,6 @@ hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const 
   else if (chunks_per_lane <= 4) go(route_multi_kernel<4>);
   else if (chunks_per_lane <= 8) go(route_multi_kernel<8>);
   else go(route_multi_kernel<16>);
-  return hipGetLastError();
-}
-
-hipError_t launch_repeat_rows(const half_t* x, int T, int top_g, int d, half_t* xrep, hipStream_t st) {
-  hipLaunchKernelGGL(repeat_rows_kernel, dim3((d / 8 + 255) / 256, T * top_g), dim3(256), 0, st, x, top_g, d, xrep);
   return hipGetLastError();
 }
 

@@ -167,11 +167,12 @@ __device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, 
 __device__ __forceinline__ void skinny_t1_job(int p, int j, const half_t* __restrict__ x,
                                               const int* __restrict__ perm, const int* __restrict__ expert_idx,
                                               const uint8_t* __restrict__ v1_q, const half_t* __restrict__ v1_s,
-                                              int d, int q, int r, int k, half_t* __restrict__ t1) {
+                                              int d, int q, int r, int k, int x_div,
+                                              half_t* __restrict__ t1) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int tok = perm[p];
   const int e = expert_idx[(size_t)tok * k + j];
-  const half_t* xr = x + (size_t)tok * d;
+  const half_t* xr = x + (size_t)(tok / x_div) * d;
   for (int rho = wave; rho < r; rho += nw) {
     const size_t row = (size_t)e * r + rho;
     const uint8_t* qr = v1_q + row * (d / 2);
@@ -290,6 +291,7 @@ struct SideArgs {
   half_t* t1;
   float* ures;
   int T, d, q, r, k, n_parts, n_jobs;
+  int x_div;             // row of x of a token index = index / x_div (>= 1)
   int n_side;            // workgroups reserved for the jobs (n_jobs rounded up to 8)
 };
 
@@ -310,7 +312,8 @@ __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(con
     const int job = blockIdx.x;
     if (job >= sa.n_jobs) return;
     if (SIDE == SIDE_T1) {
-      skinny_t1_job(job / sa.k, job % sa.k, sa.x, sa.perm, sa.expert_idx, sa.fq, sa.fs, sa.d, sa.q, sa.r, sa.k, sa.t1);
+      skinny_t1_job(job / sa.k, job % sa.k, sa.x, sa.perm, sa.expert_idx, sa.fq, sa.fs, sa.d, sa.q, sa.r, sa.k,
+                    sa.x_div, sa.t1);
     } else {
       const int nch = (sa.d + 2047) / 2048;
       skinny_ures_job(job / nch, job % nch, sa.perm, sa.expert_idx, sa.gate, sa.fq, sa.fs, sa.spart, sa.n_parts, sa.T,
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(con
 #pragma unroll
   for (int i = 0; i < COLS / 8; ++i) {
     int r = min(t.m0 + 8 * i + lrow, t.m_end - 1);
-    if (gather != nullptr) r = gather[r];
+    if (gather != nullptr) r = gather[r] / sa.x_div;
     brow[i] = X + (size_t)r * Kc;
   }
   float16v acc[SK_RB];
@@ -592,12 +595,14 @@ __global__ __launch_bounds__(256) void skinny_combine_kernel(const half_t* __res
 }  // namespace
 
 // Hb = W1_base(c) x for every sorted row; with t1 != NULL the t1 = V1 x jobs ride along.
-hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, const int* perm,
-                            const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st) {
+hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T,
+                            const int* perm, const int* offsets, const int* expert_idx, half_t* t1, half_t* hb,
+                            hipStream_t st) {
   const int passes = (T + SK_COLS - 1) / SK_COLS, nx = dm.d_ff / SK_ROWS;
   const unsigned n_stream = (unsigned)nx * dm.G * passes;
   dim3 block(256);
   SideArgs sa{};
+  sa.x_div = x_div > 1 ? x_div : 1;
   if (t1 == nullptr) {
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, x, perm,
                        (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
@@ -647,6 +652,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   const unsigned n_stream = (unsigned)nx * dm.G * passes;
   dim3 block(256);
   SideArgs sa{};
+  sa.x_div = 1;
   if (ures == nullptr) {
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, a, (const int*)nullptr,
                        (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
@@ -679,6 +685,7 @@ hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offse
                               int max_rows, half_t* out, hipStream_t st) {
   const int nx = N / SK_ROWS;
   SideArgs sa{};
+  sa.x_div = 1;
   if (max_rows > 16) {
     const int passes = (max_rows + 31) / 32;
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, 32>), dim3((unsigned)nx * n_groups * passes), dim3(256), 0, st, X,
