@@ -460,8 +460,9 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
   if (n <= 0) return;
   auto key_of = [&](int i) {
     const int* e = expert_idx + (size_t)perm[lo + i] * k;
-    const int j0 = e[0] - c * K;
-    return two_keys ? j0 * K + (e[1] - c * K) : j0;
+    // expert slots outside the cluster (inconsistent caller input) are clamped into it
+    const int j0 = min(max(e[0] - c * K, 0), K - 1);
+    return two_keys ? j0 * K + min(max(e[1] - c * K, 0), K - 1) : j0;
   };
   if (tid < 64) binbase[tid] = 0;
   __syncthreads();

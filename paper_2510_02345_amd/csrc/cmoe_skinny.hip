@@ -167,11 +167,11 @@ __device__ __forceinline__ bool skinny_tile(const int* offsets, int id, int nx, 
 __device__ __forceinline__ void skinny_t1_job(int p, int j, const half_t* __restrict__ x,
                                               const int* __restrict__ perm, const int* __restrict__ expert_idx,
                                               const uint8_t* __restrict__ v1_q, const half_t* __restrict__ v1_s,
-                                              int d, int q, int r, int k, int x_div,
+                                              int d, int q, int r, int k, int x_div, int n_exp,
                                               half_t* __restrict__ t1) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int tok = perm[p];
-  const int e = expert_idx[(size_t)tok * k + j];
+  const int e = min(max(expert_idx[(size_t)tok * k + j], 0), n_exp - 1);
   const half_t* xr = x + (size_t)(tok / x_div) * d;
   for (int rho = wave; rho < r; rho += nw) {
     const size_t row = (size_t)e * r + rho;
@@ -214,7 +214,7 @@ __device__ __forceinline__ void skinny_ures_job(int p, int chunk, const int* __r
                                                 const int* __restrict__ expert_idx, const float* __restrict__ gate,
                                                 const uint8_t* __restrict__ u2_q, const half_t* __restrict__ u2_s,
                                                 const float* __restrict__ spart, int n_parts, int T, int d, int q,
-                                                int r, int k, float* __restrict__ ures) {
+                                                int r, int k, int n_exp, float* __restrict__ ures) {
   __shared__ float gs[8 * 32];
   __shared__ int es[8];
   const int tid = threadIdx.x;
@@ -225,7 +225,7 @@ __device__ __forceinline__ void skinny_ures_job(int p, int chunk, const int* __r
     for (int part = 0; part < n_parts; ++part) sum += spart[((size_t)part * T + p) * kr + tid];
     gs[tid] = gate[(size_t)tok * k + tid / r] * sum;
   }
-  if (tid < k) es[tid] = expert_idx[(size_t)tok * k + tid];
+  if (tid < k) es[tid] = min(max(expert_idx[(size_t)tok * k + tid], 0), n_exp - 1);
   __syncthreads();
   const int ch = chunk * 256 + tid;  // 8 output columns
   if (ch >= d / 8) return;
@@ -292,6 +292,7 @@ struct SideArgs {
   float* ures;
   int T, d, q, r, k, n_parts, n_jobs;
   int x_div;             // row of x of a token index = index / x_div (>= 1)
+  int n_exp;             // G * K: expert slots are clamped to [0, n_exp)
   int n_side;            // workgroups reserved for the jobs (n_jobs rounded up to 8)
 };
 
@@ -313,11 +314,11 @@ __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(con
     if (job >= sa.n_jobs) return;
     if (SIDE == SIDE_T1) {
       skinny_t1_job(job / sa.k, job % sa.k, sa.x, sa.perm, sa.expert_idx, sa.fq, sa.fs, sa.d, sa.q, sa.r, sa.k,
-                    sa.x_div, sa.t1);
+                    sa.x_div, sa.n_exp, sa.t1);
     } else {
       const int nch = (sa.d + 2047) / 2048;
       skinny_ures_job(job / nch, job % nch, sa.perm, sa.expert_idx, sa.gate, sa.fq, sa.fs, sa.spart, sa.n_parts, sa.T,
-                      sa.d, sa.q, sa.r, sa.k, sa.ures);
+                      sa.d, sa.q, sa.r, sa.k, sa.n_exp, sa.ures);
     }
     return;
   }
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(256) void skinny_resid_up_kernel(
     half_t* __restrict__ A, const half_t* __restrict__ t1, const int* __restrict__ perm,
     const int* __restrict__ expert_idx, const float* __restrict__ gate, const uint8_t* __restrict__ u1_q,
     const half_t* __restrict__ u1_s, const uint8_t* __restrict__ v2_q, const half_t* __restrict__ v2_s, int T,
-    int d_ff, int k, int q, float* __restrict__ spart) {
+    int d_ff, int k, int q, int n_exp, float* __restrict__ spart) {
   constexpr int EPG = 64 / R;    // experts per group of 64 (expert, rank row) values
   __shared__ int srow[8];        // first factor row e_j R of selected expert j
   __shared__ float st1[256];     // t1_j[rho]
@@ -435,7 +436,7 @@ __global__ __launch_bounds__(256) void skinny_resid_up_kernel(
   const int tok = perm[p];
   if (tid < kr) st1[tid] = (float)t1[(size_t)p * kr + tid];
   if (tid < k) {
-    srow[tid] = expert_idx[(size_t)tok * k + tid] * R;
+    srow[tid] = min(max(expert_idx[(size_t)tok * k + tid], 0), n_exp - 1) * R;
     sg[tid] = gate[(size_t)tok * k + tid];
   }
   const int n = chunk * RU_CH + tid * RU_N;
@@ -552,12 +553,12 @@ __global__ __launch_bounds__(256) void skinny_combine_kernel(const half_t* __res
                                                              const float* __restrict__ gate,
                                                              const uint8_t* __restrict__ u2_q,
                                                              const half_t* __restrict__ u2_s, int d, int q, int r,
-                                                             int k, half_t* __restrict__ y) {
+                                                             int k, int n_exp, half_t* __restrict__ y) {
   __shared__ float gs[8 * 32];
   __shared__ int es[8];
   const int t = blockIdx.x, tid = threadIdx.x;
   if (tid < k * r) gs[tid] = gate[(size_t)t * k + tid / r] * s_down[(size_t)t * k * r + tid];
-  if (tid < k) es[tid] = expert_idx[(size_t)t * k + tid];
+  if (tid < k) es[tid] = min(max(expert_idx[(size_t)t * k + tid], 0), n_exp - 1);
   __syncthreads();
   const int ch = blockIdx.y * 256 + tid;  // 8 output columns
   if (ch >= d / 8) return;
@@ -619,6 +620,7 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
   sa.q = dm.q;
   sa.r = dm.r;
   sa.k = dm.k;
+  sa.n_exp = dm.G * dm.K;
   sa.n_jobs = T * dm.k;
   sa.n_side = (sa.n_jobs + 7) & ~7;
   hipLaunchKernelGGL((skinny_base_kernel<SIDE_T1, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, x, perm,
@@ -632,7 +634,7 @@ hipError_t launch_skinny_resid_up(const cmoe_dims& dm, const cmoe_weights& w, in
   dim3 grid(T, (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN), block(256);
   auto go = [&](auto kern) {
     hipLaunchKernelGGL(kern, grid, block, 0, st, a, t1, perm, expert_idx, gate, w.u1_q, (const half_t*)w.u1_s,
-                       w.v2_q, (const half_t*)w.v2_s, T, dm.d_ff, dm.k, dm.q, spart);
+                       w.v2_q, (const half_t*)w.v2_s, T, dm.d_ff, dm.k, dm.q, dm.G * dm.K, spart);
   };
   switch (dm.r) {
     case 4: go(skinny_resid_up_kernel<4>); break;
@@ -670,6 +672,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   sa.q = dm.q;
   sa.r = dm.r;
   sa.k = dm.k;
+  sa.n_exp = dm.G * dm.K;
   sa.n_parts = n_parts;
   sa.n_jobs = T * ((dm.d + 2047) / 2048);
   sa.n_side = (sa.n_jobs + 7) & ~7;
@@ -708,6 +711,6 @@ hipError_t launch_skinny_combine(const cmoe_dims& dm, const cmoe_weights& w, con
                                  const float* s_down, const int* inv_perm, const int* expert_idx, const float* gate,
                                  int T, half_t* y, hipStream_t st) {
   hipLaunchKernelGGL(skinny_combine_kernel, dim3(T, (dm.d / 8 + 255) / 256), dim3(256), 0, st, y_base_sorted, s_down, inv_perm, expert_idx,
-                     gate, w.u2_q, (const half_t*)w.u2_s, dm.d, dm.q, dm.r, dm.k, y);
+                     gate, w.u2_q, (const half_t*)w.u2_s, dm.d, dm.q, dm.r, dm.k, dm.G * dm.K, y);
   return hipGetLastError();
 }
