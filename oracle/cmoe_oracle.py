@@ -291,6 +291,75 @@ def ffn_rewrite(w, x, perm, offsets, expert_idx, gate, K, q):
 
 
 
+# ---------------------------------------------------------------- backward pass (training, Sec. 3.5)
+# Gradients of the layer output for a given routing.  The expert choice is piecewise constant
+# in x and in the router weights, so it carries no gradient; the gates do (softmax over the
+# selected in-cluster logits).  Factors are differentiated as the real-valued matrices they
+# dequantise to.  With W_e = W_base(c) + U_e V_e (Eq. 7):
+#   dW_base(c) = sum over the cluster's experts of dW_e,  dU_e = dW_e V_e^T,  dV_e = U_e^T dW_e.
+def gelu_grad(u):
+    """d/du [u Phi(u)] = Phi(u) + u phi(u), Phi / phi the standard normal CDF / density."""
+    u = np.asarray(u, dtype=np.float64)
+    return 0.5 * (1.0 + _erf(u / np.sqrt(2.0))) + u * np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi)
+
+
+def backward_naive(w, x, dy, expert_idx, gate, K, q):
+    """Gradients of L = sum(dy * y), y the layer output for the given selection (expert_idx
+    [T][k], gate [T][k] = softmax over the selected logits), by the chain rule on dense
+    per-expert matrices.  Returns dx [T][d], d_router_expert [E][d], dw1_base [G][d_ff][d],
+    dw2_base [G][d][d_ff], and per expert du1 [E][r][d_ff], dv1 [E][r][d], du2 [E][r][d],
+    dv2 [E][r][d_ff] in the stored (rank-major) orientation.  float64."""
+    X = np.asarray(x, dtype=np.float64)
+    DY = np.asarray(dy, dtype=np.float64)
+    T, d = X.shape
+    k = expert_idx.shape[1]
+    G = w["w1_base"].shape[0]
+    d_ff = w["w1_base"].shape[1]
+    E = G * K
+    f = _factors(w, q)
+    r = f["u1"].shape[1]
+    RE = w["router_expert"].astype(np.float64)
+    dx = np.zeros((T, d))
+    d_re = np.zeros((E, d))
+    dW1 = np.zeros((E, d_ff, d))
+    dW2 = np.zeros((E, d, d_ff))
+    dg = np.zeros((T, k))
+    for e in np.unique(expert_idx):
+        e = int(e)
+        W1, W2 = expert_weights(w, e, K, q, f)
+        for j in range(k):
+            rows = np.nonzero(expert_idx[:, j] == e)[0]
+            if len(rows) == 0:
+                continue
+            h = X[rows] @ W1.T                       # [n][d_ff]
+            a = gelu(h)
+            o = a @ W2.T                             # [n][d]
+            dg[rows, j] = (DY[rows] * o).sum(axis=1)
+            do = gate[rows, j][:, None] * DY[rows]
+            da = do @ W2
+            dh = da * gelu_grad(h)
+            dx[rows] += dh @ W1
+            dW2[e] += do.T @ a
+            dW1[e] += dh.T @ X[rows]
+    # gates: g = softmax(l_sel); dl_j = g_j (dg_j - sum_i g_i dg_i); l_j = v_{e_j} . x
+    dl = gate * (dg - (gate * dg).sum(axis=1, keepdims=True))
+    for j in range(k):
+        ej = expert_idx[:, j].astype(np.int64)
+        dx += dl[:, j][:, None] * RE[ej]
+        np.add.at(d_re, ej, dl[:, j][:, None] * X)
+    dw1_base = dW1.reshape(G, K, d_ff, d).sum(axis=1)
+    dw2_base = dW2.reshape(G, K, d, d_ff).sum(axis=1)
+    du1 = np.empty((E, r, d_ff)); dv1 = np.empty((E, r, d)); du2 = np.empty((E, r, d)); dv2 = np.empty((E, r, d_ff))
+    for e in range(E):
+        U1, V1, U2, V2 = f["u1"][e].T, f["v1"][e], f["u2"][e].T, f["v2"][e]     # U [out][r], V [r][in]
+        du1[e] = (dW1[e] @ V1.T).T
+        dv1[e] = U1.T @ dW1[e]
+        du2[e] = (dW2[e] @ V2.T).T
+        dv2[e] = U2.T @ dW2[e]
+    return dict(dx=dx, d_router_expert=d_re, dw1_base=dw1_base, dw2_base=dw2_base, du1=du1, dv1=dv1, du2=du2,
+                dv2=dv2, dgate_logits=dl)
+
+
 # ---------------------------------------------------------------- compression (Sec. 3.2, 3.4)
 # Construction of the stored form from dense expert matrices W_e [out][in]: the base of a
 # cluster is the mean of its experts (Eq. 6), each expert keeps a rank-r factorisation of

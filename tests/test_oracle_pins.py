@@ -591,3 +591,64 @@ def test_ffn_dense_equals_compressed_form_with_exact_factors():
     ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
     y = orc.ffn_dense(W1, W2, w["x"], ref["expert_idx"], ref["gate"])
     assert np.allclose(y, ref["y"], rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ backward pass (Sec. 3.5)
+def test_gelu_grad_is_the_derivative():
+    u = np.linspace(-4, 4, 41)
+    eps = 1e-6
+    num = (orc.gelu(u + eps) - orc.gelu(u - eps)) / (2 * eps)
+    assert np.allclose(orc.gelu_grad(u), num, rtol=1e-8, atol=1e-9)
+    assert orc.gelu_grad(0.0) == pytest.approx(0.5) and orc.gelu_grad(10.0) == pytest.approx(1.0, abs=1e-12)
+
+
+def test_backward_matches_central_differences():
+    """L = sum(dy * y) with the selection frozen and the gates recomputed from the logits, written
+    here with scalar loops and math.erf; every gradient the oracle returns against central
+    differences of that function."""
+    cfg = ci.small_config("bw", T=4, d=6, d_ff=8, G=2, K=2, r=2, k=2, q=2, seed=31)
+    w = ci.generate(cfg)
+    E, T, d, f_, r, k, K = cfg.E, cfg.T, cfg.d, cfg.d_ff, cfg.r, cfg.k, cfg.K
+    ref = orc.forward_naive(w, w["x"], K, k, cfg.q)
+    eidx = ref["expert_idx"]
+    rng = np.random.default_rng(32)
+    dy = rng.standard_normal((T, d))
+    fac = {n: orc.dequant_int4(w[n + "_q"], w[n + "_s"], cfg.q) for n in ("v1", "u1", "v2", "u2")}
+    P = dict(x=w["x"].astype(np.float64), re=w["router_expert"].astype(np.float64),
+             b1=w["w1_base"].astype(np.float64), b2=w["w2_base"].astype(np.float64), **fac)
+
+    def loss(P):
+        tot = 0.0
+        for t in range(T):
+            ls = [sum(P["re"][eidx[t, j]][i] * P["x"][t][i] for i in range(d)) for j in range(k)]
+            m = max(ls)
+            ex = [math.exp(v - m) for v in ls]
+            g = [v / sum(ex) for v in ex]
+            for j in range(k):
+                e = int(eidx[t, j]); c = e // K
+                W1 = P["b1"][c] + P["u1"][e].T @ P["v1"][e]
+                W2 = P["b2"][c] + P["u2"][e].T @ P["v2"][e]
+                h = W1 @ P["x"][t]
+                a = np.array([0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in h])
+                tot += g[j] * float(dy[t] @ (W2 @ a))
+        return tot
+
+    got = orc.backward_naive(w, w["x"], dy, eidx, ref["gate"], K, cfg.q)
+    names = dict(x="dx", re="d_router_expert", b1="dw1_base", b2="dw2_base", u1="du1", v1="dv1", u2="du2", v2="dv2")
+    eps = 1e-6
+    for pn, gn in names.items():
+        arr = P[pn]
+        for _ in range(12):
+            idx = tuple(int(rng.integers(0, s)) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + eps
+            lp = loss(P)
+            arr[idx] = old - eps
+            lm = loss(P)
+            arr[idx] = old
+            num = (lp - lm) / (2 * eps)
+            assert got[gn][idx] == pytest.approx(num, rel=2e-6, abs=2e-8), (pn, idx)
+    # experts that no token selected get no gradient; the base gradient is the sum over its experts
+    unused = [e for e in range(E) if e not in set(eidx.reshape(-1).tolist())]
+    for e in unused:
+        assert not got["du1"][e].any() and not got["d_router_expert"][e].any()
