@@ -915,6 +915,18 @@ hipError_t launch_gemm(const GemmArgs& g, int T, const Epi& epi, hipStream_t st)
   if (ga.m_slots < 32) {
     ga.spx = 0;
     ga.rel_hi = ga.m_slots;
+    if constexpr (!std::is_void<TLT>::value) {
+      // fewer big tiles than half the CUs: the small tile shape fills the machine better
+      if (ga.m_slots * g.n_tiles <= 128) {
+        ga.m_slots = (T + TLT::BM - 1) / TLT::BM + g.G;
+        ga.slot_bm = TLT::BM;
+        ga.rel_hi = ga.m_slots;
+        ga.n_tiles = (g.N + TLT::BN - 1) / TLT::BN;
+        hipLaunchKernelGGL((gemm_nt_kernel<TLT, Epi>), dim3((unsigned)(ga.m_slots * ga.n_tiles)), dim3(TLT::NT), 0, st,
+                           ga, epi);
+        return hipGetLastError();
+      }
+    }
     hipLaunchKernelGGL((gemm_nt_kernel<TL, Epi>), dim3((unsigned)(ga.m_slots * g.n_tiles)), block, 0, st, ga, epi);
     return hipGetLastError();
   }
