@@ -349,8 +349,9 @@ def backward_naive(w, x, dy, expert_idx, gate, K, q):
         np.add.at(d_re, ej, dl[:, j][:, None] * X)
     dw1_base = dW1.reshape(G, K, d_ff, d).sum(axis=1)
     dw2_base = dW2.reshape(G, K, d, d_ff).sum(axis=1)
-    du1 = np.empty((E, r, d_ff)); dv1 = np.empty((E, r, d)); du2 = np.empty((E, r, d)); dv2 = np.empty((E, r, d_ff))
-    for e in range(E):
+    du1 = np.zeros((E, r, d_ff)); dv1 = np.zeros((E, r, d)); du2 = np.zeros((E, r, d)); dv2 = np.zeros((E, r, d_ff))
+    for e in np.unique(expert_idx):     # an expert without tokens has dW = 0 whatever its factors hold
+        e = int(e)
         U1, V1, U2, V2 = f["u1"][e].T, f["v1"][e], f["u2"][e].T, f["v2"][e]     # U [out][r], V [r][in]
         du1[e] = (dW1[e] @ V1.T).T
         dv1[e] = U1.T @ dW1[e]
