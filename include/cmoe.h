@@ -231,6 +231,34 @@ int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W
                               const cmoe_f16 *v_s, float *err, void *workspace, size_t workspace_bytes,
                               void *stream);
 
+/* ---- Backward pass for a frozen selection (training step of Sec. 3.5) ----
+ * Gradients of L = sum(dy * y), y = the layer output of Sec. 3.2 / Eq. 8 for the given
+ * expert_idx [T][top_k] and gate [T][top_k] (the softmax of Eq. 10 over the selected
+ * logits, as cmoe_route returns them).  The selection itself (cluster and expert argmax)
+ * is piecewise constant and carries no gradient; the cluster router receives none.
+ * All outputs are FP32 device buffers and are overwritten:
+ *   dx              [T][d]         through the experts and through the gate logits
+ *   d_logits        [T][top_k]     dL / d(selected expert logits); may be NULL
+ *   d_router_expert [G*K][d]       rows v_i of the expert router
+ *   dw1_base [G][d_ff][d], dw2_base [G][d][d_ff]     = sum over the cluster of dW_e
+ *   du1 [G*K][r][d_ff], dv1 [G*K][r][d], du2 [G*K][r][d], dv2 [G*K][r][d_ff]
+ *                                  with respect to the DEQUANTISED factors, in the stored
+ *                                  rank-major orientation: dU = dW V^T, dV = U^T dW
+ * Experts that received no token get zero gradients and their stored weights are not read.
+ * Intermediates are FP16 with FP32 accumulation.  Supported: G*K <= 64.
+ * Deterministic (fixed summation order). */
+typedef struct cmoe_grads {
+  float *dx, *d_logits, *d_router_expert, *dw1_base, *dw2_base, *du1, *dv1, *du2, *dv2;
+} cmoe_grads;
+
+/* Workspace of cmoe_backward for up to T_max tokens (0 for a bad handle, T_max < 0 or an
+ * unsupported shape).  It holds the dense FP16 expert matrices and their FP32 gradients:
+ * about 16 * G*K * d * d_ff bytes plus 4 * T_max * top_k * d_ff. */
+size_t cmoe_backward_workspace_bytes(const cmoe_handle *h, int32_t T_max);
+int cmoe_backward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, const cmoe_f16 *dy,
+                  int32_t T, const int32_t *expert_idx, const float *gate, const cmoe_grads *grads,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* hipError_t (as int) of the last failed HIP call made through this handle, 0 if none. */
 int cmoe_last_hip_error(const cmoe_handle *h);
 const char *cmoe_status_string(int status);

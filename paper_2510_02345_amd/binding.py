@@ -19,7 +19,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
            "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi",
            "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes", "cmoe_compress",
-           "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_last_hip_error", "cmoe_status_string",
+           "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_backward_workspace_bytes", "cmoe_backward",
+           "cmoe_last_hip_error", "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
 
 
@@ -32,6 +33,11 @@ class CmoeError(RuntimeError):
 class CompressConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("out_dim", "in_dim", "G", "K", "r", "q_group", "sketch", "n_iter",
                                          "use_gate")] + [("gate_gamma", C.c_float)]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dx", "d_logits", "d_router_expert", "dw1_base", "dw2_base", "du1", "dv1",
+                                          "du2", "dv2")]
 
 
 class RouteOptions(C.Structure):
@@ -80,6 +86,9 @@ def lib():
     L.cmoe_compress.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_quantize_int4.argtypes = [vp, C.c_int64, i32, i32, vp, vp, vp]
     L.cmoe_reconstruction_error.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_backward_workspace_bytes.argtypes = [vp, i32]
+    L.cmoe_backward_workspace_bytes.restype = sz
+    L.cmoe_backward.argtypes = [vp, C.POINTER(Weights), vp, vp, i32, vp, vp, C.POINTER(Grads), vp, sz, vp]
     L.cmoe_last_hip_error.argtypes = [vp]
     L.cmoe_status_string.argtypes = [C.c_int]
     L.cmoe_status_string.restype = C.c_char_p
@@ -89,7 +98,8 @@ def lib():
     L.cmoe_timing_name.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
-                        "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi"):
+                        "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi",
+                        "cmoe_backward_workspace_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -306,6 +316,31 @@ class Layer:
                                            _ptr(load), _ptr(cload), _ptr(cv), _ptr(self.ws), self.ws.numel(),
                                            self._stream()), "cmoe_route_stats")
         return load, cload, cv
+
+    def backward(self, x, dy, expert_idx, gate):
+        """Gradients of sum(dy * y) for the frozen selection (expert_idx, gate): dict of f32
+        tensors dx, d_logits, d_router_expert, dw1_base, dw2_base, du1, dv1, du2, dv2.  The
+        workspace (dense expert matrices and their gradients) is allocated on first use."""
+        t = self.torch
+        c = self.cfg
+        T = x.shape[0]
+        E = c.G * c.K
+        need = lib().cmoe_backward_workspace_bytes(self._h, T)
+        if need == 0:
+            raise CmoeError(-2, "cmoe_backward_workspace_bytes")
+        if getattr(self, "bw_ws", None) is None or self.bw_ws.numel() < need:
+            self.bw_ws = t.empty(need, dtype=t.uint8, device=self.device)
+        f32 = t.float32
+        out = dict(dx=self._empty((T, c.d), f32), d_logits=self._empty((T, c.top_k), f32),
+                   d_router_expert=self._empty((E, c.d), f32), dw1_base=self._empty((c.G, c.d_ff, c.d), f32),
+                   dw2_base=self._empty((c.G, c.d, c.d_ff), f32), du1=self._empty((E, c.r, c.d_ff), f32),
+                   dv1=self._empty((E, c.r, c.d), f32), du2=self._empty((E, c.r, c.d), f32),
+                   dv2=self._empty((E, c.r, c.d_ff), f32))
+        g = Grads(**{n: _ptr(v) for n, v in out.items()})
+        self._check(lib().cmoe_backward(self._h, C.byref(self.w), _ptr(x), _ptr(dy), T, _ptr(expert_idx), _ptr(gate),
+                                        C.byref(g), _ptr(self.bw_ws), self.bw_ws.numel(), self._stream()),
+                    "cmoe_backward")
+        return out
 
     def forward_buffers(self, T):
         t = self.torch

@@ -104,7 +104,7 @@ extern "C" const char* cmoe_status_string(int status) {
 // ---------------------------------------------------------------- per-kernel timing
 static const char* const kSlotNames[TS_COUNT] = {"route", "permute", "dequant", "t1", "gemm1_fused",
                                                  "s_reduce", "gemm2", "combine", "gemm1_base",
-                                                 "residual_up", "route_stats"};
+                                                 "residual_up", "route_stats", "backward"};
 
 extern "C" const char* cmoe_timing_name(int32_t slot) {
   return (slot >= 0 && slot < TS_COUNT) ? kSlotNames[slot] : "";
@@ -423,6 +423,33 @@ extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, co
   CMOE_LAUNCH(TS_STATS, launch_route_stats(h->dm, (const half_t*)x, T, perm, offsets, expert_idx, beta, lam, mu,
                                            cluster_act, cluster_idle, expert_load, cluster_load, i_load,
                                            (float*)(ws + L.stats_part), (int*)(ws + L.stats_cnt), st));
+  return CMOE_OK;
+}
+
+extern "C" size_t cmoe_backward_workspace_bytes(const cmoe_handle* h, int32_t T_max) {
+  if (!handle_ok(h) || T_max < 0 || h->dm.G * h->dm.K > 64) return 0;
+  if ((size_t)T_max * h->dm.k > ((size_t)1 << 30)) return 0;
+  return cmoe_backward_layout(h->dm, T_max).total;
+}
+
+extern "C" int cmoe_backward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, const cmoe_f16* dy, int32_t T,
+                             const int32_t* expert_idx, const float* gate, const cmoe_grads* grads, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!handle_ok(h) || T < 0 || grads == nullptr) return CMOE_ERR_INVALID_ARG;
+  if (!weights_route_ok(w) || !weights_ffn_ok(w) || !weights_combine_ok(w)) return CMOE_ERR_INVALID_ARG;
+  if (h->dm.G * h->dm.K > 64 || (size_t)T * h->dm.k > ((size_t)1 << 30)) return CMOE_ERR_UNSUPPORTED;
+  const cmoe_grads& g = *grads;
+  if (!ptr_ok(g.d_router_expert) || !ptr_ok(g.dw1_base) || !ptr_ok(g.dw2_base) || !ptr_ok(g.du1) || !ptr_ok(g.dv1) ||
+      !ptr_ok(g.du2) || !ptr_ok(g.dv2) || (g.d_logits != nullptr && !aligned16(g.d_logits)))
+    return CMOE_ERR_INVALID_ARG;
+  if (T > 0 && (!ptr_ok(x) || !ptr_ok(dy) || !ptr_ok(expert_idx) || !ptr_ok(gate) || !ptr_ok(g.dx)))
+    return CMOE_ERR_INVALID_ARG;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return CMOE_ERR_WORKSPACE;
+  const cmoe_bw_layout L = cmoe_backward_layout(h->dm, T);
+  if (workspace_bytes < L.total) return CMOE_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  CMOE_LAUNCH(TS_BACKWARD, launch_backward(h->dm, *w, (const half_t*)x, (const half_t*)dy, T, expert_idx, gate, g,
+                                           (char*)workspace, L, st));
   return CMOE_OK;
 }
 

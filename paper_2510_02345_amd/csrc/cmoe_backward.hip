@@ -1,0 +1,476 @@
+// Backward pass of the layer for a frozen selection (the training step of Sec. 3.5): the
+// gradients of L = sum(dy * y) with respect to x, the expert-router rows, the shared bases
+// and the dequantised low-rank factors, for y of Sec. 3.2 / Eq. 8 with the gates of Eq. 10.
+//
+// The base reuse of Sec. 3.2 carries over to every product of the chain rule.  With
+// W_e = B_c + U_e V_e, tokens sorted by cluster and (token, expert) pairs m = t k + j sorted
+// by expert:
+//   h_m  = B1 x_t + U1 (V1 x_t)                 base product once per token, rank-r per pair
+//   da_m = B2^T dy_t + V2^T (U2^T dy_t)         likewise
+//   a_m = GELU(h_m), dg_m = da_m . a_m, dh_m = g_m da_m GELU'(h_m)
+//   dx_t = B1^T (sum_j dh_m) + sum_j V1^T (U1^T dh_m) + gate path
+//   dB1_c = sum_{t in c} (sum_j dh_m) x_t^T     dB2_c = sum_{t in c} dy_t (sum_j g_m a_m)^T
+//   dU1_e = sum_m dh_m (V1 x_t)^T   dV1_e = sum_m (U1^T dh_m) x_t^T
+//   dU2_e = sum_m g_m dy_t (V2 a_m)^T   dV2_e = sum_m g_m (U2^T dy_t) a_m^T
+// All products run on the grouped matrix-core kernel of the forward pass; those that
+// contract over rows do so after a transposing copy that pads every group to a multiple of
+// 32 columns.  Rank panels are padded to 32 rows.
+#include "cmoe_internal.h"
+
+namespace {
+
+constexpr int RP = 32;   // padded rank
+
+__device__ __forceinline__ float nib_val(unsigned byte, int odd) {
+  return (float)(odd ? ((int)(byte << 24) >> 28) : ((int)(byte << 28) >> 28));
+}
+
+// FP16 panels of one INT4 factor F [E][r][L] (value = scale * code): rows_out [E][32][L]
+// (rank rows >= r zero) and / or trans_out [E][L][32].  Experts without pairs are skipped:
+// their stored factors are never read.  Block (L / 256, E).
+__global__ __launch_bounds__(256) void bw_panel_kernel(const uint8_t* __restrict__ qv, const half_t* __restrict__ sv,
+                                                       int L, int q, int r, const int* __restrict__ offe,
+                                                       half_t* __restrict__ rows_out,
+                                                       half_t* __restrict__ trans_out) {
+  const int e = blockIdx.y;
+  if (offe[e + 1] == offe[e]) return;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= L) return;
+  half_t v[RP];
+#pragma unroll
+  for (int rho = 0; rho < RP; ++rho) {
+    float f = 0.f;
+    if (rho < r) {
+      const size_t row = (size_t)e * r + rho;
+      f = (float)sv[row * (L / q) + i / q] * nib_val(qv[row * (L / 2) + i / 2], i & 1);
+    }
+    v[rho] = (half_t)f;
+    if (rows_out != nullptr) rows_out[((size_t)e * RP + rho) * L + i] = v[rho];
+  }
+  if (trans_out != nullptr) {
+    half8* dst = (half8*)(trans_out + ((size_t)e * L + i) * RP);
+#pragma unroll
+    for (int b = 0; b < RP / 8; ++b)
+      dst[b] = half8{v[8 * b], v[8 * b + 1], v[8 * b + 2], v[8 * b + 3], v[8 * b + 4], v[8 * b + 5], v[8 * b + 6],
+                     v[8 * b + 7]};
+  }
+}
+
+// cluster of a token = cluster of its first selected expert
+__global__ __launch_bounds__(256) void bw_cluster_kernel(const int* __restrict__ expert_idx, int T, int k, int K,
+                                                         int* __restrict__ cid) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t < T) cid[t] = expert_idx[(size_t)t * k] / K;
+}
+
+// Column ranges of the group-padded transposed copies and, for every padded column qc, the
+// sorted row it holds (-1: padding), the source row perm[row] / div and its gate.
+// krange[2g] = first column of group g, krange[2g+1] = its rows rounded up to 32.
+__global__ __launch_bounds__(256) void bw_map_kernel(const int* __restrict__ off, const int* __restrict__ perm,
+                                                     const float* __restrict__ gate, int n_groups, int div, int Npad,
+                                                     int* __restrict__ krange, int* __restrict__ srow,
+                                                     int* __restrict__ ssrc, float* __restrict__ sgate) {
+  __shared__ int start[65];
+  if (threadIdx.x == 0) {
+    int at = 0;
+    for (int g = 0; g < n_groups; ++g) {
+      start[g] = at;
+      at += (off[g + 1] - off[g] + 31) / 32 * 32;
+    }
+    start[n_groups] = at;
+  }
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int g = threadIdx.x; g < n_groups; g += 256) {
+      krange[2 * g] = start[g];
+      krange[2 * g + 1] = start[g + 1] - start[g];
+    }
+  const int qc = blockIdx.x * 256 + threadIdx.x;
+  if (qc >= Npad) return;
+  int row = -1;
+  for (int g = 0; g < n_groups; ++g)
+    if (qc >= start[g] && qc < start[g + 1]) {
+      const int local = qc - start[g];
+      if (local < off[g + 1] - off[g]) row = off[g] + local;
+    }
+  srow[qc] = row;
+  const int m = row >= 0 ? perm[row] : 0;
+  ssrc[qc] = row >= 0 ? m / div : -1;
+  if (sgate != nullptr) sgate[qc] = row >= 0 ? gate[m] : 0.f;
+}
+
+// offx[g] = g * I (g <= n_groups) and gidx[p] = p % I for the n_groups * I rows of a
+// weight gradient.
+__global__ __launch_bounds__(256) void bw_rows_kernel(int n_groups, int I, int* __restrict__ offx,
+                                                      int* __restrict__ gidx) {
+  const size_t p = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (p <= (size_t)n_groups) offx[p] = (int)p * I;
+  if (p < (size_t)n_groups * I) gidx[p] = (int)(p % I);
+}
+
+// One token per block.  For its k pairs (sorted rows p_j = invm[t k + j]):
+//   h = hb[t] + rh[p_j], da = dab[t] + rda[p_j]          FP32
+//   a16[p_j] = GELU(h), dh16[p_j] = g_j da GELU'(h), dg_j = da . GELU(h)
+//   dhsum16[t] = sum_j dh, ag16[t] = sum_j g_j GELU(h)
+// and the softmax backward over the selected logits (Eq. 10):
+//   dl_j = g_j (dg_j - sum_i g_i dg_i).
+// dg is taken from the FP32 values: the gate gradient is a difference of nearly equal dg
+// of experts that share a base.
+template <int KMAX>
+__global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ hb, const float* __restrict__ dab,
+                                                     const float* __restrict__ rh, const float* __restrict__ rda,
+                                                     const int* __restrict__ invm, const float* __restrict__ gate,
+                                                     int k, int d_ff, half_t* __restrict__ a16,
+                                                     half_t* __restrict__ dh16, half_t* __restrict__ dhsum16,
+                                                     half_t* __restrict__ ag16, float* __restrict__ dl) {
+  __shared__ float red[KMAX][4];
+  const size_t t = blockIdx.x;
+  size_t prow[KMAX];
+  float g[KMAX], dot[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    prow[j] = j < k ? (size_t)invm[t * k + j] : 0;
+    g[j] = j < k ? gate[t * k + j] : 0.f;
+    dot[j] = 0.f;
+  }
+  for (int col = threadIdx.x * 4; col < d_ff; col += 1024) {
+    const float4v hv = *(const float4v*)(hb + t * d_ff + col), dv = *(const float4v*)(dab + t * d_ff + col);
+    float dhs[4] = {0.f, 0.f, 0.f, 0.f}, ags[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+      if (j >= k) break;
+      const float4v r1 = *(const float4v*)(rh + prow[j] * d_ff + col), r2 = *(const float4v*)(rda + prow[j] * d_ff + col);
+      half4 ao, ho;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float u = hv[i] + r1[i], z = dv[i] + r2[i];
+        const float cdf = 0.5f * (1.f + erff(u * 0.70710678118654752f));
+        const float pdf = 0.3989422804014327f * __expf(-0.5f * u * u);
+        const float a = u * cdf, dh = g[j] * z * (cdf + u * pdf);
+        dot[j] += z * a;
+        ao[i] = (half_t)a;
+        ho[i] = (half_t)dh;
+        dhs[i] += dh;
+        ags[i] += g[j] * a;
+      }
+      *(half4*)(a16 + prow[j] * d_ff + col) = ao;
+      *(half4*)(dh16 + prow[j] * d_ff + col) = ho;
+    }
+    *(half4*)(dhsum16 + t * d_ff + col) = half4{(half_t)dhs[0], (half_t)dhs[1], (half_t)dhs[2], (half_t)dhs[3]};
+    *(half4*)(ag16 + t * d_ff + col) = half4{(half_t)ags[0], (half_t)ags[1], (half_t)ags[2], (half_t)ags[3]};
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) {
+    float v = dot[j];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) red[j][wave] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float dg[KMAX], mean = 0.f;
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+      dg[j] = (red[j][0] + red[j][1]) + (red[j][2] + red[j][3]);
+      mean += g[j] * dg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j)
+      if (j < k) dl[t * k + j] = g[j] * (dg[j] - mean);
+  }
+}
+
+// dx[t] = dxb[t] + sum_j dxr[t k + j] + sum_j dl_j v_{e_j}: shared-base part, per-pair
+// residual part, and the gate path of Eq. 10.
+__global__ __launch_bounds__(256) void bw_dx_kernel(const float* __restrict__ dxb, const float* __restrict__ dxr,
+                                                    const float* __restrict__ dl, const int* __restrict__ expert_idx,
+                                                    const half_t* __restrict__ router_expert, int k, int d,
+                                                    float* __restrict__ dx) {
+  const size_t t = blockIdx.x;
+  const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (col >= d) return;
+  float4v acc = *(const float4v*)(dxb + t * d + col);
+  for (int j = 0; j < k; ++j) {
+    acc += *(const float4v*)(dxr + (t * k + j) * d + col);
+    const float c = dl[t * k + j];
+    const half4 v = *(const half4*)(router_expert + (size_t)expert_idx[t * k + j] * d + col);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += c * (float)v[i];
+  }
+  *(float4v*)(dx + t * d + col) = acc;
+}
+
+// d v_e = sum over the pair rows of expert e of dl_m x_t, rows in sorted order.
+__global__ __launch_bounds__(256) void bw_drouter_kernel(const half_t* __restrict__ x, const int* __restrict__ permm,
+                                                         const int* __restrict__ offe, const float* __restrict__ dl,
+                                                         int k, int d, float* __restrict__ d_re) {
+  const int e = blockIdx.x;
+  const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (col >= d) return;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  const int lo = offe[e], hi = offe[e + 1];
+  for (int p0 = lo; p0 < hi; p0 += 4) {
+    half4 v[4];
+    float c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool ok = p0 + u < hi;
+      const int m = ok ? permm[p0 + u] : 0;
+      c[u] = ok ? dl[m] : 0.f;
+      v[u] = *(const half4*)(x + (size_t)(m / k) * d + col);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] += c[u] * (float)v[u][i];
+  }
+  *(float4v*)(d_re + (size_t)e * d + col) = float4v{acc[0], acc[1], acc[2], acc[3]};
+}
+
+// out[z][i][qc] = scale[qc] * src[z][idx[qc]][i] (zero where idx[qc] < 0; idx == NULL: row
+// qc), i < I (a multiple of 16), qc < Npad (a multiple of 64).  Matrices z whose group in
+// skip_off is empty are skipped.  Block (Npad / 64, ceil(I / 64), Z): 64 x 64 tile through LDS.
+__global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restrict__ src, int ld, int I,
+                                                           const int* __restrict__ idx,
+                                                           const float* __restrict__ scale, int Npad,
+                                                           const int* __restrict__ skip_off, size_t zstride,
+                                                           half_t* __restrict__ out) {
+  __shared__ half_t tile[64][72];
+  const int z = blockIdx.z;
+  if (skip_off != nullptr && skip_off[z + 1] == skip_off[z]) return;
+  src += z * zstride;
+  out += z * zstride;
+  const int q0 = blockIdx.x * 64, i0 = blockIdx.y * 64, tid = threadIdx.x;
+  {
+    const int ql = tid >> 2, part = tid & 3;
+    const int row = idx != nullptr ? idx[q0 + ql] : q0 + ql;
+    half8 a = {0, 0, 0, 0, 0, 0, 0, 0}, b = a;
+    if (row >= 0 && i0 + part * 16 < I) {
+      a = *(const half8*)(src + (size_t)row * ld + i0 + part * 16);
+      b = *(const half8*)(src + (size_t)row * ld + i0 + part * 16 + 8);
+      if (scale != nullptr) {
+        const float s = scale[q0 + ql];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          a[i] = (half_t)(s * (float)a[i]);
+          b[i] = (half_t)(s * (float)b[i]);
+        }
+      }
+    }
+    *(half8*)&tile[ql][part * 16] = a;
+    *(half8*)&tile[ql][part * 16 + 8] = b;
+  }
+  __syncthreads();
+  const int il = tid >> 2, part = tid & 3;
+  if (i0 + il >= I) return;
+  half8 a, b;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    a[u] = tile[part * 16 + u][il];
+    b[u] = tile[part * 16 + 8 + u][il];
+  }
+  half_t* dst = out + (size_t)(i0 + il) * Npad + q0 + part * 16;
+  *(half8*)dst = a;
+  *(half8*)(dst + 8) = b;
+}
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+void transpose(const half_t* src, int ld, int I, const int* idx, const float* scale, int Npad, half_t* out,
+               hipStream_t st) {
+  hipLaunchKernelGGL(bw_transpose_kernel, dim3(Npad / 64, (I + 63) / 64, 1), dim3(256), 0, st, src, ld, I, idx, scale,
+                     Npad, (const int*)nullptr, (size_t)0, out);
+}
+
+}  // namespace
+
+cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
+  cmoe_bw_layout L;
+  const size_t E = (size_t)dm.G * dm.K, G = dm.G, Tz = (size_t)(T > 0 ? T : 0), M = Tz * dm.k;
+  const size_t d = dm.d, f = dm.d_ff, r = dm.r;
+  L.M = (int)M;
+  L.Mpad = (int)((M + 32 * E + 63) / 64 * 64);
+  L.Tpad = (int)((Tz + 32 * G + 63) / 64 * 64);
+  const size_t Mp = L.Mpad, Tp = L.Tpad;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = up256(off + bytes);
+    return at;
+  };
+  const size_t n_blocks = (M + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
+  L.blk_counts = take(sizeof(int) * (n_blocks + 1) * 64);
+  L.cid = take(sizeof(int) * Tz);
+  L.permc = take(sizeof(int) * Tz);
+  L.invc = take(sizeof(int) * Tz);
+  L.offc = take(sizeof(int) * (G + 1));
+  L.permm = take(sizeof(int) * M);
+  L.invm = take(sizeof(int) * M);
+  L.offe = take(sizeof(int) * (E + 1));
+  L.krange_p = take(sizeof(int) * 2 * E);
+  L.krange_c = take(sizeof(int) * 2 * G);
+  L.srow_p = take(sizeof(int) * Mp);
+  L.ssrc_p = take(sizeof(int) * Mp);
+  L.sgate_p = take(sizeof(float) * Mp);
+  L.srow_c = take(sizeof(int) * Tp);
+  L.ssrc_c = take(sizeof(int) * Tp);
+  L.offx_f = take(sizeof(int) * (G + 1));
+  L.gidx_f = take(sizeof(int) * G * f);
+  L.offx_d = take(sizeof(int) * (G + 1));
+  L.gidx_d = take(sizeof(int) * G * d);
+  L.offx_r = take(sizeof(int) * (E + 1));
+  L.gidx_r = take(sizeof(int) * E * r);
+  L.dl = take(sizeof(float) * M);
+  L.v1p = take(sizeof(half_t) * E * 32 * d);
+  L.u2p = take(sizeof(half_t) * E * 32 * d);
+  L.u1p = take(sizeof(half_t) * E * 32 * f);
+  L.v2p = take(sizeof(half_t) * E * 32 * f);
+  L.v1t = take(sizeof(half_t) * E * 32 * d);
+  L.u1t = take(sizeof(half_t) * E * 32 * f);
+  L.v2t = take(sizeof(half_t) * E * 32 * f);
+  L.w1bt = take(sizeof(half_t) * G * f * d);
+  L.w2bt = take(sizeof(half_t) * G * f * d);
+  L.hb = take(sizeof(float) * Tz * f);
+  L.dab = take(sizeof(float) * Tz * f);
+  L.rh = take(sizeof(float) * M * f);
+  L.rda = take(sizeof(float) * M * f);
+  L.a16 = take(sizeof(half_t) * M * f);
+  L.dh16 = take(sizeof(half_t) * M * f);
+  L.dhsum16 = take(sizeof(half_t) * Tz * f);
+  L.ag16 = take(sizeof(half_t) * Tz * f);
+  L.t1 = take(sizeof(half_t) * M * 32);
+  L.uy = take(sizeof(half_t) * M * 32);
+  L.qq = take(sizeof(half_t) * M * 32);
+  L.ss = take(sizeof(half_t) * M * 32);
+  L.dxb = take(sizeof(float) * Tz * d);
+  L.dxr = take(sizeof(float) * M * d);
+  L.xpt = take(sizeof(half_t) * d * Mp);
+  L.dot = take(sizeof(half_t) * d * Mp);
+  L.at = take(sizeof(half_t) * f * Mp);
+  L.dht = take(sizeof(half_t) * f * Mp);
+  L.t1t = take(sizeof(half_t) * 32 * Mp);
+  L.qt = take(sizeof(half_t) * 32 * Mp);
+  L.st = take(sizeof(half_t) * 32 * Mp);
+  L.uyt = take(sizeof(half_t) * 32 * Mp);
+  L.xct = take(sizeof(half_t) * d * Tp);
+  L.dyct = take(sizeof(half_t) * d * Tp);
+  L.dhst = take(sizeof(half_t) * f * Tp);
+  L.agt = take(sizeof(half_t) * f * Tp);
+  L.total = off;
+  return L;
+}
+
+hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, const half_t* dy, int T,
+                           const int* expert_idx, const float* gate, const cmoe_grads& out, char* ws,
+                           const cmoe_bw_layout& L, hipStream_t st) {
+  const int E = dm.G * dm.K, G = dm.G, d = dm.d, f = dm.d_ff, r = dm.r, k = dm.k, M = L.M, Mpad = L.Mpad,
+            Tpad = L.Tpad;
+  auto I = [&](size_t o) { return (int*)(ws + o); };
+  auto H = [&](size_t o) { return (half_t*)(ws + o); };
+  auto F = [&](size_t o) { return (float*)(ws + o); };
+  int *permc = I(L.permc), *offc = I(L.offc), *permm = I(L.permm), *invm = I(L.invm), *offe = I(L.offe);
+  int *krp = I(L.krange_p), *krc = I(L.krange_c);
+  float* dl = out.d_logits ? out.d_logits : F(L.dl);
+  const long mat = (long)f * d;
+  const half_t *w1b = (const half_t*)w.w1_base, *w2b = (const half_t*)w.w2_base;
+  hipError_t err;
+#define BW_CHECK(call)                    \
+  do {                                    \
+    err = (call);                         \
+    if (err != hipSuccess) return err;    \
+  } while (0)
+#define BW_GEMM(...) BW_CHECK(launch_gemm_plain(__VA_ARGS__, st))
+
+  // tokens sorted by cluster, pairs sorted by expert (both stable)
+  if (T > 0)
+    hipLaunchKernelGGL(bw_cluster_kernel, dim3((T + 255) / 256), dim3(256), 0, st, expert_idx, T, k, dm.K, I(L.cid));
+  BW_CHECK(launch_permute_bins(G, I(L.cid), T, permc, I(L.invc), offc, I(L.blk_counts), st));
+  BW_CHECK(launch_permute_bins(E, expert_idx, M, permm, invm, offe, I(L.blk_counts), st));
+  hipLaunchKernelGGL(bw_map_kernel, dim3((Mpad + 255) / 256), dim3(256), 0, st, offe, permm, gate, E, k, Mpad, krp,
+                     I(L.srow_p), I(L.ssrc_p), F(L.sgate_p));
+  hipLaunchKernelGGL(bw_map_kernel, dim3((Tpad + 255) / 256), dim3(256), 0, st, offc, permc, (const float*)nullptr, G,
+                     1, Tpad, krc, I(L.srow_c), I(L.ssrc_c), (float*)nullptr);
+  hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)G * f + 256) / 256)), dim3(256), 0, st, G, f,
+                     I(L.offx_f), I(L.gidx_f));
+  hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)G * d + 256) / 256)), dim3(256), 0, st, G, d,
+                     I(L.offx_d), I(L.gidx_d));
+  hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)E * r + 256) / 256)), dim3(256), 0, st, E, r,
+                     I(L.offx_r), I(L.gidx_r));
+  // no token: the products below find empty groups and write zero gradients
+  if (T > 0) {
+    // operand panels: rank factors and transposed bases
+    const int q = dm.q;
+    hipLaunchKernelGGL(bw_panel_kernel, dim3((d + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v1_q,
+                       (const half_t*)w.v1_s, d, q, r, offe, H(L.v1p), H(L.v1t));
+    hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.u1_q,
+                       (const half_t*)w.u1_s, f, q, r, offe, H(L.u1p), H(L.u1t));
+    hipLaunchKernelGGL(bw_panel_kernel, dim3((d + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.u2_q,
+                       (const half_t*)w.u2_s, d, q, r, offe, H(L.u2p), (half_t*)nullptr);
+    hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v2_q,
+                       (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p), H(L.v2t));
+    // w1bt [G][d][d_ff] = B1^T, w2bt [G][d_ff][d] = B2^T
+    hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, d, (const int*)nullptr,
+                       (const float*)nullptr, f, offc, (size_t)mat, H(L.w1bt));
+    hipLaunchKernelGGL(bw_transpose_kernel, dim3(d / 64, f / 64, G), dim3(256), 0, st, w2b, f, f, (const int*)nullptr,
+                       (const float*)nullptr, d, offc, (size_t)mat, H(L.w2bt));
+    BW_CHECK(hipGetLastError());
+
+    // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
+    BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.hb), f, true);
+    BW_GEMM(H(L.v1p), (long)RP * d, d, RP, x, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.t1), RP, false);
+    BW_GEMM(H(L.u1t), (long)f * RP, RP, f, H(L.t1), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, F(L.rh), f, true);
+    // da = B2^T dy + V2^T (U2^T dy)
+    BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.dab), f, true);
+    BW_GEMM(H(L.u2p), (long)RP * d, d, RP, dy, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.uy), RP, false);
+    BW_GEMM(H(L.v2t), (long)f * RP, RP, f, H(L.uy), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, F(L.rda), f, true);
+    if (k <= 2)
+      hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), F(L.rh), F(L.rda), invm, gate, k,
+                         f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
+    else
+      hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), F(L.rh), F(L.rda), invm, gate, k,
+                         f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
+    // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
+    BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);
+    BW_GEMM(H(L.u1p), (long)RP * f, f, RP, H(L.dh16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.qq), RP, false);
+    BW_GEMM(H(L.v1t), (long)d * RP, RP, d, H(L.qq), RP, nullptr, 1, RP, offe, E, M, nullptr, permm, F(L.dxr), d, true);
+    hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, F(L.dxb), F(L.dxr), dl, expert_idx,
+                       (const half_t*)w.router_expert, k, d, out.dx);
+    // s = V2 a per pair
+    BW_GEMM(H(L.v2p), (long)RP * f, f, RP, H(L.a16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.ss), RP, false);
+    // transposed, group-padded copies for the products that contract over rows
+    const int *srow_p = I(L.srow_p), *ssrc_p = I(L.ssrc_p), *ssrc_c = I(L.ssrc_c);
+    const float* sgate_p = F(L.sgate_p);
+    transpose(x, d, d, ssrc_p, nullptr, Mpad, H(L.xpt), st);
+    transpose(dy, d, d, ssrc_p, sgate_p, Mpad, H(L.dot), st);
+    transpose(H(L.a16), f, f, srow_p, nullptr, Mpad, H(L.at), st);
+    transpose(H(L.dh16), f, f, srow_p, nullptr, Mpad, H(L.dht), st);
+    transpose(H(L.t1), RP, RP, srow_p, nullptr, Mpad, H(L.t1t), st);
+    transpose(H(L.qq), RP, RP, srow_p, nullptr, Mpad, H(L.qt), st);
+    transpose(H(L.ss), RP, RP, srow_p, nullptr, Mpad, H(L.st), st);
+    transpose(H(L.uy), RP, RP, srow_p, sgate_p, Mpad, H(L.uyt), st);
+    transpose(x, d, d, ssrc_c, nullptr, Tpad, H(L.xct), st);
+    transpose(dy, d, d, ssrc_c, nullptr, Tpad, H(L.dyct), st);
+    transpose(H(L.dhsum16), f, f, ssrc_c, nullptr, Tpad, H(L.dhst), st);
+    transpose(H(L.ag16), f, f, ssrc_c, nullptr, Tpad, H(L.agt), st);
+    BW_CHECK(hipGetLastError());
+  }
+  hipLaunchKernelGGL(bw_drouter_kernel, dim3(E, (d / 4 + 255) / 256), dim3(256), 0, st, x, permm, offe, dl, k, d,
+                     out.d_router_expert);
+  // base gradients: contraction over the tokens of a cluster
+  BW_GEMM(H(L.xct), 0, Tpad, d, H(L.dhst), Tpad, I(L.gidx_f), 1, Tpad, I(L.offx_f), G, G * f, krc, nullptr,
+          out.dw1_base, d, true);
+  BW_GEMM(H(L.agt), 0, Tpad, f, H(L.dyct), Tpad, I(L.gidx_d), 1, Tpad, I(L.offx_d), G, G * d, krc, nullptr,
+          out.dw2_base, f, true);
+  // factor gradients: contraction over the pairs of an expert, r output rows per expert
+  BW_GEMM(H(L.dht), 0, Mpad, f, H(L.t1t), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.du1, f,
+          true);
+  BW_GEMM(H(L.xpt), 0, Mpad, d, H(L.qt), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.dv1, d,
+          true);
+  BW_GEMM(H(L.dot), 0, Mpad, d, H(L.st), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.du2, d,
+          true);
+  BW_GEMM(H(L.at), 0, Mpad, f, H(L.uyt), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.dv2, f,
+          true);
+#undef BW_GEMM
+#undef BW_CHECK
+  return hipGetLastError();
+}

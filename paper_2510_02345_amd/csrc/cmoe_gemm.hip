@@ -57,6 +57,9 @@ struct GemmArgs {
   // slot_bm / BM row tiles of a smaller tile shape.
   int slot_bm, rel_lo, rel_hi, tail;
   int x_div;         // row of X = gather[p] / x_div (several sorted rows may share one row of X); 0 = 1
+  // optional per-group contraction range: group c contracts columns krange[2c] ..
+  // krange[2c] + krange[2c+1] (both multiples of 32) of W and X instead of 0 .. Kc
+  const int* krange;
 };
 
 struct TileCtx {
@@ -134,6 +137,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   }
   const int n0 = n_tile * TL::BN;
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
+  const int k_lo = g.krange ? g.krange[2 * c] : 0;
   const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 
   // global source of each of this wavefront's load instructions (16 tile rows x 64 B);
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
       const int p = min(m0 + row - TL::BN, m_end - 1);
       base = g.X + (size_t)(g.gather ? (g.x_div > 1 ? g.gather[p] / g.x_div : g.gather[p]) : p) * g.ldx;
     }
-    gsrc[i] = base + chunk * 8;
+    gsrc[i] = base + chunk * 8 + k_lo;
   }
   auto issue = [&](int kt, int stage) {
 #pragma unroll
@@ -192,7 +196,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
   for (int b = 0; b < TL::MB; ++b) bv[b] = m0 + wm * TL::WM + b * 32 < m_end;
 
-  const int KT = g.Kc / TL::BK;
+  const int KT = (g.krange ? g.krange[2 * c + 1] : g.Kc) / TL::BK;
 #pragma unroll
   for (int s = 0; s < TL::NS - 1; ++s)
     if (s < KT) issue(s, s);
@@ -280,8 +284,9 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 
 // ---------------------------------------------------------------- epilogue: plain store
 // out[p][n] = acc (f16), rows p in cluster-sorted order.
-struct EpiStore {
-  half_t* out;
+template <class OutT>
+struct EpiStoreT {
+  OutT* out;
   const int* rowmap;  // row p of the tile order is written to out[rowmap[p]] (NULL: identity)
   int ldo, N;
   template <class TL>
@@ -300,11 +305,16 @@ struct EpiStore {
         if (nb >= N) continue;
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd)
-          *(half4*)(out + orow * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+          if constexpr (sizeof(OutT) == 2)
+            *(half4*)(out + orow * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
+          else
+            *(float4v*)(out + orow * ldo + nb + 8 * qd + 4 * h) =
+                float4v{acc[a][b][4 * qd], acc[a][b][4 * qd + 1], acc[a][b][4 * qd + 2], acc[a][b][4 * qd + 3]};
       }
     }
   }
 };
+using EpiStore = EpiStoreT<half_t>;
 
 // ---------------------------------------------------------------- epilogue: down-projection + combine
 // acc = (W2_base A)^T block.  Adds the residual of the second matrix as one more
@@ -1088,4 +1098,25 @@ hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, cons
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   EpiDownCombine epi{u2t, s_down, rperm, expert_idx, gate, y, dm.k, dm.K, dm.r, dm.KRp, dm.d};
   return launch_gemm<TL, EpiDownCombine, TileTail>(g, T, epi, st);
+}
+
+// Grouped product with a plain store, for callers outside the forward path:
+//   out[rowmap ? rowmap[p] : p][n] = sum_k X[row(p)][k_g + k] * W_g[n][k_g + k],
+// W_g = W + g * w_gstride, row(p) = gather ? gather[p] / x_div : p, rows p of group g in
+// [offsets[g], offsets[g+1]); k runs over [0, Kc) or over the group's krange.
+hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, const half_t* X, int ldx,
+                             const int* gather, int x_div, int Kc, const int* offsets, int n_groups, int rows,
+                             const int* krange, const int* rowmap, void* out, int ldo, bool out_f32,
+                             hipStream_t st) {
+  using TL = TileBig;
+  GemmArgs g{W, w_gstride, ldw, N, X, ldx, gather, Kc, offsets, n_groups, (N + TL::BN - 1) / TL::BN, 0, 0, nullptr,
+             0, 0};
+  g.x_div = x_div;
+  g.krange = krange;
+  if (out_f32) {
+    EpiStoreT<float> epi{(float*)out, rowmap, ldo, N};
+    return launch_gemm<TL, EpiStoreT<float>, TileTail>(g, rows, epi, st);
+  }
+  EpiStore epi{(half_t*)out, rowmap, ldo, N};
+  return launch_gemm<TL, EpiStore, TileTail>(g, rows, epi, st);
 }
