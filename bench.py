@@ -119,13 +119,31 @@ def run_config(cfg, steps, warmup, want_stats=False):
         multi_ms = (time.perf_counter() - t0) / max(steps // 2, 3) * 1e3
         del om
 
+    backward_ms = None
+    if want_stats:
+        # backward pass for the frozen selection of this step (whole entry point between two
+        # HIP events on its stream)
+        dy = torch.from_numpy(np.random.default_rng(cfg.seed + 7).standard_normal((cfg.T, cfg.d)).astype(np.float16))
+        dy = dy.to("cuda:0")
+        grads = layer.backward(x, dy, out["expert_idx"], out["gate"])
+        torch.cuda.synchronize()
+        layer.timing_enable(True)
+        n_bw = max(steps // 4, 3)
+        for _ in range(n_bw):
+            grads = layer.backward(x, dy, out["expert_idx"], out["gate"])
+        torch.cuda.synchronize()
+        backward_ms = layer.timing_read()["backward"][0] / n_bw
+        layer.timing_enable(False)
+        del grads, dy
+        layer.bw_ws = None
+
     eidx = out["expert_idx"].cpu().numpy()
     offs = out["offsets"].cpu().numpy()
     clusters_hit = int((np.diff(offs) > 0).sum())
     experts_hit = int(len(np.unique(eidx)))
     layer.close()
     return dict(ms_per_step=ms_per_step, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
-                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms)
+                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms, backward_ms=backward_ms)
 
 
 def roofline(cfg, res, bound, traffic_table):
@@ -283,6 +301,16 @@ def main():
                                  "vs_two_single_cluster_steps": round(res["multi_ms"] / (2 * res["ms_per_step"]), 3),
                                  "note": "cmoe_forward_multi, workspace allocated per call by the binding (inside "
                                          "the timed region); 2 T virtual tokens through the same kernels"}
+    if res["backward_ms"]:
+        M = cfg.T * cfg.k
+        flops = 5 * 2.0 * cfg.T * cfg.d * cfg.d_ff + 2.0 * M * cfg.r * (5 * cfg.d + 6 * cfg.d_ff)
+        tf = flops / (res["backward_ms"] * 1e-3) / 1e12
+        line["backward"] = {"ms": round(res["backward_ms"], 4), "bound": "mfma", "achieved": round(tf, 1),
+                            "peak": PEAK_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_F16_TFLOPS, 4),
+                            "vs_forward": round(res["backward_ms"] / res["ms_per_step"], 3),
+                            "note": "cmoe_backward for the frozen selection of the step: five shared-base products "
+                                    "of 2 T d d_ff flops (once per token) and eleven rank-r products per (token, "
+                                    "expert) pair; all launches timed together; not part of ms_per_step"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
     del res

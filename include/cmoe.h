@@ -245,15 +245,17 @@ int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W
  *                                  with respect to the DEQUANTISED factors, in the stored
  *                                  rank-major orientation: dU = dW V^T, dV = U^T dW
  * Experts that received no token get zero gradients and their stored weights are not read.
- * Intermediates are FP16 with FP32 accumulation.  Supported: G*K <= 64.
- * Deterministic (fixed summation order). */
+ * The shared-base products are computed once per token, the rank-r products once per
+ * (token, expert) pair (Sec. 3.2).  Matrix operands are FP16, accumulation, the hidden
+ * pre-activations and the gate path are FP32.  Supported: G*K <= 64.  T = 0 writes zero
+ * weight gradients.  Deterministic (fixed summation order). */
 typedef struct cmoe_grads {
   float *dx, *d_logits, *d_router_expert, *dw1_base, *dw2_base, *du1, *dv1, *du2, *dv2;
 } cmoe_grads;
 
 /* Workspace of cmoe_backward for up to T_max tokens (0 for a bad handle, T_max < 0 or an
- * unsupported shape).  It holds the dense FP16 expert matrices and their FP32 gradients:
- * about 16 * G*K * d * d_ff bytes plus 4 * T_max * top_k * d_ff. */
+ * unsupported shape): per-token and per-pair activations and their transposed copies, about
+ * 16 * T_max * (top_k + 1) * d_ff bytes, plus the transposed bases, 4 * G * d * d_ff bytes. */
 size_t cmoe_backward_workspace_bytes(const cmoe_handle *h, int32_t T_max);
 int cmoe_backward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, const cmoe_f16 *dy,
                   int32_t T, const int32_t *expert_idx, const float *gate, const cmoe_grads *grads,

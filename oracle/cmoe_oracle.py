@@ -361,6 +361,70 @@ def backward_naive(w, x, dy, expert_idx, gate, K, q):
                 dv2=dv2, dgate_logits=dl)
 
 
+def backward_sampled(w, x, dy, expert_idx, gate, K, q, tokens, hidden):
+    """The part of backward_naive that can be computed one by one at any size, by the same
+    chain rule on materialised expert matrices (Eq. 7):
+      dx [len(tokens)][d], dgate_logits [len(tokens)][k]   of the given tokens (each depends
+          on its own token only);
+      for the given hidden indices n (rows of W1_e, columns of W2_e), whose h and da columns
+      over all tokens cost one matrix-vector product each:
+          dw1_base [G][len(hidden)][d], dw2_base [G][d][len(hidden)],
+          du1 [E][r][len(hidden)], dv2 [E][r][len(hidden)].
+    float64."""
+    X = np.asarray(x, dtype=np.float64)
+    DY = np.asarray(dy, dtype=np.float64)
+    tokens = np.asarray(tokens, dtype=np.int64)
+    hidden = np.asarray(hidden, dtype=np.int64)
+    T, d = X.shape
+    k = expert_idx.shape[1]
+    G = w["w1_base"].shape[0]
+    E = G * K
+    f = _factors(w, q)
+    r = f["u1"].shape[1]
+    RE = w["router_expert"].astype(np.float64)
+    nt, nh = len(tokens), len(hidden)
+    dx = np.zeros((nt, d))
+    dg = np.zeros((nt, k))
+    dw1 = np.zeros((G, nh, d)); dw2 = np.zeros((G, d, nh))
+    du1 = np.zeros((E, r, nh)); dv2 = np.zeros((E, r, nh))
+    e_tok = expert_idx[tokens]
+    for e in np.unique(expert_idx):
+        e = int(e)
+        c = e // K
+        # sampled tokens: the whole chain through the dense matrices of this expert
+        if np.any(e_tok == e):
+            W1, W2 = expert_weights(w, e, K, q, f)
+            for j in range(k):
+                sel = np.nonzero(e_tok[:, j] == e)[0]
+                if len(sel) == 0:
+                    continue
+                rows = tokens[sel]
+                h = X[rows] @ W1.T
+                a = gelu(h)
+                dg[sel, j] = (DY[rows] * (a @ W2.T)).sum(axis=1)
+                dh = ((gate[rows, j][:, None] * DY[rows]) @ W2) * gelu_grad(h)
+                dx[sel] += dh @ W1
+        # sampled hidden units: row n of W1_e and column n of W2_e against every pair of e
+        tt, jj = np.nonzero(expert_idx == e)
+        Xe = X[tt]
+        DOe = gate[tt, jj][:, None] * DY[tt]
+        w1rows = w["w1_base"][c][hidden].astype(np.float64) + f["u1"][e][:, hidden].T @ f["v1"][e]      # [nh][d]
+        w2cols = w["w2_base"][c][:, hidden].astype(np.float64) + f["u2"][e].T @ f["v2"][e][:, hidden]   # [d][nh]
+        h = Xe @ w1rows.T                    # [n_e][nh]
+        dh = (DOe @ w2cols) * gelu_grad(h)
+        dW1 = dh.T @ Xe                      # rows `hidden` of dW1_e
+        dW2 = DOe.T @ gelu(h)                # columns `hidden` of dW2_e
+        dw1[c] += dW1
+        dw2[c] += dW2
+        du1[e] = f["v1"][e] @ dW1.T
+        dv2[e] = f["u2"][e] @ dW2
+    gt = gate[tokens]
+    dl = gt * (dg - (gt * dg).sum(axis=1, keepdims=True))
+    for j in range(k):
+        dx += dl[:, j][:, None] * RE[e_tok[:, j].astype(np.int64)]
+    return dict(dx=dx, dgate_logits=dl, dw1_base=dw1, dw2_base=dw2, du1=du1, dv2=dv2)
+
+
 # ---------------------------------------------------------------- compression (Sec. 3.2, 3.4)
 # Construction of the stored form from dense expert matrices W_e [out][in]: the base of a
 # cluster is the mean of its experts (Eq. 6), each expert keeps a rank-r factorisation of

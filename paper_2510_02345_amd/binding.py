@@ -320,7 +320,8 @@ class Layer:
     def backward(self, x, dy, expert_idx, gate):
         """Gradients of sum(dy * y) for the frozen selection (expert_idx, gate): dict of f32
         tensors dx, d_logits, d_router_expert, dw1_base, dw2_base, du1, dv1, du2, dv2.  The
-        workspace (dense expert matrices and their gradients) is allocated on first use."""
+        workspace (activations per token and per pair, transposed bases) is allocated on first
+        use and kept."""
         t = self.torch
         c = self.cfg
         T = x.shape[0]

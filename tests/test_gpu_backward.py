@@ -150,3 +150,42 @@ def test_backward_rejects_more_than_64_experts():
     with pytest.raises(cm.CmoeError):
         layer.backward(_dev(w["x"]), _dev(w["x"]), _dev(np.zeros((8, 2), np.int32)), _dev(np.ones((8, 2), np.float32)))
     layer.close()
+
+
+def _sampled(cfg, clusters, n_tok, hidden, seed=0):
+    """Full-size run; dx and d_logits checked on sampled tokens of a few clusters, the weight
+    gradients on sampled hidden units (rows of dW1, columns of dW2) over every expert."""
+    import torch
+    import paper_2510_02345_amd as cm
+    print(f"case {cfg}", flush=True)
+    w = ci.generate(cfg)
+    rng = np.random.default_rng(cfg.seed + 7)
+    dy = rng.standard_normal((cfg.T, cfg.d)).astype(np.float16)
+    cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
+    pool = np.nonzero(np.isin(cid, clusters))[0]
+    tokens = np.sort(np.random.default_rng(seed).choice(pool, size=min(n_tok, len(pool)), replace=False))
+    hidden = np.asarray(hidden)
+    ref = orc.backward_sampled(w, w["x"], dy, eidx, gate, cfg.K, cfg.q, tokens, hidden)
+    print("oracle done", flush=True)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T)
+    out = layer.backward(_dev(w["x"]), _dev(dy), _dev(eidx.astype(np.int32)), _dev(gate.astype(np.float32)))
+    torch.cuda.synchronize()
+    ti, hi = _dev(tokens), _dev(hidden)
+    got = dict(dx=out["dx"][ti], dgate_logits=out["d_logits"][ti], dw1_base=out["dw1_base"][:, hi, :],
+               dw2_base=out["dw2_base"][:, :, hi], du1=out["du1"][:, :, hi], dv2=out["dv2"][:, :, hi])
+    for n in NAMES[1:]:
+        assert bool(torch.isfinite(out[n]).all()), n
+    for n, g in got.items():
+        m = orc.error_metrics(g.cpu().numpy().astype(np.float64), ref[n])
+        print(f"  {n}: max/rms={m['max_over_rms']:.3e} mean_rel={m['mean_rel']:.3e}", flush=True)
+        assert m["max_over_rms"] <= 2e-2, (n, m)
+        assert m["mean_rel"] <= 2e-3, (n, m)
+    layer.close()
+
+
+def test_backward_config2_zipf_loads_sampled():
+    _sampled(ci.config(2), clusters=[0, 3], n_tok=64, hidden=[0, 1, 2047, 2048, 4095])
+
+
+def test_backward_config3_sampled():
+    _sampled(ci.config(3), clusters=[2, 7], n_tok=64, hidden=[0, 255, 256, 4097, 8191])

@@ -652,3 +652,25 @@ def test_backward_matches_central_differences():
     unused = [e for e in range(E) if e not in set(eidx.reshape(-1).tolist())]
     for e in unused:
         assert not got["du1"][e].any() and not got["d_router_expert"][e].any()
+
+
+def test_backward_sampled_is_a_slice_of_the_full_backward():
+    """The token-wise / hidden-unit-wise form used at sizes where the dense per-expert gradients
+    do not fit must return exactly the corresponding slices of backward_naive, which the
+    central differences above pin."""
+    cfg = ci.small_config("bws", T=70, d=16, d_ff=24, G=3, K=3, r=4, k=2, q=4, seed=33)
+    w = ci.generate(cfg)
+    ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    rng = np.random.default_rng(34)
+    dy = rng.standard_normal((cfg.T, cfg.d))
+    full = orc.backward_naive(w, w["x"], dy, ref["expert_idx"], ref["gate"], cfg.K, cfg.q)
+    tokens = np.array([0, 3, 17, 42, 69])
+    hidden = np.array([1, 5, 23])
+    got = orc.backward_sampled(w, w["x"], dy, ref["expert_idx"], ref["gate"], cfg.K, cfg.q, tokens, hidden)
+    assert np.allclose(got["dx"], full["dx"][tokens], rtol=1e-11, atol=1e-13)
+    assert np.allclose(got["dgate_logits"], full["dgate_logits"][tokens], rtol=1e-11, atol=1e-13)
+    assert np.allclose(got["dw1_base"], full["dw1_base"][:, hidden, :], rtol=1e-11, atol=1e-13)
+    assert np.allclose(got["dw2_base"], full["dw2_base"][:, :, hidden], rtol=1e-11, atol=1e-13)
+    assert np.allclose(got["du1"], full["du1"][:, :, hidden], rtol=1e-11, atol=1e-13)
+    assert np.allclose(got["dv2"], full["dv2"][:, :, hidden], rtol=1e-11, atol=1e-13)
+    assert np.abs(full["dgate_logits"]).max() > 1e-3 and np.abs(full["du1"]).max() > 1e-3
