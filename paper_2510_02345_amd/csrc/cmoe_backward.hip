@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void bw_rows_kernel(int n_groups, int I, int* 
 }
 
 // One token per block.  For its k pairs (sorted rows p_j = invm[t k + j]):
-//   h = hb[t] + rh[p_j], da = dab[t] + rda[p_j]          FP32
+//   h = hb[t] + rh[p_j], da = dab[t] + rda[p_j]          FP32 sums of FP32 base and FP16 rank parts
 //   a16[p_j] = GELU(h), dh16[p_j] = g_j da GELU'(h), dg_j = da . GELU(h)
 //   dhsum16[t] = sum_j dh, ag16[t] = sum_j g_j GELU(h)
 // and the softmax backward over the selected logits (Eq. 10):
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void bw_rows_kernel(int n_groups, int I, int* 
 // of experts that share a base.
 template <int KMAX>
 __global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ hb, const float* __restrict__ dab,
-                                                     const float* __restrict__ rh, const float* __restrict__ rda,
+                                                     const half_t* __restrict__ rh, const half_t* __restrict__ rda,
                                                      const int* __restrict__ invm, const float* __restrict__ gate,
                                                      int k, int d_ff, half_t* __restrict__ a16,
                                                      half_t* __restrict__ dh16, half_t* __restrict__ dhsum16,
@@ -139,11 +139,11 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ h
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
       if (j >= k) break;
-      const float4v r1 = *(const float4v*)(rh + prow[j] * d_ff + col), r2 = *(const float4v*)(rda + prow[j] * d_ff + col);
+      const half4 r1 = *(const half4*)(rh + prow[j] * d_ff + col), r2 = *(const half4*)(rda + prow[j] * d_ff + col);
       half4 ao, ho;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float u = hv[i] + r1[i], z = dv[i] + r2[i];
+        const float u = hv[i] + (float)r1[i], z = dv[i] + (float)r2[i];
         const float cdf = 0.5f * (1.f + erff(u * 0.70710678118654752f));
         const float pdf = 0.3989422804014327f * __expf(-0.5f * u * u);
         const float a = u * cdf, dh = g[j] * z * (cdf + u * pdf);
@@ -332,8 +332,8 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.w2bt = take(sizeof(half_t) * G * f * d);
   L.hb = take(sizeof(float) * Tz * f);
   L.dab = take(sizeof(float) * Tz * f);
-  L.rh = take(sizeof(float) * M * f);
-  L.rda = take(sizeof(float) * M * f);
+  L.rh = take(sizeof(half_t) * M * f);
+  L.rda = take(sizeof(half_t) * M * f);
   L.a16 = take(sizeof(half_t) * M * f);
   L.dh16 = take(sizeof(half_t) * M * f);
   L.dhsum16 = take(sizeof(half_t) * Tz * f);
@@ -418,16 +418,16 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
     BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.hb), f, true);
     BW_GEMM(H(L.v1p), (long)RP * d, d, RP, x, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.t1), RP, false);
-    BW_GEMM(H(L.u1t), (long)f * RP, RP, f, H(L.t1), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, F(L.rh), f, true);
+    BW_GEMM(H(L.u1t), (long)f * RP, RP, f, H(L.t1), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, H(L.rh), f, false);
     // da = B2^T dy + V2^T (U2^T dy)
     BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.dab), f, true);
     BW_GEMM(H(L.u2p), (long)RP * d, d, RP, dy, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.uy), RP, false);
-    BW_GEMM(H(L.v2t), (long)f * RP, RP, f, H(L.uy), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, F(L.rda), f, true);
+    BW_GEMM(H(L.v2t), (long)f * RP, RP, f, H(L.uy), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, H(L.rda), f, false);
     if (k <= 2)
-      hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), F(L.rh), F(L.rda), invm, gate, k,
+      hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     else
-      hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), F(L.rh), F(L.rda), invm, gate, k,
+      hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
     BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);
