@@ -12,9 +12,11 @@
 //   dB1_c = sum_{t in c} (sum_j dh_m) x_t^T     dB2_c = sum_{t in c} dy_t (sum_j g_m a_m)^T
 //   dU1_e = sum_m dh_m (V1 x_t)^T   dV1_e = sum_m (U1^T dh_m) x_t^T
 //   dU2_e = sum_m g_m dy_t (V2 a_m)^T   dV2_e = sum_m g_m (U2^T dy_t) a_m^T
-// All products run on the grouped matrix-core kernel of the forward pass; those that
-// contract over rows do so after a transposing copy that pads every group to a multiple of
-// 32 columns.  Rank panels are padded to 32 rows.
+// All products but the factor gradients run on the grouped matrix-core kernel of the
+// forward pass; the base gradients, which contract over the tokens of a cluster, do so after
+// a transposing copy that pads every cluster to a multiple of 32 columns.  Rank panels are
+// padded to 32 rows.  The factor gradients (r output rows per expert) stream the pair rows
+// of the expert once on the vector ALUs.
 #include "cmoe_internal.h"
 
 namespace {
@@ -274,6 +276,84 @@ __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restr
   *(half8*)(dst + 8) = b;
 }
 
+// Factor gradients: part[sp][e][rho][n] = sum over the sorted pair rows p of expert e in
+// split sp of coef_p * t[p][rho] * D[row(p)][n], rho < R; row(p) = p (D in sorted pair order)
+// or permm[p] / k (D = x or dy); coef_p = gate[permm[p]] or 1.  The rows of an expert are cut
+// into RG_SPLIT equal runs, added in row order; bw_rankgrad_finish_kernel adds the runs in
+// order.  One thread owns C consecutive columns n.  Block (ceil(L / (256 C)), E, RG_SPLIT).
+constexpr int RG_SPLIT = 4;
+template <int R, int C>
+__global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restrict__ t, const half_t* __restrict__ D,
+                                                          int L, const int* __restrict__ offe,
+                                                          const int* __restrict__ permm, int k, int gather,
+                                                          const float* __restrict__ gate, int E,
+                                                          float* __restrict__ part) {
+  typedef _Float16 halfC __attribute__((ext_vector_type(C)));
+  const int e = blockIdx.y, sp = blockIdx.z;
+  const int col = (blockIdx.x * 256 + threadIdx.x) * C;
+  if (col >= L) return;
+  const int lo = offe[e], n = offe[e + 1] - lo;
+  const int per = (n + RG_SPLIT - 1) / RG_SPLIT;
+  const int p0 = lo + sp * per, p1 = min(lo + n, p0 + per);
+  float acc[R][C];
+#pragma unroll
+  for (int rho = 0; rho < R; ++rho)
+#pragma unroll
+    for (int i = 0; i < C; ++i) acc[rho][i] = 0.f;
+  for (int p = p0; p < p1; ++p) {
+    const int m = permm[p];
+    const size_t row = gather ? (size_t)(m / k) : (size_t)p;
+    const halfC v = *(const halfC*)(D + row * L + col);
+    const float cf = gate != nullptr ? gate[m] : 1.f;
+    float dv[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) dv[i] = cf * (float)v[i];
+    const half_t* tp = t + (size_t)p * RP;
+#pragma unroll
+    for (int rho = 0; rho < R; ++rho) {
+      const float tv = (float)tp[rho];
+#pragma unroll
+      for (int i = 0; i < C; ++i) acc[rho][i] += tv * dv[i];
+    }
+  }
+#pragma unroll
+  for (int rho = 0; rho < R; ++rho) {
+    float* dst = part + (((size_t)sp * E + e) * R + rho) * L + col;
+#pragma unroll
+    for (int i = 0; i < C; i += 4) *(float4v*)(dst + i) = float4v{acc[rho][i], acc[rho][i + 1], acc[rho][i + 2], acc[rho][i + 3]};
+  }
+}
+
+// out[i] = part[0][i] + part[1][i] + ... in split order, i < n (a multiple of 4)
+__global__ __launch_bounds__(256) void bw_rankgrad_finish_kernel(const float* __restrict__ part, size_t n,
+                                                                 float* __restrict__ out) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  float4v acc = *(const float4v*)(part + i);
+  for (int sp = 1; sp < RG_SPLIT; ++sp) acc += *(const float4v*)(part + sp * n + i);
+  *(float4v*)(out + i) = acc;
+}
+
+template <int R>
+void rankgrad_r(const half_t* t, const half_t* D, int L, const int* offe, const int* permm, int k, int gather,
+                const float* gate, int E, float* part, float* out, hipStream_t st) {
+  constexpr int C = R >= 32 ? 4 : 8;
+  hipLaunchKernelGGL((bw_rankgrad_kernel<R, C>), dim3((L + 256 * C - 1) / (256 * C), E, RG_SPLIT), dim3(256), 0, st, t,
+                     D, L, offe, permm, k, gather, gate, E, part);
+  const size_t n = (size_t)E * R * L;
+  hipLaunchKernelGGL(bw_rankgrad_finish_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st, part, n, out);
+}
+
+void rankgrad(int r, const half_t* t, const half_t* D, int L, const int* offe, const int* permm, int k, int gather,
+              const float* gate, int E, float* part, float* out, hipStream_t st) {
+  switch (r) {
+    case 4: rankgrad_r<4>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
+    case 8: rankgrad_r<8>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
+    case 16: rankgrad_r<16>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
+    default: rankgrad_r<32>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
+  }
+}
+
 inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 void transpose(const half_t* src, int ld, int I, const int* idx, const float* scale, int Npad, half_t* out,
@@ -289,9 +369,8 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   const size_t E = (size_t)dm.G * dm.K, G = dm.G, Tz = (size_t)(T > 0 ? T : 0), M = Tz * dm.k;
   const size_t d = dm.d, f = dm.d_ff, r = dm.r;
   L.M = (int)M;
-  L.Mpad = (int)((M + 32 * E + 63) / 64 * 64);
   L.Tpad = (int)((Tz + 32 * G + 63) / 64 * 64);
-  const size_t Mp = L.Mpad, Tp = L.Tpad;
+  const size_t Tp = L.Tpad;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     const size_t at = off;
@@ -307,19 +386,13 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.permm = take(sizeof(int) * M);
   L.invm = take(sizeof(int) * M);
   L.offe = take(sizeof(int) * (E + 1));
-  L.krange_p = take(sizeof(int) * 2 * E);
   L.krange_c = take(sizeof(int) * 2 * G);
-  L.srow_p = take(sizeof(int) * Mp);
-  L.ssrc_p = take(sizeof(int) * Mp);
-  L.sgate_p = take(sizeof(float) * Mp);
   L.srow_c = take(sizeof(int) * Tp);
   L.ssrc_c = take(sizeof(int) * Tp);
   L.offx_f = take(sizeof(int) * (G + 1));
   L.gidx_f = take(sizeof(int) * G * f);
   L.offx_d = take(sizeof(int) * (G + 1));
   L.gidx_d = take(sizeof(int) * G * d);
-  L.offx_r = take(sizeof(int) * (E + 1));
-  L.gidx_r = take(sizeof(int) * E * r);
   L.dl = take(sizeof(float) * M);
   L.v1p = take(sizeof(half_t) * E * 32 * d);
   L.u2p = take(sizeof(half_t) * E * 32 * d);
@@ -344,18 +417,11 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.ss = take(sizeof(half_t) * M * 32);
   L.dxb = take(sizeof(float) * Tz * d);
   L.dxr = take(sizeof(float) * M * d);
-  L.xpt = take(sizeof(half_t) * d * Mp);
-  L.dot = take(sizeof(half_t) * d * Mp);
-  L.at = take(sizeof(half_t) * f * Mp);
-  L.dht = take(sizeof(half_t) * f * Mp);
-  L.t1t = take(sizeof(half_t) * 32 * Mp);
-  L.qt = take(sizeof(half_t) * 32 * Mp);
-  L.st = take(sizeof(half_t) * 32 * Mp);
-  L.uyt = take(sizeof(half_t) * 32 * Mp);
   L.xct = take(sizeof(half_t) * d * Tp);
   L.dyct = take(sizeof(half_t) * d * Tp);
   L.dhst = take(sizeof(half_t) * f * Tp);
   L.agt = take(sizeof(half_t) * f * Tp);
+  L.rgpart = take(sizeof(float) * RG_SPLIT * E * r * (f > d ? f : d));
   L.total = off;
   return L;
 }
@@ -363,13 +429,12 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
 hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, const half_t* dy, int T,
                            const int* expert_idx, const float* gate, const cmoe_grads& out, char* ws,
                            const cmoe_bw_layout& L, hipStream_t st) {
-  const int E = dm.G * dm.K, G = dm.G, d = dm.d, f = dm.d_ff, r = dm.r, k = dm.k, M = L.M, Mpad = L.Mpad,
-            Tpad = L.Tpad;
+  const int E = dm.G * dm.K, G = dm.G, d = dm.d, f = dm.d_ff, r = dm.r, k = dm.k, M = L.M, Tpad = L.Tpad;
   auto I = [&](size_t o) { return (int*)(ws + o); };
   auto H = [&](size_t o) { return (half_t*)(ws + o); };
   auto F = [&](size_t o) { return (float*)(ws + o); };
   int *permc = I(L.permc), *offc = I(L.offc), *permm = I(L.permm), *invm = I(L.invm), *offe = I(L.offe);
-  int *krp = I(L.krange_p), *krc = I(L.krange_c);
+  int* krc = I(L.krange_c);
   float* dl = out.d_logits ? out.d_logits : F(L.dl);
   const long mat = (long)f * d;
   const half_t *w1b = (const half_t*)w.w1_base, *w2b = (const half_t*)w.w2_base;
@@ -386,16 +451,12 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     hipLaunchKernelGGL(bw_cluster_kernel, dim3((T + 255) / 256), dim3(256), 0, st, expert_idx, T, k, dm.K, I(L.cid));
   BW_CHECK(launch_permute_bins(G, I(L.cid), T, permc, I(L.invc), offc, I(L.blk_counts), st));
   BW_CHECK(launch_permute_bins(E, expert_idx, M, permm, invm, offe, I(L.blk_counts), st));
-  hipLaunchKernelGGL(bw_map_kernel, dim3((Mpad + 255) / 256), dim3(256), 0, st, offe, permm, gate, E, k, Mpad, krp,
-                     I(L.srow_p), I(L.ssrc_p), F(L.sgate_p));
   hipLaunchKernelGGL(bw_map_kernel, dim3((Tpad + 255) / 256), dim3(256), 0, st, offc, permc, (const float*)nullptr, G,
                      1, Tpad, krc, I(L.srow_c), I(L.ssrc_c), (float*)nullptr);
   hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)G * f + 256) / 256)), dim3(256), 0, st, G, f,
                      I(L.offx_f), I(L.gidx_f));
   hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)G * d + 256) / 256)), dim3(256), 0, st, G, d,
                      I(L.offx_d), I(L.gidx_d));
-  hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)E * r + 256) / 256)), dim3(256), 0, st, E, r,
-                     I(L.offx_r), I(L.gidx_r));
   // no token: the products below find empty groups and write zero gradients
   if (T > 0) {
     // operand panels: rank factors and transposed bases
@@ -437,17 +498,8 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                        (const half_t*)w.router_expert, k, d, out.dx);
     // s = V2 a per pair
     BW_GEMM(H(L.v2p), (long)RP * f, f, RP, H(L.a16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.ss), RP, false);
-    // transposed, group-padded copies for the products that contract over rows
-    const int *srow_p = I(L.srow_p), *ssrc_p = I(L.ssrc_p), *ssrc_c = I(L.ssrc_c);
-    const float* sgate_p = F(L.sgate_p);
-    transpose(x, d, d, ssrc_p, nullptr, Mpad, H(L.xpt), st);
-    transpose(dy, d, d, ssrc_p, sgate_p, Mpad, H(L.dot), st);
-    transpose(H(L.a16), f, f, srow_p, nullptr, Mpad, H(L.at), st);
-    transpose(H(L.dh16), f, f, srow_p, nullptr, Mpad, H(L.dht), st);
-    transpose(H(L.t1), RP, RP, srow_p, nullptr, Mpad, H(L.t1t), st);
-    transpose(H(L.qq), RP, RP, srow_p, nullptr, Mpad, H(L.qt), st);
-    transpose(H(L.ss), RP, RP, srow_p, nullptr, Mpad, H(L.st), st);
-    transpose(H(L.uy), RP, RP, srow_p, sgate_p, Mpad, H(L.uyt), st);
+    // transposed, cluster-padded copies for the base gradients (contraction over tokens)
+    const int* ssrc_c = I(L.ssrc_c);
     transpose(x, d, d, ssrc_c, nullptr, Tpad, H(L.xct), st);
     transpose(dy, d, d, ssrc_c, nullptr, Tpad, H(L.dyct), st);
     transpose(H(L.dhsum16), f, f, ssrc_c, nullptr, Tpad, H(L.dhst), st);
@@ -461,15 +513,12 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
           out.dw1_base, d, true);
   BW_GEMM(H(L.agt), 0, Tpad, f, H(L.dyct), Tpad, I(L.gidx_d), 1, Tpad, I(L.offx_d), G, G * d, krc, nullptr,
           out.dw2_base, f, true);
-  // factor gradients: contraction over the pairs of an expert, r output rows per expert
-  BW_GEMM(H(L.dht), 0, Mpad, f, H(L.t1t), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.du1, f,
-          true);
-  BW_GEMM(H(L.xpt), 0, Mpad, d, H(L.qt), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.dv1, d,
-          true);
-  BW_GEMM(H(L.dot), 0, Mpad, d, H(L.st), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.du2, d,
-          true);
-  BW_GEMM(H(L.at), 0, Mpad, f, H(L.uyt), Mpad, I(L.gidx_r), 1, Mpad, I(L.offx_r), E, E * r, krp, nullptr, out.dv2, f,
-          true);
+  // factor gradients: contraction over the pairs of an expert, streamed once
+  float* part = F(L.rgpart);
+  rankgrad(r, H(L.t1), H(L.dh16), f, offe, permm, k, 0, nullptr, E, part, out.du1, st);
+  rankgrad(r, H(L.qq), x, d, offe, permm, k, 1, nullptr, E, part, out.dv1, st);
+  rankgrad(r, H(L.ss), dy, d, offe, permm, k, 1, gate, E, part, out.du2, st);
+  rankgrad(r, H(L.uy), H(L.a16), f, offe, permm, k, 0, gate, E, part, out.dv2, st);
 #undef BW_GEMM
 #undef BW_CHECK
   return hipGetLastError();

@@ -136,21 +136,21 @@ hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* 
                           const int* perm, const int* offsets, const int* expert_idx, const float* gate, int T,
                           half_t* y, hipStream_t st);
 
-// Workspace of the backward pass (byte offsets).  M = T * top_k pair rows; Mpad / Tpad =
-// columns of the transposed copies whose groups (experts / clusters) are padded to 32.
+// Workspace of the backward pass (byte offsets).  M = T * top_k pair rows; Tpad = columns of
+// the transposed copies whose groups (clusters) are padded to 32.
 struct cmoe_bw_layout {
-  int M, Mpad, Tpad;
-  size_t blk_counts, cid, permc, invc, offc, permm, invm, offe, krange_p, krange_c;
-  size_t srow_p, ssrc_p, sgate_p, srow_c, ssrc_c;
-  size_t offx_f, gidx_f, offx_d, gidx_d, offx_r, gidx_r, dl;
+  int M, Tpad;
+  size_t blk_counts, cid, permc, invc, offc, permm, invm, offe, krange_c;
+  size_t srow_c, ssrc_c;
+  size_t offx_f, gidx_f, offx_d, gidx_d, dl;
   size_t v1p, u2p, u1p, v2p, v1t, u1t, v2t;   // f16 rank panels [E][32][L] / [E][L][32]
   size_t w1bt, w2bt;                          // f16 transposed bases
   size_t hb, dab, rh, rda;                    // f32 [T][d_ff] x2 (token order), f16 [M][d_ff] x2 (sorted pairs)
   size_t a16, dh16, dhsum16, ag16;            // f16 [M][d_ff] x2, [T][d_ff] x2
   size_t t1, uy, qq, ss;                      // f16 [M][32] rank-space rows of the pairs
   size_t dxb, dxr;                            // f32 [T][d], [M][d]
-  size_t xpt, dot, at, dht, t1t, qt, st, uyt; // f16 transposed copies, Mpad columns
   size_t xct, dyct, dhst, agt;                // f16 transposed copies, Tpad columns
+  size_t rgpart;                              // f32 [4][E][r][max(d, d_ff)] partial factor gradients
   size_t total;
 };
 cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T);
