@@ -27,34 +27,23 @@ __device__ __forceinline__ float nib_val(unsigned byte, int odd) {
   return (float)(odd ? ((int)(byte << 24) >> 28) : ((int)(byte << 28) >> 28));
 }
 
-// FP16 panels of one INT4 factor F [E][r][L] (value = scale * code): rows_out [E][32][L]
-// (rank rows >= r zero) and / or trans_out [E][L][32].  Experts without pairs are skipped:
-// their stored factors are never read.  Block (L / 256, E).
+// FP16 panel of one INT4 factor F [E][r][L] (value = scale * code): rows_out [E][32][L], rank
+// rows >= r zero.  Experts without pairs are skipped: their stored factors are never read.
+// Block (L / 256, E).
 __global__ __launch_bounds__(256) void bw_panel_kernel(const uint8_t* __restrict__ qv, const half_t* __restrict__ sv,
                                                        int L, int q, int r, const int* __restrict__ offe,
-                                                       half_t* __restrict__ rows_out,
-                                                       half_t* __restrict__ trans_out) {
+                                                       half_t* __restrict__ rows_out) {
   const int e = blockIdx.y;
   if (offe[e + 1] == offe[e]) return;
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= L) return;
-  half_t v[RP];
-#pragma unroll
   for (int rho = 0; rho < RP; ++rho) {
     float f = 0.f;
     if (rho < r) {
       const size_t row = (size_t)e * r + rho;
       f = (float)sv[row * (L / q) + i / q] * nib_val(qv[row * (L / 2) + i / 2], i & 1);
     }
-    v[rho] = (half_t)f;
-    if (rows_out != nullptr) rows_out[((size_t)e * RP + rho) * L + i] = v[rho];
-  }
-  if (trans_out != nullptr) {
-    half8* dst = (half8*)(trans_out + ((size_t)e * L + i) * RP);
-#pragma unroll
-    for (int b = 0; b < RP / 8; ++b)
-      dst[b] = half8{v[8 * b], v[8 * b + 1], v[8 * b + 2], v[8 * b + 3], v[8 * b + 4], v[8 * b + 5], v[8 * b + 6],
-                     v[8 * b + 7]};
+    rows_out[((size_t)e * RP + rho) * L + i] = (half_t)f;
   }
 }
 
@@ -276,6 +265,59 @@ __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restr
   *(half8*)(dst + 8) = b;
 }
 
+// Rank-space rows back to full width: out[row(p)][n] = sum_{rho < R} t[p][rho] P[e][rho][n] for
+// the sorted pair rows p of expert e (P = a [E][32][L] panel), row(p) = rowmap ? rowmap[p] : p.
+// A thread keeps its 4 columns of the R panel rows in registers and walks the rows of its
+// run.  Block (ceil(L / 1024), E, RX_SPLIT).
+constexpr int RX_SPLIT = 8;
+template <int R, class OutT>
+__global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __restrict__ t,
+                                                            const half_t* __restrict__ P, int L,
+                                                            const int* __restrict__ offe,
+                                                            const int* __restrict__ rowmap, OutT* __restrict__ out) {
+  const int e = blockIdx.y, sp = blockIdx.z;
+  const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (col >= L) return;
+  const int lo = offe[e], n = offe[e + 1] - lo;
+  const int per = (n + RX_SPLIT - 1) / RX_SPLIT;
+  const int p0 = lo + sp * per, p1 = min(lo + n, p0 + per);
+  if (p0 >= p1) return;
+  float w[R][4];
+#pragma unroll
+  for (int rho = 0; rho < R; ++rho) {
+    const half4 v = *(const half4*)(P + ((size_t)e * RP + rho) * L + col);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[rho][i] = (float)v[i];
+  }
+  for (int p = p0; p < p1; ++p) {
+    const half_t* tp = t + (size_t)p * RP;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rho = 0; rho < R; ++rho) {
+      const float tv = (float)tp[rho];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] += tv * w[rho][i];
+    }
+    const size_t row = rowmap != nullptr ? (size_t)rowmap[p] : (size_t)p;
+    if constexpr (sizeof(OutT) == 2)
+      *(half4*)(out + row * L + col) = half4{(half_t)acc[0], (half_t)acc[1], (half_t)acc[2], (half_t)acc[3]};
+    else
+      *(float4v*)(out + row * L + col) = float4v{acc[0], acc[1], acc[2], acc[3]};
+  }
+}
+
+template <class OutT>
+void rankexpand(int r, const half_t* t, const half_t* P, int L, const int* offe, const int* rowmap, int E, OutT* out,
+                hipStream_t st) {
+  const dim3 grid((L + 1023) / 1024, E, RX_SPLIT), block(256);
+  switch (r) {
+    case 4: hipLaunchKernelGGL((bw_rankexpand_kernel<4, OutT>), grid, block, 0, st, t, P, L, offe, rowmap, out); break;
+    case 8: hipLaunchKernelGGL((bw_rankexpand_kernel<8, OutT>), grid, block, 0, st, t, P, L, offe, rowmap, out); break;
+    case 16: hipLaunchKernelGGL((bw_rankexpand_kernel<16, OutT>), grid, block, 0, st, t, P, L, offe, rowmap, out); break;
+    default: hipLaunchKernelGGL((bw_rankexpand_kernel<32, OutT>), grid, block, 0, st, t, P, L, offe, rowmap, out); break;
+  }
+}
+
 // Factor gradients: part[sp][e][rho][n] = sum over the sorted pair rows p of expert e in
 // split sp of coef_p * t[p][rho] * D[row(p)][n], rho < R; row(p) = p (D in sorted pair order)
 // or permm[p] / k (D = x or dy); coef_p = gate[permm[p]] or 1.  The rows of an expert are cut
@@ -398,9 +440,6 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.u2p = take(sizeof(half_t) * E * 32 * d);
   L.u1p = take(sizeof(half_t) * E * 32 * f);
   L.v2p = take(sizeof(half_t) * E * 32 * f);
-  L.v1t = take(sizeof(half_t) * E * 32 * d);
-  L.u1t = take(sizeof(half_t) * E * 32 * f);
-  L.v2t = take(sizeof(half_t) * E * 32 * f);
   L.w1bt = take(sizeof(half_t) * G * f * d);
   L.w2bt = take(sizeof(half_t) * G * f * d);
   L.hb = take(sizeof(float) * Tz * f);
@@ -462,13 +501,13 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     // operand panels: rank factors and transposed bases
     const int q = dm.q;
     hipLaunchKernelGGL(bw_panel_kernel, dim3((d + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v1_q,
-                       (const half_t*)w.v1_s, d, q, r, offe, H(L.v1p), H(L.v1t));
+                       (const half_t*)w.v1_s, d, q, r, offe, H(L.v1p));
     hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.u1_q,
-                       (const half_t*)w.u1_s, f, q, r, offe, H(L.u1p), H(L.u1t));
+                       (const half_t*)w.u1_s, f, q, r, offe, H(L.u1p));
     hipLaunchKernelGGL(bw_panel_kernel, dim3((d + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.u2_q,
-                       (const half_t*)w.u2_s, d, q, r, offe, H(L.u2p), (half_t*)nullptr);
+                       (const half_t*)w.u2_s, d, q, r, offe, H(L.u2p));
     hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v2_q,
-                       (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p), H(L.v2t));
+                       (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p));
     // w1bt [G][d][d_ff] = B1^T, w2bt [G][d_ff][d] = B2^T
     hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, d, (const int*)nullptr,
                        (const float*)nullptr, f, offc, (size_t)mat, H(L.w1bt));
@@ -479,11 +518,11 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
     BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.hb), f, true);
     BW_GEMM(H(L.v1p), (long)RP * d, d, RP, x, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.t1), RP, false);
-    BW_GEMM(H(L.u1t), (long)f * RP, RP, f, H(L.t1), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, H(L.rh), f, false);
+    rankexpand(r, H(L.t1), H(L.u1p), f, offe, nullptr, E, H(L.rh), st);
     // da = B2^T dy + V2^T (U2^T dy)
     BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.dab), f, true);
     BW_GEMM(H(L.u2p), (long)RP * d, d, RP, dy, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.uy), RP, false);
-    BW_GEMM(H(L.v2t), (long)f * RP, RP, f, H(L.uy), RP, nullptr, 1, RP, offe, E, M, nullptr, nullptr, H(L.rda), f, false);
+    rankexpand(r, H(L.uy), H(L.v2p), f, offe, nullptr, E, H(L.rda), st);
     if (k <= 2)
       hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
@@ -493,7 +532,7 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
     BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);
     BW_GEMM(H(L.u1p), (long)RP * f, f, RP, H(L.dh16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.qq), RP, false);
-    BW_GEMM(H(L.v1t), (long)d * RP, RP, d, H(L.qq), RP, nullptr, 1, RP, offe, E, M, nullptr, permm, F(L.dxr), d, true);
+    rankexpand(r, H(L.qq), H(L.v1p), d, offe, permm, E, F(L.dxr), st);
     hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, F(L.dxb), F(L.dxr), dl, expert_idx,
                        (const half_t*)w.router_expert, k, d, out.dx);
     // s = V2 a per pair
