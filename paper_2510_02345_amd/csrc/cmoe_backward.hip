@@ -100,15 +100,16 @@ __global__ __launch_bounds__(256) void bw_rows_kernel(int n_groups, int I, int* 
 }
 
 // One token per block.  For its k pairs (sorted rows p_j = invm[t k + j]):
-//   h = hb[t] + rh[p_j], da = dab[t] + rda[p_j]          FP32 sums of FP32 base and FP16 rank parts
+//   h = hb[t] + rh[p_j], da = dab[t] + rda[p_j]          FP32 sums of FP16 base and rank parts
 //   a16[p_j] = GELU(h), dh16[p_j] = g_j da GELU'(h), dg_j = da . GELU(h)
 //   dhsum16[t] = sum_j dh, ag16[t] = sum_j g_j GELU(h)
 // and the softmax backward over the selected logits (Eq. 10):
 //   dl_j = g_j (dg_j - sum_i g_i dg_i).
-// dg is taken from the FP32 values: the gate gradient is a difference of nearly equal dg
-// of experts that share a base.
+// The gate gradient is a difference of nearly equal dg of experts that share a base: the
+// base parts hb, dab enter every dg_j of the token with the same rounding, so the
+// differences keep the relative accuracy of the rank parts.
 template <int KMAX>
-__global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ hb, const float* __restrict__ dab,
+__global__ __launch_bounds__(256) void bw_act_kernel(const half_t* __restrict__ hb, const half_t* __restrict__ dab,
                                                      const half_t* __restrict__ rh, const half_t* __restrict__ rda,
                                                      const int* __restrict__ invm, const float* __restrict__ gate,
                                                      int k, int d_ff, half_t* __restrict__ a16,
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ h
     dot[j] = 0.f;
   }
   for (int col = threadIdx.x * 4; col < d_ff; col += 1024) {
-    const float4v hv = *(const float4v*)(hb + t * d_ff + col), dv = *(const float4v*)(dab + t * d_ff + col);
+    const half4 hv = *(const half4*)(hb + t * d_ff + col), dv = *(const half4*)(dab + t * d_ff + col);
     float dhs[4] = {0.f, 0.f, 0.f, 0.f}, ags[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const float* __restrict__ h
       half4 ao, ho;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float u = hv[i] + (float)r1[i], z = dv[i] + (float)r2[i];
+        const float u = (float)hv[i] + (float)r1[i], z = (float)dv[i] + (float)r2[i];
         const float cdf = 0.5f * (1.f + erff(u * 0.70710678118654752f));
         const float pdf = 0.3989422804014327f * __expf(-0.5f * u * u);
         const float a = u * cdf, dh = g[j] * z * (cdf + u * pdf);
@@ -289,20 +290,32 @@ __global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __rest
 #pragma unroll
     for (int i = 0; i < 4; ++i) w[rho][i] = (float)v[i];
   }
-  for (int p = p0; p < p1; ++p) {
-    const half_t* tp = t + (size_t)p * RP;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int pb = p0; pb < p1; pb += 4) {
+    float acc[4][4];
+    size_t row[4];
 #pragma unroll
-    for (int rho = 0; rho < R; ++rho) {
-      const float tv = (float)tp[rho];
+    for (int u = 0; u < 4; ++u) {
+      const int p = min(pb + u, p1 - 1);
+      row[u] = rowmap != nullptr ? (size_t)rowmap[p] : (size_t)p;
+      const half_t* tp = t + (size_t)p * RP;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] += tv * w[rho][i];
+      for (int i = 0; i < 4; ++i) acc[u][i] = 0.f;
+#pragma unroll
+      for (int rho = 0; rho < R; ++rho) {
+        const float tv = (float)tp[rho];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[u][i] += tv * w[rho][i];
+      }
     }
-    const size_t row = rowmap != nullptr ? (size_t)rowmap[p] : (size_t)p;
-    if constexpr (sizeof(OutT) == 2)
-      *(half4*)(out + row * L + col) = half4{(half_t)acc[0], (half_t)acc[1], (half_t)acc[2], (half_t)acc[3]};
-    else
-      *(float4v*)(out + row * L + col) = float4v{acc[0], acc[1], acc[2], acc[3]};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (pb + u >= p1) break;
+      if constexpr (sizeof(OutT) == 2)
+        *(half4*)(out + row[u] * L + col) =
+            half4{(half_t)acc[u][0], (half_t)acc[u][1], (half_t)acc[u][2], (half_t)acc[u][3]};
+      else
+        *(float4v*)(out + row[u] * L + col) = float4v{acc[u][0], acc[u][1], acc[u][2], acc[u][3]};
+    }
   }
 }
 
@@ -342,20 +355,30 @@ __global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restri
   for (int rho = 0; rho < R; ++rho)
 #pragma unroll
     for (int i = 0; i < C; ++i) acc[rho][i] = 0.f;
-  for (int p = p0; p < p1; ++p) {
-    const int m = permm[p];
-    const size_t row = gather ? (size_t)(m / k) : (size_t)p;
-    const halfC v = *(const halfC*)(D + row * L + col);
-    const float cf = gate != nullptr ? gate[m] : 1.f;
-    float dv[C];
+  // four rows per batch: their loads are issued before the first is used
+  for (int pb = p0; pb < p1; pb += 4) {
+    halfC v[4];
+    float cf[4];
 #pragma unroll
-    for (int i = 0; i < C; ++i) dv[i] = cf * (float)v[i];
-    const half_t* tp = t + (size_t)p * RP;
+    for (int u = 0; u < 4; ++u) {
+      const int p = min(pb + u, p1 - 1);
+      const int m = permm[p];
+      const size_t row = gather ? (size_t)(m / k) : (size_t)p;
+      v[u] = *(const halfC*)(D + row * L + col);
+      cf[u] = pb + u < p1 ? (gate != nullptr ? gate[m] : 1.f) : 0.f;
+    }
 #pragma unroll
-    for (int rho = 0; rho < R; ++rho) {
-      const float tv = (float)tp[rho];
+    for (int u = 0; u < 4; ++u) {
+      float dv[C];
 #pragma unroll
-      for (int i = 0; i < C; ++i) acc[rho][i] += tv * dv[i];
+      for (int i = 0; i < C; ++i) dv[i] = cf[u] * (float)v[u][i];
+      const half_t* tp = t + (size_t)min(pb + u, p1 - 1) * RP;
+#pragma unroll
+      for (int rho = 0; rho < R; ++rho) {
+        const float tv = (float)tp[rho];
+#pragma unroll
+        for (int i = 0; i < C; ++i) acc[rho][i] += tv * dv[i];
+      }
     }
   }
 #pragma unroll
@@ -442,8 +465,8 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.v2p = take(sizeof(half_t) * E * 32 * f);
   L.w1bt = take(sizeof(half_t) * G * f * d);
   L.w2bt = take(sizeof(half_t) * G * f * d);
-  L.hb = take(sizeof(float) * Tz * f);
-  L.dab = take(sizeof(float) * Tz * f);
+  L.hb = take(sizeof(half_t) * Tz * f);
+  L.dab = take(sizeof(half_t) * Tz * f);
   L.rh = take(sizeof(half_t) * M * f);
   L.rda = take(sizeof(half_t) * M * f);
   L.a16 = take(sizeof(half_t) * M * f);
@@ -516,18 +539,18 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     BW_CHECK(hipGetLastError());
 
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
-    BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.hb), f, true);
+    BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.hb), f, false);
     BW_GEMM(H(L.v1p), (long)RP * d, d, RP, x, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.t1), RP, false);
     rankexpand(r, H(L.t1), H(L.u1p), f, offe, nullptr, E, H(L.rh), st);
     // da = B2^T dy + V2^T (U2^T dy)
-    BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, F(L.dab), f, true);
+    BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.dab), f, false);
     BW_GEMM(H(L.u2p), (long)RP * d, d, RP, dy, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.uy), RP, false);
     rankexpand(r, H(L.uy), H(L.v2p), f, offe, nullptr, E, H(L.rda), st);
     if (k <= 2)
-      hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), H(L.rh), H(L.rda), invm, gate, k,
+      hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, H(L.hb), H(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     else
-      hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, F(L.hb), F(L.dab), H(L.rh), H(L.rda), invm, gate, k,
+      hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, H(L.hb), H(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
     BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);

@@ -145,7 +145,7 @@ struct cmoe_bw_layout {
   size_t offx_f, gidx_f, offx_d, gidx_d, dl;
   size_t v1p, u2p, u1p, v2p;                  // f16 rank panels [E][32][L]
   size_t w1bt, w2bt;                          // f16 transposed bases
-  size_t hb, dab, rh, rda;                    // f32 [T][d_ff] x2 (token order), f16 [M][d_ff] x2 (sorted pairs)
+  size_t hb, dab, rh, rda;                    // f16 [T][d_ff] x2 (token order), [M][d_ff] x2 (sorted pairs)
   size_t a16, dh16, dhsum16, ag16;            // f16 [M][d_ff] x2, [T][d_ff] x2
   size_t t1, uy, qq, ss;                      // f16 [M][32] rank-space rows of the pairs
   size_t dxb, dxr;                            // f32 [T][d], [M][d]
