@@ -254,8 +254,9 @@ typedef struct cmoe_grads {
 } cmoe_grads;
 
 /* Workspace of cmoe_backward for up to T_max tokens (0 for a bad handle, T_max < 0 or an
- * unsupported shape): per-token and per-pair activations and their transposed copies, about
- * 16 * T_max * (top_k + 1) * d_ff bytes, plus the transposed bases, 4 * G * d * d_ff bytes. */
+ * unsupported shape): per-token and per-pair activations, about
+ * (8 * top_k + 12) * T_max * d_ff bytes, plus the transposed bases, 4 * G * d * d_ff bytes,
+ * the rank panels and partial results. */
 size_t cmoe_backward_workspace_bytes(const cmoe_handle *h, int32_t T_max);
 int cmoe_backward(cmoe_handle *h, const cmoe_weights *w, const cmoe_f16 *x, const cmoe_f16 *dy,
                   int32_t T, const int32_t *expert_idx, const float *gate, const cmoe_grads *grads,
