@@ -236,6 +236,8 @@ int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W
  * expert_idx [T][top_k] and gate [T][top_k] (the softmax of Eq. 10 over the selected
  * logits, as cmoe_route returns them).  The selection itself (cluster and expert argmax)
  * is piecewise constant and carries no gradient; the cluster router receives none.
+ * Precondition (not checked): the top_k experts of a token lie in one cluster, as
+ * cmoe_route produces them; the shared-base products are taken once per token.
  * All outputs are FP32 device buffers and are overwritten:
  *   dx              [T][d]         through the experts and through the gate logits
  *   d_logits        [T][top_k]     dL / d(selected expert logits); may be NULL

@@ -189,3 +189,8 @@ def test_backward_config2_zipf_loads_sampled():
 
 def test_backward_config3_sampled():
     _sampled(ci.config(3), clusters=[2, 7], n_tok=64, hidden=[0, 255, 256, 4097, 8191])
+
+
+def test_backward_config4_weight_bound_sampled():
+    # 64 tokens, every cluster hit, r = 32: tokens of one cluster, a few hidden units
+    _sampled(ci.config(4), clusters=[5], n_tok=8, hidden=[0, 1023, 1024, 14335])
