@@ -1113,6 +1113,14 @@ hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, co
              0, 0};
   g.x_div = x_div;
   g.krange = krange;
+  if (N <= 64 && !out_f32) {
+    // a few output columns per row (products into rank space): one 64-row weight tile, the
+    // launch is bound by the stream of X rows
+    using TN = Tile<64, 128, 1, 4, 4, 3, false, 8, 1>;
+    g.n_tiles = 1;
+    EpiStore epi{(half_t*)out, rowmap, ldo, N};
+    return launch_gemm<TN, EpiStore>(g, rows, epi, st);
+  }
   if (out_f32) {
     EpiStoreT<float> epi{(float*)out, rowmap, ldo, N};
     return launch_gemm<TL, EpiStoreT<float>, TileTail>(g, rows, epi, st);
