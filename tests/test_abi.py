@@ -135,3 +135,30 @@ def test_new_entry_points_reject_bad_arguments_without_touching_the_gpu():
     assert L.cmoe_compress(C.byref(good), fake, fake, fake, fake, fake, fake, fake, fake, fake, 16, None) == B.ERR_WORKSPACE
     assert L.cmoe_quantize_int4(fake, 4, 64, 24, fake, fake, None) == B.ERR_INVALID_ARG    # q does not divide L
     assert L.cmoe_quantize_int4(fake, 0, 64, 8, fake, fake, None) == B.OK                  # no rows: no-op
+
+
+def test_backward_rejects_bad_arguments_without_touching_the_gpu():
+    rc, h = _create(d=768, d_ff=3072, G=2, K=4, r=8, top_k=2, q_group=32)
+    L = cm.lib()
+    fake = 0x1000
+    w2 = B.Weights(*([fake] * 13))
+    g = B.Grads(*([fake] * 9))
+    need = L.cmoe_backward_workspace_bytes(h, 4096)
+    # per-token and per-pair FP16 activations and the transposed bases at least
+    assert need > (8 * 2 + 12) * 4096 * 3072 + 4 * 2 * 768 * 3072
+    assert L.cmoe_backward_workspace_bytes(h, -1) == 0 and L.cmoe_backward_workspace_bytes(None, 8) == 0
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, None, fake, need, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_backward(h, C.byref(w2), None, fake, 8, fake, fake, C.byref(g), fake, need, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, -1, fake, fake, C.byref(g), fake, need, None) == B.ERR_INVALID_ARG
+    g_bad = B.Grads(*([fake] * 9))
+    g_bad.dw1_base = None
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, C.byref(g_bad), fake, need, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, C.byref(g), fake, 16, None) == B.ERR_WORKSPACE
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, C.byref(g), None, need, None) == B.ERR_WORKSPACE
+    L.cmoe_destroy(h)
+    # more than 64 experts: no workspace size, call refused
+    rc, h = _create(d=64, d_ff=64, G=20, K=8, r=4, top_k=2, q_group=8)
+    assert rc == B.OK
+    assert L.cmoe_backward_workspace_bytes(h, 8) == 0
+    assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, C.byref(g), fake, 1 << 40, None) == B.ERR_UNSUPPORTED
+    L.cmoe_destroy(h)
