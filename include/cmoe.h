@@ -249,7 +249,7 @@ int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W
  * Experts that received no token get zero gradients and their stored weights are not read.
  * The shared-base products are computed once per token, the rank-r products once per
  * (token, expert) pair (Sec. 3.2).  Matrix operands are FP16, accumulation, the hidden
- * pre-activations and the gate path are FP32.  Supported: G*K <= 64.  T = 0 writes zero
+ * pre-activations and the gate path are FP32.  T = 0 writes zero
  * weight gradients.  Deterministic (fixed summation order). */
 typedef struct cmoe_grads {
   float *dx, *d_logits, *d_router_expert, *dw1_base, *dw2_base, *du1, *dv1, *du2, *dv2;

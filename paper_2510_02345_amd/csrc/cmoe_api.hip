@@ -427,7 +427,7 @@ extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, co
 }
 
 extern "C" size_t cmoe_backward_workspace_bytes(const cmoe_handle* h, int32_t T_max) {
-  if (!handle_ok(h) || T_max < 0 || h->dm.G * h->dm.K > 64) return 0;
+  if (!handle_ok(h) || T_max < 0) return 0;
   if ((size_t)T_max * h->dm.k > ((size_t)1 << 30)) return 0;
   return cmoe_backward_layout(h->dm, T_max).total;
 }
@@ -437,7 +437,7 @@ extern "C" int cmoe_backward(cmoe_handle* h, const cmoe_weights* w, const cmoe_f
                              size_t workspace_bytes, void* stream) {
   if (!handle_ok(h) || T < 0 || grads == nullptr) return CMOE_ERR_INVALID_ARG;
   if (!weights_route_ok(w) || !weights_ffn_ok(w) || !weights_combine_ok(w)) return CMOE_ERR_INVALID_ARG;
-  if (h->dm.G * h->dm.K > 64 || (size_t)T * h->dm.k > ((size_t)1 << 30)) return CMOE_ERR_UNSUPPORTED;
+  if ((size_t)T * h->dm.k > ((size_t)1 << 30)) return CMOE_ERR_UNSUPPORTED;
   const cmoe_grads& g = *grads;
   if (!ptr_ok(g.d_router_expert) || !ptr_ok(g.dw1_base) || !ptr_ok(g.dw2_base) || !ptr_ok(g.du1) || !ptr_ok(g.dv1) ||
       !ptr_ok(g.du2) || !ptr_ok(g.dv2) || (g.d_logits != nullptr && !aligned16(g.d_logits)))

@@ -54,6 +54,37 @@ __global__ __launch_bounds__(256) void bw_cluster_kernel(const int* __restrict__
   if (t < T) cid[t] = expert_idx[(size_t)t * k] / K;
 }
 
+// More than 64 experts: the pairs are sorted by expert in two stable counting sorts, by the
+// expert's index inside its cluster and then by cluster.
+// mode 0: key[i] = expert_idx[i] % K;  mode 1: key[i] = expert_idx[perm_a[i]] / K.
+__global__ __launch_bounds__(256) void bw_key_kernel(const int* __restrict__ expert_idx,
+                                                     const int* __restrict__ perm_a, int M, int K, int E, int mode,
+                                                     int* __restrict__ key) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M) return;
+  const int e = min(max(expert_idx[mode ? perm_a[i] : i], 0), E - 1);
+  key[i] = mode ? e / K : e % K;
+}
+
+// permm[i] = perm_a[perm_b[i]], invm[permm[i]] = i, and the expert offsets from the sorted
+// keys: offe[e] = first sorted row whose expert is >= e, offe[E] = M.
+__global__ __launch_bounds__(256) void bw_compose_kernel(const int* __restrict__ expert_idx,
+                                                         const int* __restrict__ perm_a,
+                                                         const int* __restrict__ perm_b, int M, int E,
+                                                         int* __restrict__ permm, int* __restrict__ invm,
+                                                         int* __restrict__ offe) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M) return;
+  const int m = perm_a[perm_b[i]];
+  permm[i] = m;
+  invm[m] = i;
+  const int e = min(max(expert_idx[m], 0), E - 1);
+  const int prev = i > 0 ? min(max(expert_idx[perm_a[perm_b[i - 1]]], 0), E - 1) : -1;
+  for (int x = prev + 1; x <= e; ++x) offe[x] = i;
+  if (i == M - 1)
+    for (int x = e + 1; x <= E; ++x) offe[x] = M;
+}
+
 // Column ranges of the group-padded transposed copies and, for every padded column qc, the
 // sorted row it holds (-1: padding), the source row perm[row] / div and its gate.
 // krange[2g] = first column of group g, krange[2g+1] = its rows rounded up to 32.
@@ -88,6 +119,11 @@ __global__ __launch_bounds__(256) void bw_map_kernel(const int* __restrict__ off
   const int m = row >= 0 ? perm[row] : 0;
   ssrc[qc] = row >= 0 ? m / div : -1;
   if (sgate != nullptr) sgate[qc] = row >= 0 ? gate[m] : 0.f;
+}
+
+__global__ __launch_bounds__(256) void bw_zero_kernel(int* __restrict__ p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
 // offx[g] = g * I (g <= n_groups) and gidx[p] = p % I for the n_groups * I rows of a
@@ -451,6 +487,8 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.permm = take(sizeof(int) * M);
   L.invm = take(sizeof(int) * M);
   L.offe = take(sizeof(int) * (E + 1));
+  L.sort_tmp = take(E > 64 ? sizeof(int) * 4 * M : 0);   // key, perm_a, perm_b, scratch inverse
+  L.off_tmp = take(sizeof(int) * 65);
   L.krange_c = take(sizeof(int) * 2 * G);
   L.srow_c = take(sizeof(int) * Tp);
   L.ssrc_c = take(sizeof(int) * Tp);
@@ -507,12 +545,37 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     if (err != hipSuccess) return err;    \
   } while (0)
 #define BW_GEMM(...) BW_CHECK(launch_gemm_plain(__VA_ARGS__, st))
+  // a product over expert groups, at most 64 groups per launch (the kernel finds the group of
+  // a tile by a linear walk over the offsets); rows are addressed absolutely, so a launch
+  // over a slice of the offsets needs no other change
+  auto rank_gemm = [&](const half_t* P, int L_, const half_t* X, int ldx, const int* gather, int x_div,
+                       half_t* outp) -> hipError_t {
+    for (int e0 = 0; e0 < E; e0 += 64) {
+      hipError_t rc = launch_gemm_plain(P + (size_t)e0 * RP * L_, (long)RP * L_, L_, RP, X, ldx, gather, x_div, L_,
+                                        offe + e0, E - e0 < 64 ? E - e0 : 64, M, nullptr, nullptr, outp, RP, false, st);
+      if (rc != hipSuccess) return rc;
+    }
+    return hipSuccess;
+  };
 
   // tokens sorted by cluster, pairs sorted by expert (both stable)
   if (T > 0)
     hipLaunchKernelGGL(bw_cluster_kernel, dim3((T + 255) / 256), dim3(256), 0, st, expert_idx, T, k, dm.K, I(L.cid));
   BW_CHECK(launch_permute_bins(G, I(L.cid), T, permc, I(L.invc), offc, I(L.blk_counts), st));
-  BW_CHECK(launch_permute_bins(E, expert_idx, M, permm, invm, offe, I(L.blk_counts), st));
+  if (E <= 64) {
+    BW_CHECK(launch_permute_bins(E, expert_idx, M, permm, invm, offe, I(L.blk_counts), st));
+  } else if (M > 0) {
+    int *key = I(L.sort_tmp), *perm_a = key + M, *perm_b = key + 2 * (size_t)M, *scratch = key + 3 * (size_t)M;
+    const dim3 gm((M + 255) / 256), blk(256);
+    hipLaunchKernelGGL(bw_key_kernel, gm, blk, 0, st, expert_idx, (const int*)nullptr, M, dm.K, E, 0, key);
+    BW_CHECK(launch_permute_bins(dm.K, key, M, perm_a, scratch, I(L.off_tmp), I(L.blk_counts), st));
+    hipLaunchKernelGGL(bw_key_kernel, gm, blk, 0, st, expert_idx, (const int*)perm_a, M, dm.K, E, 1, key);
+    BW_CHECK(launch_permute_bins(G, key, M, perm_b, scratch, I(L.off_tmp), I(L.blk_counts), st));
+    hipLaunchKernelGGL(bw_compose_kernel, gm, blk, 0, st, expert_idx, (const int*)perm_a, (const int*)perm_b, M, E,
+                       permm, invm, offe);
+  } else {
+    hipLaunchKernelGGL(bw_zero_kernel, dim3((E + 256) / 256), dim3(256), 0, st, offe, E + 1);
+  }
   hipLaunchKernelGGL(bw_map_kernel, dim3((Tpad + 255) / 256), dim3(256), 0, st, offc, permc, (const float*)nullptr, G,
                      1, Tpad, krc, I(L.srow_c), I(L.ssrc_c), (float*)nullptr);
   hipLaunchKernelGGL(bw_rows_kernel, dim3((unsigned)(((size_t)G * f + 256) / 256)), dim3(256), 0, st, G, f,
@@ -540,11 +603,11 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
 
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
     BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.hb), f, false);
-    BW_GEMM(H(L.v1p), (long)RP * d, d, RP, x, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.t1), RP, false);
+    BW_CHECK(rank_gemm(H(L.v1p), d, x, d, permm, k, H(L.t1)));
     rankexpand(r, H(L.t1), H(L.u1p), f, offe, nullptr, E, H(L.rh), st);
     // da = B2^T dy + V2^T (U2^T dy)
     BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.dab), f, false);
-    BW_GEMM(H(L.u2p), (long)RP * d, d, RP, dy, d, permm, k, d, offe, E, M, nullptr, nullptr, H(L.uy), RP, false);
+    BW_CHECK(rank_gemm(H(L.u2p), d, dy, d, permm, k, H(L.uy)));
     rankexpand(r, H(L.uy), H(L.v2p), f, offe, nullptr, E, H(L.rda), st);
     if (k <= 2)
       hipLaunchKernelGGL(bw_act_kernel<2>, dim3(T), dim3(256), 0, st, H(L.hb), H(L.dab), H(L.rh), H(L.rda), invm, gate, k,
@@ -554,12 +617,12 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
     BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);
-    BW_GEMM(H(L.u1p), (long)RP * f, f, RP, H(L.dh16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.qq), RP, false);
+    BW_CHECK(rank_gemm(H(L.u1p), f, H(L.dh16), f, nullptr, 1, H(L.qq)));
     rankexpand(r, H(L.qq), H(L.v1p), d, offe, permm, E, F(L.dxr), st);
     hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, F(L.dxb), F(L.dxr), dl, expert_idx,
                        (const half_t*)w.router_expert, k, d, out.dx);
     // s = V2 a per pair
-    BW_GEMM(H(L.v2p), (long)RP * f, f, RP, H(L.a16), f, nullptr, 1, f, offe, E, M, nullptr, nullptr, H(L.ss), RP, false);
+    BW_CHECK(rank_gemm(H(L.v2p), f, H(L.a16), f, nullptr, 1, H(L.ss)));
     // transposed, cluster-padded copies for the base gradients (contraction over tokens)
     const int* ssrc_c = I(L.ssrc_c);
     transpose(x, d, d, ssrc_c, nullptr, Tpad, H(L.xct), st);

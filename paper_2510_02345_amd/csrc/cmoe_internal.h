@@ -140,7 +140,7 @@ hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* 
 // the transposed copies whose groups (clusters) are padded to 32.
 struct cmoe_bw_layout {
   int M, Tpad;
-  size_t blk_counts, cid, permc, invc, offc, permm, invm, offe, krange_c;
+  size_t blk_counts, cid, permc, invc, offc, permm, invm, offe, sort_tmp, off_tmp, krange_c;
   size_t srow_c, ssrc_c;
   size_t offx_f, gidx_f, offx_d, gidx_d, dl;
   size_t v1p, u2p, u1p, v2p;                  // f16 rank panels [E][32][L]
