@@ -256,13 +256,14 @@ __global__ __launch_bounds__(256) void bw_drouter_kernel(const half_t* __restric
 }
 
 // out[z][i][qc] = scale[qc] * src[z][idx[qc]][i] (zero where idx[qc] < 0; idx == NULL: row
-// qc), i < I (a multiple of 16), qc < Npad (a multiple of 64).  Matrices z whose group in
+// qc), i < I (a multiple of 16), qc < Npad (a multiple of 64); with blocked != 0 the same
+// values in the layout [Npad / 32][I][32].  Matrices z whose group in
 // skip_off is empty are skipped.  Block (Npad / 64, ceil(I / 64), Z): 64 x 64 tile through LDS.
 __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restrict__ src, int ld, int I,
                                                            const int* __restrict__ idx,
                                                            const float* __restrict__ scale, int Npad,
                                                            const int* __restrict__ skip_off, size_t zstride,
-                                                           half_t* __restrict__ out) {
+                                                           int blocked, half_t* __restrict__ out) {
   __shared__ half_t tile[64][72];
   const int z = blockIdx.z;
   if (skip_off != nullptr && skip_off[z + 1] == skip_off[z]) return;
@@ -297,7 +298,10 @@ __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restr
     a[u] = tile[part * 16 + u][il];
     b[u] = tile[part * 16 + 8 + u][il];
   }
-  half_t* dst = out + (size_t)(i0 + il) * Npad + q0 + part * 16;
+  // blocked: [Npad / 32][I][32], the operand layout whose contraction blocks are contiguous
+  const int qq = q0 + part * 16;
+  half_t* dst = blocked ? out + ((size_t)(qq >> 5) * I + i0 + il) * 32 + (qq & 31)
+                        : out + (size_t)(i0 + il) * Npad + qq;
   *(half8*)dst = a;
   *(half8*)(dst + 8) = b;
 }
@@ -460,7 +464,7 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 void transpose(const half_t* src, int ld, int I, const int* idx, const float* scale, int Npad, half_t* out,
                hipStream_t st) {
   hipLaunchKernelGGL(bw_transpose_kernel, dim3(Npad / 64, (I + 63) / 64, 1), dim3(256), 0, st, src, ld, I, idx, scale,
-                     Npad, (const int*)nullptr, (size_t)0, out);
+                     Npad, (const int*)nullptr, (size_t)0, 1, out);
 }
 
 }  // namespace
@@ -596,9 +600,9 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                        (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p));
     // w1bt [G][d][d_ff] = B1^T, w2bt [G][d_ff][d] = B2^T
     hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, d, (const int*)nullptr,
-                       (const float*)nullptr, f, offc, (size_t)mat, H(L.w1bt));
+                       (const float*)nullptr, f, offc, (size_t)mat, 0, H(L.w1bt));
     hipLaunchKernelGGL(bw_transpose_kernel, dim3(d / 64, f / 64, G), dim3(256), 0, st, w2b, f, f, (const int*)nullptr,
-                       (const float*)nullptr, d, offc, (size_t)mat, H(L.w2bt));
+                       (const float*)nullptr, d, offc, (size_t)mat, 0, H(L.w2bt));
     BW_CHECK(hipGetLastError());
 
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
@@ -623,7 +627,8 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                        (const half_t*)w.router_expert, k, d, out.dx);
     // s = V2 a per pair
     BW_CHECK(rank_gemm(H(L.v2p), f, H(L.a16), f, nullptr, 1, H(L.ss)));
-    // transposed, cluster-padded copies for the base gradients (contraction over tokens)
+    // transposed, cluster-padded copies for the base gradients (contraction over tokens),
+    // stored in 32-column blocks
     const int* ssrc_c = I(L.ssrc_c);
     transpose(x, d, d, ssrc_c, nullptr, Tpad, H(L.xct), st);
     transpose(dy, d, d, ssrc_c, nullptr, Tpad, H(L.dyct), st);
@@ -634,10 +639,11 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
   hipLaunchKernelGGL(bw_drouter_kernel, dim3(E, (d / 4 + 255) / 256), dim3(256), 0, st, x, permm, offe, dl, k, d,
                      out.d_router_expert);
   // base gradients: contraction over the tokens of a cluster
-  BW_GEMM(H(L.xct), 0, Tpad, d, H(L.dhst), Tpad, I(L.gidx_f), 1, Tpad, I(L.offx_f), G, G * f, krc, nullptr,
-          out.dw1_base, d, true);
-  BW_GEMM(H(L.agt), 0, Tpad, f, H(L.dyct), Tpad, I(L.gidx_d), 1, Tpad, I(L.offx_d), G, G * d, krc, nullptr,
-          out.dw2_base, f, true);
+  // (operands in the blocked layout [Tpad / 32][rows][32]: row stride 32, block stride rows * 32)
+  BW_CHECK(launch_gemm_plain(H(L.xct), 0, 32, d, H(L.dhst), 32, I(L.gidx_f), 1, Tpad, I(L.offx_f), G, G * f, krc,
+                             nullptr, out.dw1_base, d, true, st, (long)d * 32, (long)f * 32));
+  BW_CHECK(launch_gemm_plain(H(L.agt), 0, 32, f, H(L.dyct), 32, I(L.gidx_d), 1, Tpad, I(L.offx_d), G, G * d, krc,
+                             nullptr, out.dw2_base, f, true, st, (long)f * 32, (long)d * 32));
   // factor gradients: contraction over the pairs of an expert, streamed once
   float* part = F(L.rgpart);
   rankgrad(r, H(L.t1), H(L.dh16), f, offe, permm, k, 0, nullptr, E, part, out.du1, st);

@@ -60,6 +60,10 @@ struct GemmArgs {
   // optional per-group contraction range: group c contracts columns krange[2c] ..
   // krange[2c] + krange[2c+1] (both multiples of 32) of W and X instead of 0 .. Kc
   const int* krange;
+  // elements between consecutive 32-element contraction blocks of a row of W / X; 0 = 32
+  // (plain row-major rows).  An operand stored as [K / 32][rows][32] has ld = 32 and a
+  // step of rows * 32: the 16 rows of one load instruction are then 1 KiB of contiguous memory.
+  long kstep_w, kstep_x;
 };
 
 struct TileCtx {
@@ -138,6 +142,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   const int n0 = n_tile * TL::BN;
   const half_t* Wc = g.W + (size_t)c * g.w_cstride;
   const int k_lo = g.krange ? g.krange[2 * c] : 0;
+  const long kstep_w = g.kstep_w ? g.kstep_w : TL::BK, kstep_x = g.kstep_x ? g.kstep_x : TL::BK;
   const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 
   // global source of each of this wavefront's load instructions (16 tile rows x 64 B);
@@ -156,12 +161,13 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
       const int p = min(m0 + row - TL::BN, m_end - 1);
       base = g.X + (size_t)(g.gather ? (g.x_div > 1 ? g.gather[p] / g.x_div : g.gather[p]) : p) * g.ldx;
     }
-    gsrc[i] = base + chunk * 8 + k_lo;
+    const long step = row < TL::BN ? kstep_w : kstep_x;
+    gsrc[i] = base + chunk * 8 + (size_t)(k_lo / TL::BK) * step;
   }
   auto issue = [&](int kt, int stage) {
 #pragma unroll
     for (int i = 0; i < TL::PER_WAVE; ++i)
-      dma16(gsrc[i] + (size_t)kt * TL::BK,
+      dma16(gsrc[i] + (size_t)kt * (((wave * TL::PER_WAVE + i) * 16 < TL::BN) ? kstep_w : kstep_x),
             smem_base + stage * TL::STAGE_BYTES + (wave * TL::PER_WAVE + i) * 1024);
   };
 
@@ -1107,12 +1113,14 @@ hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, cons
 hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, const half_t* X, int ldx,
                              const int* gather, int x_div, int Kc, const int* offsets, int n_groups, int rows,
                              const int* krange, const int* rowmap, void* out, int ldo, bool out_f32,
-                             hipStream_t st) {
+                             hipStream_t st, long kstep_w, long kstep_x) {
   using TL = TileBig;
   GemmArgs g{W, w_gstride, ldw, N, X, ldx, gather, Kc, offsets, n_groups, (N + TL::BN - 1) / TL::BN, 0, 0, nullptr,
              0, 0};
   g.x_div = x_div;
   g.krange = krange;
+  g.kstep_w = kstep_w;
+  g.kstep_x = kstep_x;
   if (N <= 64 && !out_f32) {
     // a few output columns per row (products into rank space): one 64-row weight tile, the
     // launch is bound by the stream of X rows

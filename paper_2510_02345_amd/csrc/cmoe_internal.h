@@ -159,4 +159,5 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                            const cmoe_bw_layout& L, hipStream_t st);
 hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, const half_t* X, int ldx,
                              const int* gather, int x_div, int Kc, const int* offsets, int n_groups, int rows,
-                             const int* krange, const int* rowmap, void* out, int ldo, bool out_f32, hipStream_t st);
+                             const int* krange, const int* rowmap, void* out, int ldo, bool out_f32, hipStream_t st,
+                             long kstep_w = 0, long kstep_x = 0);
