@@ -79,6 +79,7 @@ typedef struct {
   const cmoe_f16 *w2_base;        /* [G][d][d_ff]                                          */
   const uint8_t *v1_q, *u1_q, *v2_q, *u2_q; /* [G*K][r][L/2]                                */
   const cmoe_f16 *v1_s, *u1_s, *v2_s, *u2_s; /* [G*K][r][L/q_group]                         */
+  const void *packed; /* NULL, or the buffer cmoe_pack_weights filled from THESE bases (below)  */
 } cmoe_weights;
 
 typedef struct cmoe_handle cmoe_handle;
@@ -89,6 +90,21 @@ typedef struct cmoe_handle cmoe_handle;
  * d_ff; activation = 0.  Anything else: CMOE_ERR_UNSUPPORTED. */
 int cmoe_create(const cmoe_config *cfg, cmoe_handle **out);
 int cmoe_destroy(cmoe_handle *h);
+
+/* One-time re-tiling of the two bases into the layout the matrix-core kernels load
+ * fastest (weights are static across forward calls, Sec. 3.4; the canonical layouts above
+ * stay the interface).  packed holds, per cluster, W1_base as [d/32][d_ff][32] and W2_base as
+ * [d_ff/32][d][32]: the 32 contraction elements of consecutive rows are contiguous, so one
+ * direct-to-LDS load instruction fetches 1 KiB of contiguous memory instead of 16 pieces a
+ * row apart.  cmoe_packed_bytes = 4 * G * d * d_ff (0 for a bad handle); packed is a
+ * caller-owned device buffer, 256-byte aligned.  Set cmoe_weights.packed to it and the
+ * calls that take more than 256 tokens read the bases from it (cmoe_ffn_forward,
+ * cmoe_forward, cmoe_forward_multi, cmoe_backward); with fewer tokens, or packed == NULL,
+ * the canonical arrays are read.  The canonical arrays must stay valid either way, and the
+ * caller packs again after changing a base.  Packing reads every cluster's bases. */
+size_t cmoe_packed_bytes(const cmoe_handle *h);
+int cmoe_pack_weights(cmoe_handle *h, const cmoe_weights *w, void *packed, size_t packed_bytes,
+                      void *stream);
 
 /* Bytes of device workspace that cmoe_permute / cmoe_ffn_forward / cmoe_combine /
  * cmoe_forward need for up to T_max tokens (one buffer serves all of them; contents

@@ -20,6 +20,7 @@ EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", 
            "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi",
            "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes", "cmoe_compress",
            "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_backward_workspace_bytes", "cmoe_backward",
+           "cmoe_packed_bytes", "cmoe_pack_weights",
            "cmoe_last_hip_error", "cmoe_status_string",
            "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
 
@@ -50,7 +51,8 @@ class Config(C.Structure):
 
 class Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("router_cluster", "router_expert", "cluster_bias", "w1_base", "w2_base",
-                                          "v1_q", "u1_q", "v2_q", "u2_q", "v1_s", "u1_s", "v2_s", "u2_s")]
+                                          "v1_q", "u1_q", "v2_q", "u2_q", "v1_s", "u1_s", "v2_s", "u2_s",
+                                          "packed")]
 
 
 def lib_path() -> str:
@@ -86,6 +88,9 @@ def lib():
     L.cmoe_compress.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_quantize_int4.argtypes = [vp, C.c_int64, i32, i32, vp, vp, vp]
     L.cmoe_reconstruction_error.argtypes = [C.POINTER(CompressConfig), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.cmoe_packed_bytes.argtypes = [vp]
+    L.cmoe_packed_bytes.restype = sz
+    L.cmoe_pack_weights.argtypes = [vp, C.POINTER(Weights), vp, sz, vp]
     L.cmoe_backward_workspace_bytes.argtypes = [vp, i32]
     L.cmoe_backward_workspace_bytes.restype = sz
     L.cmoe_backward.argtypes = [vp, C.POINTER(Weights), vp, vp, i32, vp, vp, C.POINTER(Grads), vp, sz, vp]
@@ -99,7 +104,7 @@ def lib():
     for name in EXPORTS:
         if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
                         "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi",
-                        "cmoe_backward_workspace_bytes"):
+                        "cmoe_backward_workspace_bytes", "cmoe_packed_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -183,7 +188,10 @@ class Layer:
     WEIGHT_NAMES = ("router_cluster", "router_expert", "cluster_bias", "w1_base", "w2_base",
                     "v1_q", "u1_q", "v2_q", "u2_q", "v1_s", "u1_s", "v2_s", "u2_s")
 
-    def __init__(self, d, d_ff, G, K, r, top_k, q_group, weights: Dict[str, object], T_max: int, device="cuda:0"):
+    def __init__(self, d, d_ff, G, K, r, top_k, q_group, weights: Dict[str, object], T_max: int, device="cuda:0",
+                 pack: bool = True):
+        """pack: make the one-time re-tiled copy of the bases (cmoe_pack_weights) that the calls with
+        more than 256 tokens read; pack=False keeps the canonical arrays only."""
         import torch
         self.torch = torch
         self.cfg = Config(d, d_ff, G, K, r, top_k, q_group, 0)
@@ -206,6 +214,19 @@ class Layer:
         self.ws_bytes = lib().cmoe_workspace_bytes(self._h, T_max)
         self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
         assert self.ws.data_ptr() % 256 == 0
+        self.packed = None
+        if pack:
+            self.pack()
+
+    def pack(self):
+        """(Re)build the packed copy of the bases from the layer's current w1_base / w2_base."""
+        t = self.torch
+        if self.packed is None:
+            self.packed = t.empty(max(lib().cmoe_packed_bytes(self._h), 256), dtype=t.uint8, device=self.device)
+        self.w.packed = None
+        self._check(lib().cmoe_pack_weights(self._h, C.byref(self.w), _ptr(self.packed), self.packed.numel(),
+                                            self._stream()), "cmoe_pack_weights")
+        self.w.packed = _ptr(self.packed)
 
     def close(self):
         if self._h:

@@ -184,7 +184,7 @@ static bool weights_route_ok(const cmoe_weights* w) {
          (w->cluster_bias == nullptr || (reinterpret_cast<uintptr_t>(w->cluster_bias) & 3u) == 0);
 }
 static bool weights_ffn_ok(const cmoe_weights* w) {
-  return w != nullptr && ptr_ok(w->w1_base) && ptr_ok(w->w2_base) && ptr_ok(w->v1_q) && ptr_ok(w->u1_q) &&
+  return w != nullptr && aligned16(w->packed) && ptr_ok(w->w1_base) && ptr_ok(w->w2_base) && ptr_ok(w->v1_q) && ptr_ok(w->u1_q) &&
          ptr_ok(w->v2_q) && ptr_ok(w->v1_s) && ptr_ok(w->u1_s) && ptr_ok(w->v2_s);
 }
 static bool weights_combine_ok(const cmoe_weights* w) { return w != nullptr && ptr_ok(w->u2_q) && ptr_ok(w->u2_s); }
@@ -423,6 +423,25 @@ extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, co
   CMOE_LAUNCH(TS_STATS, launch_route_stats(h->dm, (const half_t*)x, T, perm, offsets, expert_idx, beta, lam, mu,
                                            cluster_act, cluster_idle, expert_load, cluster_load, i_load,
                                            (float*)(ws + L.stats_part), (int*)(ws + L.stats_cnt), st));
+  return CMOE_OK;
+}
+
+extern "C" size_t cmoe_packed_bytes(const cmoe_handle* h) {
+  if (!handle_ok(h)) return 0;
+  return (size_t)4 * h->dm.G * h->dm.d * h->dm.d_ff;
+}
+
+extern "C" int cmoe_pack_weights(cmoe_handle* h, const cmoe_weights* w, void* packed, size_t packed_bytes,
+                                 void* stream) {
+  if (!handle_ok(h) || w == nullptr || !ptr_ok(w->w1_base) || !ptr_ok(w->w2_base)) return CMOE_ERR_INVALID_ARG;
+  if (packed == nullptr || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return CMOE_ERR_INVALID_ARG;
+  if (packed_bytes < cmoe_packed_bytes(h)) return CMOE_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_pack_bases(h->dm, *w, (half_t*)packed, st);
+  if (e != hipSuccess) {
+    h->last_hip_error = (int)e;
+    return CMOE_ERR_HIP;
+  }
   return CMOE_OK;
 }
 

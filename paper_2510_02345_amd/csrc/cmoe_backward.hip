@@ -598,19 +598,24 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                        (const half_t*)w.u2_s, d, q, r, offe, H(L.u2p));
     hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v2_q,
                        (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p));
-    // w1bt [G][d][d_ff] = B1^T, w2bt [G][d_ff][d] = B2^T
+    // w1bt = B1^T ([d][d_ff] per cluster), w2bt = B2^T ([d_ff][d]), both in 32-column blocks
     hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, d, (const int*)nullptr,
-                       (const float*)nullptr, f, offc, (size_t)mat, 0, H(L.w1bt));
+                       (const float*)nullptr, f, offc, (size_t)mat, 1, H(L.w1bt));
     hipLaunchKernelGGL(bw_transpose_kernel, dim3(d / 64, f / 64, G), dim3(256), 0, st, w2b, f, f, (const int*)nullptr,
-                       (const float*)nullptr, d, offc, (size_t)mat, 0, H(L.w2bt));
+                       (const float*)nullptr, d, offc, (size_t)mat, 1, H(L.w2bt));
     BW_CHECK(hipGetLastError());
 
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
-    BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.hb), f, false);
+    if (w.packed != nullptr)   // packed W1: [d/32][d_ff][32] per cluster
+      BW_CHECK(launch_gemm_plain((const half_t*)w.packed, mat, 32, f, x, d, permc, 1, d, offc, G, T, nullptr, permc,
+                                 H(L.hb), f, false, st, (long)f * 32, 0));
+    else
+      BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.hb), f, false);
     BW_CHECK(rank_gemm(H(L.v1p), d, x, d, permm, k, H(L.t1)));
     rankexpand(r, H(L.t1), H(L.u1p), f, offe, nullptr, E, H(L.rh), st);
     // da = B2^T dy + V2^T (U2^T dy)
-    BW_GEMM(H(L.w2bt), mat, d, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.dab), f, false);
+    BW_CHECK(launch_gemm_plain(H(L.w2bt), mat, 32, f, dy, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.dab), f, false,
+                               st, (long)f * 32, 0));
     BW_CHECK(rank_gemm(H(L.u2p), d, dy, d, permm, k, H(L.uy)));
     rankexpand(r, H(L.uy), H(L.v2p), f, offe, nullptr, E, H(L.rda), st);
     if (k <= 2)
@@ -620,7 +625,8 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
       hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, H(L.hb), H(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
-    BW_GEMM(H(L.w1bt), mat, f, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d, true);
+    BW_CHECK(launch_gemm_plain(H(L.w1bt), mat, 32, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d,
+                               true, st, (long)d * 32, 0));
     BW_CHECK(rank_gemm(H(L.u1p), f, H(L.dh16), f, nullptr, 1, H(L.qq)));
     rankexpand(r, H(L.qq), H(L.v1p), d, offe, permm, E, F(L.dxr), st);
     hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, F(L.dxb), F(L.dxr), dl, expert_idx,

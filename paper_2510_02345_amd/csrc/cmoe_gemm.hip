@@ -1010,6 +1010,16 @@ hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int x_div, int T, con
   return launch_gemm<TL>(g, T, epi, st);
 }
 
+// With a packed copy of the bases (per cluster W1 as [d/32][d_ff][32], then all of W2 as
+// [d_ff/32][d][32]) the weight operand is read from it: row stride 32, block stride rows * 32.
+static void use_packed_base(GemmArgs& g, const cmoe_dims& dm, const cmoe_weights& w, bool second) {
+  if (w.packed == nullptr) return;
+  const size_t mat = (size_t)dm.d * dm.d_ff;
+  g.W = (const half_t*)w.packed + (second ? mat * dm.G : 0);
+  g.ldw = 32;
+  g.kstep_w = (long)(second ? dm.d : dm.d_ff) * 32;
+}
+
 hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T,
                         const int* perm,
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
@@ -1018,6 +1028,7 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   GemmArgs g{(const half_t*)w.w1_base, (long)dm.d_ff * dm.d, dm.d, dm.d_ff, x, dm.d, perm, dm.d, offsets, dm.G,
              (dm.d_ff + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
   g.x_div = x_div;
+  use_packed_base(g, dm, w, false);
   switch (dm.r) {
     case 4: return launch_gemm1_r<4>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
     case 8: return launch_gemm1_r<8>(dm, g, T, perm, expert_idx, gate, u1t, v2p, t1, a, spart, st);
@@ -1044,6 +1055,7 @@ hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t
   using TL = TileBig;
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  use_packed_base(g, dm, w, true);
   EpiStore epi{y_base_sorted, rowmap, dm.d, dm.d};
   return launch_gemm<TL, EpiStore, TileTail>(g, T, epi, st);
 }
@@ -1102,6 +1114,7 @@ hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, cons
   using TL = TileBig;
   GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  use_packed_base(g, dm, w, true);
   EpiDownCombine epi{u2t, s_down, rperm, expert_idx, gate, y, dm.k, dm.K, dm.r, dm.KRp, dm.d};
   return launch_gemm<TL, EpiDownCombine, TileTail>(g, T, epi, st);
 }
@@ -1135,4 +1148,24 @@ hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, co
   }
   EpiStore epi{(half_t*)out, rowmap, ldo, N};
   return launch_gemm<TL, EpiStore, TileTail>(g, rows, epi, st);
+}
+
+// packed[c][(k / 32) * N + n][k % 32] = base[c][n][k]: one thread moves 8 elements.
+__global__ __launch_bounds__(256) void pack_base_kernel(const half_t* __restrict__ base, int N, int K,
+                                                        half_t* __restrict__ packed) {
+  const size_t mat = (size_t)N * K;
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;   // element index inside the cluster's matrix
+  if (i >= mat) return;
+  const size_t c = blockIdx.y;
+  const int n = (int)(i / K), k = (int)(i % K);
+  *(half8*)(packed + c * mat + ((size_t)(k >> 5) * N + n) * 32 + (k & 31)) = *(const half8*)(base + c * mat + i);
+}
+
+hipError_t launch_pack_bases(const cmoe_dims& dm, const cmoe_weights& w, half_t* packed, hipStream_t st) {
+  const size_t mat = (size_t)dm.d * dm.d_ff;
+  const dim3 grid((unsigned)((mat / 8 + 255) / 256), dm.G);
+  hipLaunchKernelGGL(pack_base_kernel, grid, dim3(256), 0, st, (const half_t*)w.w1_base, dm.d_ff, dm.d, packed);
+  hipLaunchKernelGGL(pack_base_kernel, grid, dim3(256), 0, st, (const half_t*)w.w2_base, dm.d, dm.d_ff,
+                     packed + mat * dm.G);
+  return hipGetLastError();
 }

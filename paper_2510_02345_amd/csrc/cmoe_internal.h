@@ -161,3 +161,4 @@ hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, co
                              const int* gather, int x_div, int Kc, const int* offsets, int n_groups, int rows,
                              const int* krange, const int* rowmap, void* out, int ldo, bool out_f32, hipStream_t st,
                              long kstep_w = 0, long kstep_x = 0);
+hipError_t launch_pack_bases(const cmoe_dims& dm, const cmoe_weights& w, half_t* packed, hipStream_t st);

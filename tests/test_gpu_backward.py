@@ -21,7 +21,7 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def _run(cfg, w=None, dy_scale=1.0):
+def _run(cfg, w=None, dy_scale=1.0, pack=True):
     import torch
     import paper_2510_02345_amd as cm
     print(f"case {cfg}", flush=True)
@@ -30,7 +30,7 @@ def _run(cfg, w=None, dy_scale=1.0):
     dy = (dy_scale * rng.standard_normal((cfg.T, cfg.d))).astype(np.float16)
     cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
     ref = orc.backward_naive(w, w["x"], dy, eidx, gate, cfg.K, cfg.q)
-    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T)
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T, pack=pack)
     out = layer.backward(_dev(w["x"]), _dev(dy), _dev(eidx.astype(np.int32)), _dev(gate.astype(np.float32)))
     torch.cuda.synchronize()
     res = {}
@@ -71,6 +71,10 @@ def test_backward_small(cfg):
 
 def test_backward_config1():
     _run(ci.config(1))
+
+
+def test_backward_canonical_bases_without_the_packed_copy():
+    _run(SMALL[0], pack=False)
 
 
 def test_backward_live_residual_and_gate_path():

@@ -16,9 +16,10 @@ MAX_OVER_RMS = 1e-2
 MEAN_REL = 2e-3
 
 
-def _layer(cfg, w, T_max=None):
+def _layer(cfg, w, T_max=None, pack=True):
     import paper_2510_02345_amd as cm
-    return cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, T_max if T_max is not None else cfg.T)
+    return cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, T_max if T_max is not None else cfg.T,
+                    pack=pack)
 
 
 def _dev(a):
@@ -40,13 +41,13 @@ def _check_y(y, y_ref, what):
     return m
 
 
-def _stepwise(cfg, w=None):
+def _stepwise(cfg, w=None, pack=True):
     """Each entry point on its own against the oracle, then cmoe_forward."""
-    print(f"case {cfg}", flush=True)
+    print(f"case {cfg} pack={pack}", flush=True)
     w = w if w is not None else ci.generate(cfg)
     ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
     rw = orc.ffn_rewrite(w, w["x"], ref["perm"], ref["offsets"], ref["expert_idx"], ref["gate"], cfg.K, cfg.q)
-    layer = _layer(cfg, w)
+    layer = _layer(cfg, w, pack=pack)
     x = _dev(w["x"])
 
     cid, eidx, gate = layer.route(x)
@@ -128,6 +129,28 @@ SMALL = [
 @pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
 def test_small_shapes_every_entry_point(cfg):
     _stepwise(cfg)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[9], SMALL[12]], ids=lambda c: c.name)
+def test_canonical_bases_without_the_packed_copy(cfg):
+    # the layer reads the caller's row-major bases when no packed copy is given
+    _stepwise(cfg, pack=False)
+
+
+def test_packed_and_canonical_bases_give_identical_outputs():
+    # the packed copy only changes where the operand tiles are fetched from: same products,
+    # same order, bit-identical y
+    import torch
+    cfg = ci.config(1)
+    w = ci.generate(cfg)
+    x = _dev(w["x"])
+    ys = []
+    for pack in (True, False):
+        layer = _layer(cfg, w, pack=pack)
+        ys.append(layer.forward(x)["y"].clone())
+        _sync()
+        layer.close()
+    assert torch.equal(ys[0], ys[1])
 
 
 def test_empty_input_is_a_noop():
