@@ -758,8 +758,10 @@ struct EpiFusedUp {
                        : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s2 + 8 * h);
         };
         FU::block(acc[a][b], tk[b], k, n_chunks, n_pass, h, uf, vf, o, sacc);
-        // A[p][nb .. nb + 32) for the block's 32 tokens: through the wavefront's LDS patch
-        // so that four lanes write one token's 64 contiguous bytes
+        // A[p][nb .. nb + 32) for the block's 32 tokens, stored in 32-column blocks
+        // ([d_ff / 32][T][32], the operand layout of the down-projection): through the
+        // wavefront's LDS patch, so that four lanes write one token's 64 bytes and the block's
+        // 32 tokens 2 KiB of contiguous memory
         half_t* ot = (half_t*)((char*)t.smem + panel_bytes<TL>()) + (t.wm * TL::WAVES_N + t.wn) * (OT_BYTES / 2);
 #pragma unroll
         for (int qd = 0; qd < 4; ++qd) *(half4*)(ot + ml * OT_LD + 8 * qd + 4 * h) = to_half4(o, qd);
@@ -769,7 +771,7 @@ struct EpiFusedUp {
           const int tr = (t.lane >> 2) + 16 * i, cq = t.lane & 3;
           const half8 v8 = *(const half8*)(ot + tr * OT_LD + cq * 8);
           const int p = t.m0 + t.wm * TL::WM + b * 32 + tr;
-          if (p < t.m_end) *(half8*)(A + (size_t)p * d_ff + nb + cq * 8) = v8;
+          if (p < t.m_end) *(half8*)(A + ((size_t)(nb >> 5) * T + p) * 32 + cq * 8) = v8;
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
       }
@@ -1053,8 +1055,10 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
 hipError_t launch_gemm2(const cmoe_dims& dm, const cmoe_weights& w, const half_t* a, int T, const int* offsets,
                         const int* rowmap, half_t* y_base_sorted, hipStream_t st) {
   using TL = TileBig;
-  GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
+  // a is [d_ff / 32][T][32]
+  GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, 32, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  g.kstep_x = (long)T * 32;
   use_packed_base(g, dm, w, true);
   EpiStore epi{y_base_sorted, rowmap, dm.d, dm.d};
   return launch_gemm<TL, EpiStore, TileTail>(g, T, epi, st);
@@ -1112,8 +1116,9 @@ hipError_t launch_gemm2_combine(const cmoe_dims& dm, const cmoe_weights& w, cons
                                 const int* offsets, const int* rperm, const half_t* u2t, const float* s_down,
                                 const int* expert_idx, const float* gate, half_t* y, hipStream_t st) {
   using TL = TileBig;
-  GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, dm.d_ff, nullptr, dm.d_ff, offsets,
+  GemmArgs g{(const half_t*)w.w2_base, (long)dm.d * dm.d_ff, dm.d_ff, dm.d, a, 32, nullptr, dm.d_ff, offsets,
              dm.G, (dm.d + TL::BN - 1) / TL::BN, 0, 0, nullptr, 0, 0};
+  g.kstep_x = (long)T * 32;
   use_packed_base(g, dm, w, true);
   EpiDownCombine epi{u2t, s_down, rperm, expert_idx, gate, y, dm.k, dm.K, dm.r, dm.KRp, dm.d};
   return launch_gemm<TL, EpiDownCombine, TileTail>(g, T, epi, st);

@@ -61,7 +61,8 @@ struct cmoe_ws_layout {
   size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2, columns permuted inside 16-groups
   size_t u2t;         // f16 [G][d][KRp]       dequantised U2, transposed
   size_t t1ext;       // f16 [T][k][KRp]       V1 x, one-hot expanded over the cluster's experts
-  size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows
+  size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows; stored as
+                      //                       [d_ff/32][T][32] on the matrix-core path
   size_t ures;        // f32 [T][d]            residual-down term, sorted rows (weight-streaming path only)
   size_t stats_part;  // f32 [slots][K][d]     routing statistics: per-slot sums of x per expert
   size_t stats_cnt;   // i32 [slots][K]        and their row counts
