@@ -162,3 +162,26 @@ def test_backward_rejects_bad_arguments_without_touching_the_gpu():
     assert L.cmoe_backward_workspace_bytes(h, 8) > 0
     assert L.cmoe_backward(h, C.byref(w2), fake, fake, 8, fake, fake, C.byref(g), fake, 16, None) == B.ERR_WORKSPACE
     L.cmoe_destroy(h)
+
+
+def test_pack_weights_rejects_bad_arguments_without_touching_the_gpu():
+    rc, h = _create(d=768, d_ff=3072, G=2, K=4, r=8, top_k=2, q_group=32)
+    L = cm.lib()
+    fake = 0x1000
+    w2 = B.Weights(*([fake] * 13))
+    assert w2.packed is None                                    # canonical arrays only by default
+    need = L.cmoe_packed_bytes(h)
+    assert need == 4 * 2 * 768 * 3072 and L.cmoe_packed_bytes(None) == 0
+    assert L.cmoe_pack_weights(h, C.byref(w2), None, need, None) == B.ERR_INVALID_ARG
+    assert L.cmoe_pack_weights(h, C.byref(w2), 0x1010, need, None) == B.ERR_INVALID_ARG      # not 256-byte aligned
+    assert L.cmoe_pack_weights(h, C.byref(w2), fake, need - 1, None) == B.ERR_WORKSPACE
+    assert L.cmoe_pack_weights(h, None, fake, need, None) == B.ERR_INVALID_ARG
+    nobase = B.Weights(*([fake] * 13))
+    nobase.w2_base = None
+    assert L.cmoe_pack_weights(h, C.byref(nobase), fake, need, None) == B.ERR_INVALID_ARG
+    # a misaligned packed pointer is refused by the calls that would read it
+    bad = B.Weights(*([fake] * 13))
+    bad.packed = 0x1008
+    assert L.cmoe_ffn_forward(h, C.byref(bad), fake, 8, fake, fake, fake, fake, fake, fake, fake, 1 << 40,
+                              None) == B.ERR_INVALID_ARG
+    L.cmoe_destroy(h)
