@@ -61,6 +61,11 @@ SMALL = [
     ci.small_config("bw_sparse", T=19, d=64, d_ff=128, G=16, K=2, r=16, k=2, q=16, seed=144),
     ci.small_config("bw_k4", T=1500, d=128, d_ff=256, G=2, K=8, r=4, k=4, q=32, seed=145),
     ci.small_config("bw_one", T=1, d=64, d_ff=64, G=2, K=2, r=8, k=2, q=8, seed=146),
+    # the largest top-k (8 of 32 experts per cluster) and the largest rank panel (K * r = 512)
+    ci.small_config("bw_k8_of_32", T=400, d=64, d_ff=128, G=2, K=32, r=4, k=8, q=8, seed=153),
+    ci.small_config("bw_max_rank", T=300, d=64, d_ff=128, G=1, K=16, r=32, k=2, q=8, seed=154),
+    # the widest model dimension
+    ci.small_config("bw_max_d", T=300, d=8192, d_ff=128, G=4, K=2, r=4, k=2, q=128, seed=155),
 ]
 
 
