@@ -12,11 +12,13 @@
 //   dB1_c = sum_{t in c} (sum_j dh_m) x_t^T     dB2_c = sum_{t in c} dy_t (sum_j g_m a_m)^T
 //   dU1_e = sum_m dh_m (V1 x_t)^T   dV1_e = sum_m (U1^T dh_m) x_t^T
 //   dU2_e = sum_m g_m dy_t (V2 a_m)^T   dV2_e = sum_m g_m (U2^T dy_t) a_m^T
-// All products but the factor gradients run on the grouped matrix-core kernel of the
-// forward pass; the base gradients, which contract over the tokens of a cluster, do so after
-// a transposing copy that pads every cluster to a multiple of 32 columns.  Rank panels are
-// padded to 32 rows.  The factor gradients (r output rows per expert) stream the pair rows
-// of the expert once on the vector ALUs.
+// The five products with a base and the four products into rank space (V1 x, U2^T dy,
+// U1^T dh, V2 a; rank panels padded to 32 rows) run on the grouped matrix-core kernel of the
+// forward pass.  The two base gradients contract over the tokens of a cluster: they use
+// transposed copies that pad every cluster to a multiple of 32 columns and are stored in
+// 32-column blocks.  The ways back from rank space (U1 t, V2^T u, V1^T q) and the factor
+// gradients (r output rows per expert) are vector-ALU kernels that stream the pair rows of
+// an expert once.
 #include "cmoe_internal.h"
 
 namespace {
