@@ -310,8 +310,9 @@ __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restr
 
 // Rank-space rows back to full width: out[row(p)][n] = sum_{rho < R} t[p][rho] P[e][rho][n] for
 // the sorted pair rows p of expert e (P = a [E][32][L] panel), row(p) = rowmap ? rowmap[p] : p.
-// A thread keeps its 4 columns of the R panel rows in registers and walks the rows of its
-// run.  Block (ceil(L / 1024), E, RX_SPLIT).
+// A thread keeps its 4 columns of the R panel rows in registers (as FP16 pairs of rank rows,
+// multiplied by v_dot2_f32_f16: exact products, FP32 sums) and walks the rows of its run.
+// Block (ceil(L / 1024), E, RX_SPLIT).
 constexpr int RX_SPLIT = 8;
 template <int R, class OutT>
 __global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __restrict__ t,
@@ -325,12 +326,14 @@ __global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __rest
   const int per = (n + RX_SPLIT - 1) / RX_SPLIT;
   const int p0 = lo + sp * per, p1 = min(lo + n, p0 + per);
   if (p0 >= p1) return;
-  float w[R][4];
+  // the panel rows in pairs (rho, rho + 1): one two-element dot product per pair and column
+  half2v w[R / 2][4];
 #pragma unroll
-  for (int rho = 0; rho < R; ++rho) {
-    const half4 v = *(const half4*)(P + ((size_t)e * RP + rho) * L + col);
+  for (int q2 = 0; q2 < R / 2; ++q2) {
+    const half4 v0 = *(const half4*)(P + ((size_t)e * RP + 2 * q2) * L + col);
+    const half4 v1 = *(const half4*)(P + ((size_t)e * RP + 2 * q2 + 1) * L + col);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[rho][i] = (float)v[i];
+    for (int i = 0; i < 4; ++i) w[q2][i] = half2v{v0[i], v1[i]};
   }
   for (int pb = p0; pb < p1; pb += 4) {
     float acc[4][4];
@@ -339,14 +342,14 @@ __global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __rest
     for (int u = 0; u < 4; ++u) {
       const int p = min(pb + u, p1 - 1);
       row[u] = rowmap != nullptr ? (size_t)rowmap[p] : (size_t)p;
-      const half_t* tp = t + (size_t)p * RP;
+      const half2v* tp = (const half2v*)(t + (size_t)p * RP);
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[u][i] = 0.f;
 #pragma unroll
-      for (int rho = 0; rho < R; ++rho) {
-        const float tv = (float)tp[rho];
+      for (int q2 = 0; q2 < R / 2; ++q2) {
+        const half2v tv = tp[q2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[u][i] += tv * w[rho][i];
+        for (int i = 0; i < 4; ++i) acc[u][i] = __builtin_amdgcn_fdot2(tv, w[q2][i], acc[u][i], false);
       }
     }
 #pragma unroll
@@ -374,8 +377,9 @@ void rankexpand(int r, const half_t* t, const half_t* P, int L, const int* offe,
 }
 
 // Factor gradients: part[sp][e][rho][n] = sum over the sorted pair rows p of expert e in
-// split sp of coef_p * t[p][rho] * D[row(p)][n], rho < R; row(p) = p (D in sorted pair order)
-// or permm[p] / k (D = x or dy); coef_p = gate[permm[p]] or 1.  The rows of an expert are cut
+// split sp of t[p][rho] * D[row(p)][n], rho < R; row(p) = p (D in sorted pair order) or
+// permm[p] / k (D = x or dy); a gate factor is folded into t beforehand (bw_scale_kernel).
+// Products are exact (FP16 x FP16), sums FP32.  The rows of an expert are cut
 // into RG_SPLIT equal runs, added in row order; bw_rankgrad_finish_kernel adds the runs in
 // order.  One thread owns C consecutive columns n.  Block (ceil(L / (256 C)), E, RG_SPLIT).
 constexpr int RG_SPLIT = 4;
@@ -383,8 +387,7 @@ template <int R, int C>
 __global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restrict__ t, const half_t* __restrict__ D,
                                                           int L, const int* __restrict__ offe,
                                                           const int* __restrict__ permm, int k, int gather,
-                                                          const float* __restrict__ gate, int E,
-                                                          float* __restrict__ part) {
+                                                          int E, float* __restrict__ part) {
   typedef _Float16 halfC __attribute__((ext_vector_type(C)));
   const int e = blockIdx.y, sp = blockIdx.z;
   const int col = (blockIdx.x * 256 + threadIdx.x) * C;
@@ -397,29 +400,29 @@ __global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restri
   for (int rho = 0; rho < R; ++rho)
 #pragma unroll
     for (int i = 0; i < C; ++i) acc[rho][i] = 0.f;
-  // four rows per batch: their loads are issued before the first is used
+  // four rows per batch (their loads are issued before the first is used), multiplied in
+  // pairs of rows: acc += t[p][rho] D[p][n] + t[p+1][rho] D[p+1][n] is one v_dot2_f32_f16
   for (int pb = p0; pb < p1; pb += 4) {
     halfC v[4];
-    float cf[4];
+    const half_t* tp[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int p = min(pb + u, p1 - 1);
-      const int m = permm[p];
-      const size_t row = gather ? (size_t)(m / k) : (size_t)p;
+      const size_t row = gather ? (size_t)(permm[p] / k) : (size_t)p;
       v[u] = *(const halfC*)(D + row * L + col);
-      cf[u] = pb + u < p1 ? (gate != nullptr ? gate[m] : 1.f) : 0.f;
+      if (pb + u >= p1) v[u] = halfC{};          // rows past the run contribute nothing
+      tp[u] = t + (size_t)p * RP;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      float dv[C];
+    for (int u = 0; u < 4; u += 2) {
+      half2v dv[C];
 #pragma unroll
-      for (int i = 0; i < C; ++i) dv[i] = cf[u] * (float)v[u][i];
-      const half_t* tp = t + (size_t)min(pb + u, p1 - 1) * RP;
+      for (int i = 0; i < C; ++i) dv[i] = half2v{v[u][i], v[u + 1][i]};
 #pragma unroll
       for (int rho = 0; rho < R; ++rho) {
-        const float tv = (float)tp[rho];
+        const half2v tv = half2v{tp[u][rho], tp[u + 1][rho]};
 #pragma unroll
-        for (int i = 0; i < C; ++i) acc[rho][i] += tv * dv[i];
+        for (int i = 0; i < C; ++i) acc[rho][i] = __builtin_amdgcn_fdot2(tv, dv[i], acc[rho][i], false);
       }
     }
   }
@@ -441,23 +444,36 @@ __global__ __launch_bounds__(256) void bw_rankgrad_finish_kernel(const float* __
   *(float4v*)(out + i) = acc;
 }
 
+// t[p][rho] *= gate[permm[p]] for the M sorted pair rows (32 rank columns each)
+__global__ __launch_bounds__(256) void bw_scale_kernel(half_t* __restrict__ t, const int* __restrict__ permm,
+                                                       const float* __restrict__ gate, int M) {
+  const int idx = blockIdx.x * 256 + threadIdx.x, p = idx >> 2;
+  if (p >= M) return;
+  const float g = gate[permm[p]];
+  half8* v = (half8*)(t + (size_t)p * RP + (idx & 3) * 8);
+  half8 x = *v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = (half_t)(g * (float)x[i]);
+  *v = x;
+}
+
 template <int R>
 void rankgrad_r(const half_t* t, const half_t* D, int L, const int* offe, const int* permm, int k, int gather,
-                const float* gate, int E, float* part, float* out, hipStream_t st) {
+                int E, float* part, float* out, hipStream_t st) {
   constexpr int C = R >= 32 ? 4 : 8;
   hipLaunchKernelGGL((bw_rankgrad_kernel<R, C>), dim3((L + 256 * C - 1) / (256 * C), E, RG_SPLIT), dim3(256), 0, st, t,
-                     D, L, offe, permm, k, gather, gate, E, part);
+                     D, L, offe, permm, k, gather, E, part);
   const size_t n = (size_t)E * R * L;
   hipLaunchKernelGGL(bw_rankgrad_finish_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, st, part, n, out);
 }
 
 void rankgrad(int r, const half_t* t, const half_t* D, int L, const int* offe, const int* permm, int k, int gather,
-              const float* gate, int E, float* part, float* out, hipStream_t st) {
+              int E, float* part, float* out, hipStream_t st) {
   switch (r) {
-    case 4: rankgrad_r<4>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
-    case 8: rankgrad_r<8>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
-    case 16: rankgrad_r<16>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
-    default: rankgrad_r<32>(t, D, L, offe, permm, k, gather, gate, E, part, out, st); break;
+    case 4: rankgrad_r<4>(t, D, L, offe, permm, k, gather, E, part, out, st); break;
+    case 8: rankgrad_r<8>(t, D, L, offe, permm, k, gather, E, part, out, st); break;
+    case 16: rankgrad_r<16>(t, D, L, offe, permm, k, gather, E, part, out, st); break;
+    default: rankgrad_r<32>(t, D, L, offe, permm, k, gather, E, part, out, st); break;
   }
 }
 
@@ -654,10 +670,15 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
                              nullptr, out.dw2_base, f, true, st, (long)f * 32, (long)d * 32));
   // factor gradients: contraction over the pairs of an expert, streamed once
   float* part = F(L.rgpart);
-  rankgrad(r, H(L.t1), H(L.dh16), f, offe, permm, k, 0, nullptr, E, part, out.du1, st);
-  rankgrad(r, H(L.qq), x, d, offe, permm, k, 1, nullptr, E, part, out.dv1, st);
-  rankgrad(r, H(L.ss), dy, d, offe, permm, k, 1, gate, E, part, out.du2, st);
-  rankgrad(r, H(L.uy), H(L.a16), f, offe, permm, k, 0, gate, E, part, out.dv2, st);
+  rankgrad(r, H(L.t1), H(L.dh16), f, offe, permm, k, 0, E, part, out.du1, st);
+  rankgrad(r, H(L.qq), x, d, offe, permm, k, 1, E, part, out.dv1, st);
+  // the gate of the pair goes into the rank-space rows of the two products of the second matrix
+  if (M > 0) {
+    hipLaunchKernelGGL(bw_scale_kernel, dim3((M * 4 + 255) / 256), dim3(256), 0, st, H(L.ss), permm, gate, M);
+    hipLaunchKernelGGL(bw_scale_kernel, dim3((M * 4 + 255) / 256), dim3(256), 0, st, H(L.uy), permm, gate, M);
+  }
+  rankgrad(r, H(L.ss), dy, d, offe, permm, k, 1, E, part, out.du2, st);
+  rankgrad(r, H(L.uy), H(L.a16), f, offe, permm, k, 0, E, part, out.dv2, st);
 #undef BW_GEMM
 #undef BW_CHECK
   return hipGetLastError();
