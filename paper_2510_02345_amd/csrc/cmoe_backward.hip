@@ -400,24 +400,32 @@ __global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restri
   for (int rho = 0; rho < R; ++rho)
 #pragma unroll
     for (int i = 0; i < C; ++i) acc[rho][i] = 0.f;
-  // four rows per batch (their loads are issued before the first is used), multiplied in
-  // pairs of rows: acc += t[p][rho] D[p][n] + t[p+1][rho] D[p+1][n] is one v_dot2_f32_f16
-  for (int pb = p0; pb < p1; pb += 4) {
-    halfC v[4];
-    const half_t* tp[4];
+  // Four rows per batch, multiplied in pairs of rows: acc += t[p][rho] D[p][n] +
+  // t[p+1][rho] D[p+1][n] is one v_dot2_f32_f16.  The loads of the next batch are issued
+  // before the current one is used, so that a wavefront keeps eight rows in flight.
+  auto load = [&](int pb, halfC (&v)[4]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int p = min(pb + u, p1 - 1);
       const size_t row = gather ? (size_t)(permm[p] / k) : (size_t)p;
       v[u] = *(const halfC*)(D + row * L + col);
-      if (pb + u >= p1) v[u] = halfC{};          // rows past the run contribute nothing
-      tp[u] = t + (size_t)p * RP;
+    }
+  };
+  halfC cur[4], nxt[4];
+  if (p0 < p1) load(p0, cur);
+  for (int pb = p0; pb < p1; pb += 4) {
+    if (pb + 4 < p1) load(pb + 4, nxt);
+    const half_t* tp[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (pb + u >= p1) cur[u] = halfC{};          // rows past the run contribute nothing
+      tp[u] = t + (size_t)min(pb + u, p1 - 1) * RP;
     }
 #pragma unroll
     for (int u = 0; u < 4; u += 2) {
       half2v dv[C];
 #pragma unroll
-      for (int i = 0; i < C; ++i) dv[i] = half2v{v[u][i], v[u + 1][i]};
+      for (int i = 0; i < C; ++i) dv[i] = half2v{cur[u][i], cur[u + 1][i]};
 #pragma unroll
       for (int rho = 0; rho < R; ++rho) {
         const half2v tv = half2v{tp[u][rho], tp[u + 1][rho]};
@@ -425,6 +433,8 @@ __global__ __launch_bounds__(256) void bw_rankgrad_kernel(const half_t* __restri
         for (int i = 0; i < C; ++i) acc[rho][i] = __builtin_amdgcn_fdot2(tv, dv[i], acc[rho][i], false);
       }
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
   }
 #pragma unroll
   for (int rho = 0; rho < R; ++rho) {
