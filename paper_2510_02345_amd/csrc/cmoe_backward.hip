@@ -230,31 +230,36 @@ __global__ __launch_bounds__(256) void bw_dx_kernel(const float* __restrict__ dx
   *(float4v*)(dx + t * d + col) = acc;
 }
 
-// d v_e = sum over the pair rows of expert e of dl_m x_t, rows in sorted order.
+// d v_e = sum over the pair rows of expert e of dl_m x_t: part[run][e][col], the rows of the
+// expert cut into DR_SPLIT runs added in row order (bw_rankgrad_finish_kernel adds the runs).
+// Block (E, ceil(d / 1024), DR_SPLIT).
+constexpr int DR_SPLIT = 4;
 __global__ __launch_bounds__(256) void bw_drouter_kernel(const half_t* __restrict__ x, const int* __restrict__ permm,
                                                          const int* __restrict__ offe, const float* __restrict__ dl,
-                                                         int k, int d, float* __restrict__ d_re) {
-  const int e = blockIdx.x;
+                                                         int k, int d, int E, float* __restrict__ part) {
+  const int e = blockIdx.x, sp = blockIdx.z;
   const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
   if (col >= d) return;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  const int lo = offe[e], hi = offe[e + 1];
-  for (int p0 = lo; p0 < hi; p0 += 4) {
-    half4 v[4];
-    float c[4];
+  const int lo = offe[e], n = offe[e + 1] - lo;
+  const int per = (n + DR_SPLIT - 1) / DR_SPLIT;
+  const int p_lo = lo + sp * per, p_hi = min(lo + n, p_lo + per);
+  for (int p0 = p_lo; p0 < p_hi; p0 += 8) {
+    half4 v[8];
+    float c[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const bool ok = p0 + u < hi;
+    for (int u = 0; u < 8; ++u) {
+      const bool ok = p0 + u < p_hi;
       const int m = ok ? permm[p0 + u] : 0;
       c[u] = ok ? dl[m] : 0.f;
       v[u] = *(const half4*)(x + (size_t)(m / k) * d + col);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] += c[u] * (float)v[u][i];
   }
-  *(float4v*)(d_re + (size_t)e * d + col) = float4v{acc[0], acc[1], acc[2], acc[3]};
+  *(float4v*)(part + ((size_t)sp * E + e) * d + col) = float4v{acc[0], acc[1], acc[2], acc[3]};
 }
 
 // out[z][i][qc] = scale[qc] * src[z][idx[qc]][i] (zero where idx[qc] < 0; idx == NULL: row
@@ -670,8 +675,11 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     transpose(H(L.ag16), f, f, ssrc_c, nullptr, Tpad, H(L.agt), st);
     BW_CHECK(hipGetLastError());
   }
-  hipLaunchKernelGGL(bw_drouter_kernel, dim3(E, (d / 4 + 255) / 256), dim3(256), 0, st, x, permm, offe, dl, k, d,
-                     out.d_router_expert);
+  static_assert(DR_SPLIT == RG_SPLIT, "the finish kernel adds RG_SPLIT runs");
+  hipLaunchKernelGGL(bw_drouter_kernel, dim3(E, (d / 4 + 255) / 256, DR_SPLIT), dim3(256), 0, st, x, permm, offe, dl,
+                     k, d, E, F(L.rgpart));
+  hipLaunchKernelGGL(bw_rankgrad_finish_kernel, dim3((unsigned)(((size_t)E * d / 4 + 255) / 256)), dim3(256), 0, st,
+                     (const float*)F(L.rgpart), (size_t)E * d, out.d_router_expert);
   // base gradients: contraction over the tokens of a cluster
   // (operands in the blocked layout [Tpad / 32][rows][32]: row stride 32, block stride rows * 32)
   BW_CHECK(launch_gemm_plain(H(L.xct), 0, 32, d, H(L.dhst), 32, I(L.gidx_f), 1, Tpad, I(L.offx_f), G, G * f, krc,
