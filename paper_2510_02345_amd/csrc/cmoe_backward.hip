@@ -212,16 +212,19 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const half_t* __restrict__ 
 
 // dx[t] = dxb[t] + sum_j dxr[t k + j] + sum_j dl_j v_{e_j}: shared-base part, per-pair
 // residual part, and the gate path of Eq. 10.
-__global__ __launch_bounds__(256) void bw_dx_kernel(const float* __restrict__ dxb, const float* __restrict__ dxr,
+__global__ __launch_bounds__(256) void bw_dx_kernel(const half_t* __restrict__ dxb, const half_t* __restrict__ dxr,
                                                     const float* __restrict__ dl, const int* __restrict__ expert_idx,
                                                     const half_t* __restrict__ router_expert, int k, int d,
                                                     float* __restrict__ dx) {
   const size_t t = blockIdx.x;
   const int col = (blockIdx.y * 256 + threadIdx.x) * 4;
   if (col >= d) return;
-  float4v acc = *(const float4v*)(dxb + t * d + col);
+  const half4 b4 = *(const half4*)(dxb + t * d + col);
+  float4v acc = {(float)b4[0], (float)b4[1], (float)b4[2], (float)b4[3]};
   for (int j = 0; j < k; ++j) {
-    acc += *(const float4v*)(dxr + (t * k + j) * d + col);
+    const half4 r4 = *(const half4*)(dxr + (t * k + j) * d + col);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += (float)r4[i];
     const float c = dl[t * k + j];
     const half4 v = *(const half4*)(router_expert + (size_t)expert_idx[t * k + j] * d + col);
 #pragma unroll
@@ -552,8 +555,8 @@ cmoe_bw_layout cmoe_backward_layout(const cmoe_dims& dm, int T) {
   L.uy = take(sizeof(half_t) * M * 32);
   L.qq = take(sizeof(half_t) * M * 32);
   L.ss = take(sizeof(half_t) * M * 32);
-  L.dxb = take(sizeof(float) * Tz * d);
-  L.dxr = take(sizeof(float) * M * d);
+  L.dxb = take(sizeof(half_t) * Tz * d);
+  L.dxr = take(sizeof(half_t) * M * d);
   L.xct = take(sizeof(half_t) * d * Tp);
   L.dyct = take(sizeof(half_t) * d * Tp);
   L.dhst = take(sizeof(half_t) * f * Tp);
@@ -658,11 +661,11 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
       hipLaunchKernelGGL(bw_act_kernel<8>, dim3(T), dim3(256), 0, st, H(L.hb), H(L.dab), H(L.rh), H(L.rda), invm, gate, k,
                          f, H(L.a16), H(L.dh16), H(L.dhsum16), H(L.ag16), dl);
     // dx = B1^T (sum_j dh) + sum_j V1^T (U1^T dh) + gate path
-    BW_CHECK(launch_gemm_plain(H(L.w1bt), mat, 32, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, F(L.dxb), d,
-                               true, st, (long)d * 32, 0));
+    BW_CHECK(launch_gemm_plain(H(L.w1bt), mat, 32, d, H(L.dhsum16), f, permc, 1, f, offc, G, T, nullptr, permc, H(L.dxb), d,
+                               false, st, (long)d * 32, 0));
     BW_CHECK(rank_gemm(H(L.u1p), f, H(L.dh16), f, nullptr, 1, H(L.qq)));
-    rankexpand(r, H(L.qq), H(L.v1p), d, offe, permm, E, F(L.dxr), st);
-    hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, F(L.dxb), F(L.dxr), dl, expert_idx,
+    rankexpand(r, H(L.qq), H(L.v1p), d, offe, permm, E, H(L.dxr), st);
+    hipLaunchKernelGGL(bw_dx_kernel, dim3(T, (d / 4 + 255) / 256), dim3(256), 0, st, H(L.dxb), H(L.dxr), dl, expert_idx,
                        (const half_t*)w.router_expert, k, d, out.dx);
     // s = V2 a per pair
     BW_CHECK(rank_gemm(H(L.v2p), f, H(L.a16), f, nullptr, 1, H(L.ss)));

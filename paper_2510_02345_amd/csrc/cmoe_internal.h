@@ -149,7 +149,7 @@ struct cmoe_bw_layout {
   size_t hb, dab, rh, rda;                    // f16 [T][d_ff] x2 (token order), [M][d_ff] x2 (sorted pairs)
   size_t a16, dh16, dhsum16, ag16;            // f16 [M][d_ff] x2, [T][d_ff] x2
   size_t t1, uy, qq, ss;                      // f16 [M][32] rank-space rows of the pairs
-  size_t dxb, dxr;                            // f32 [T][d], [M][d]
+  size_t dxb, dxr;                            // f16 [T][d], [M][d]
   size_t xct, dyct, dhst, agt;                // f16 transposed copies, Tpad columns
   size_t rgpart;                              // f32 [4][E][r][max(d, d_ff)] partial factor gradients
   size_t total;
