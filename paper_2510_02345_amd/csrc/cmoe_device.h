@@ -149,21 +149,28 @@ struct FusedUp {
   }
 
   // The lane holds rows 8*qd + 4h + (0..3) of the pass accumulator; those inside
-  // [b_e*R, b_e*R + R) are the token's s_j.  dst_tile: [T][k][R] partial of this row tile.
-  __device__ static __forceinline__ void store_s(const Tok& t, const float16v (&sacc)[KMAX], float* dst_tile, int k,
+  // [b_e*R, b_e*R + R) are the token's s_j.  dst_tile: [T][k][R] partial of this row tile
+  // (FP32, or FP16 where many partials are summed afterwards in FP32).
+  template <class ST>
+  __device__ static __forceinline__ void store_s(const Tok& t, const float16v (&sacc)[KMAX], ST* dst_tile, int k,
                                                  int h) {
     if (!t.valid) return;
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
       if (j >= k) continue;
       const int be = (t.e[j] % EPB) * R;
-      float* dst = dst_tile + ((size_t)t.p * k + j) * R;
+      ST* dst = dst_tile + ((size_t)t.p * k + j) * R;
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
         int row0 = 8 * qd + 4 * h;
         if (row0 >= be && row0 < be + R) {
-          float4v v4 = {sacc[j][4 * qd], sacc[j][4 * qd + 1], sacc[j][4 * qd + 2], sacc[j][4 * qd + 3]};
-          *(float4v*)(dst + row0 - be) = v4;
+          if constexpr (sizeof(ST) == 2) {
+            *(half4*)(dst + row0 - be) = half4{(half_t)sacc[j][4 * qd], (half_t)sacc[j][4 * qd + 1],
+                                               (half_t)sacc[j][4 * qd + 2], (half_t)sacc[j][4 * qd + 3]};
+          } else {
+            float4v v4 = {sacc[j][4 * qd], sacc[j][4 * qd + 1], sacc[j][4 * qd + 2], sacc[j][4 * qd + 3]};
+            *(float4v*)(dst + row0 - be) = v4;
+          }
         }
       }
     }

@@ -660,7 +660,7 @@ struct EpiFusedUp {
   const int* expert_idx;
   const float* gate;
   half_t* A;          // [T][d_ff]
-  float* spart;       // [n_tiles][T][k][r]
+  half_t* spart;      // [n_tiles][T][k][r] partials of V2 a over the tile's 256 rows of d_ff, FP16 (summed in FP32)
   int T, k, K, KRp, d_ff;
   using FU = FusedUp<R, KMAX>;
 
@@ -804,8 +804,8 @@ struct EpiFusedUp {
 // s_down[perm[p]][w] = sum over row tiles of spart[tile][p][w], in a fixed order: a block
 // owns 64 consecutive outputs, its NW wavefronts each sum every NW-th tile, and the NW
 // sums are added in wavefront order.
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void sreduce_kernel(const float* __restrict__ spart,
+template <int NW, class ST>
+__global__ __launch_bounds__(64 * NW) void sreduce_kernel(const ST* __restrict__ spart,
                                                           const int* __restrict__ perm, int T, int kr, int n_tiles,
                                                           float* __restrict__ s_down) {
   __shared__ float part[NW][64];
@@ -815,7 +815,7 @@ __global__ __launch_bounds__(64 * NW) void sreduce_kernel(const float* __restric
   float sum = 0.f;
   if (idx < total) {
 #pragma unroll 8
-    for (int nt = wave; nt < n_tiles; nt += NW) sum += spart[(size_t)nt * total + idx];
+    for (int nt = wave; nt < n_tiles; nt += NW) sum += (float)spart[(size_t)nt * total + idx];
   }
   part[wave][lane] = sum;
   __syncthreads();
@@ -983,10 +983,10 @@ hipError_t launch_gemm1_rk(const cmoe_dims& dm, const GemmArgs& g, int T, const 
                            float* spart, hipStream_t st) {
   using TL = TileUp;
   if (dm.KRp <= 128) {
-    EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+    EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, (half_t*)spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
     return launch_gemm<TL>(g, T, epi, st);
   }
-  EpiFusedUp<R, KMAX, false> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+  EpiFusedUp<R, KMAX, false> epi{u1t, v2p, t1, perm, expert_idx, gate, a, (half_t*)spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
   return launch_gemm<TL>(g, T, epi, st);
 }
 
@@ -1040,15 +1040,21 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
 }
 
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
-                          float* s_down, hipStream_t st) {
+                          float* s_down, hipStream_t st, bool half_in) {
   int kr = dm.k * dm.r;
   size_t n = (size_t)T * kr;
-  if (n_parts > 128)
-    hipLaunchKernelGGL(sreduce_kernel<16>, dim3((unsigned)((n + 63) / 64)), dim3(1024), 0, st, spart, perm, T, kr,
-                       n_parts, s_down);
-  else
-    hipLaunchKernelGGL(sreduce_kernel<4>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, spart, perm, T, kr,
-                       n_parts, s_down);
+  const dim3 grid((unsigned)((n + 63) / 64));
+  if (half_in) {   // the fused up-projection leaves FP16 partials in the same buffer
+    const half_t* sp = (const half_t*)spart;
+    if (n_parts > 128)
+      hipLaunchKernelGGL((sreduce_kernel<16, half_t>), grid, dim3(1024), 0, st, sp, perm, T, kr, n_parts, s_down);
+    else
+      hipLaunchKernelGGL((sreduce_kernel<4, half_t>), grid, dim3(256), 0, st, sp, perm, T, kr, n_parts, s_down);
+  } else if (n_parts > 128) {
+    hipLaunchKernelGGL((sreduce_kernel<16, float>), grid, dim3(1024), 0, st, spart, perm, T, kr, n_parts, s_down);
+  } else {
+    hipLaunchKernelGGL((sreduce_kernel<4, float>), grid, dim3(256), 0, st, spart, perm, T, kr, n_parts, s_down);
+  }
   return hipGetLastError();
 }
 
