@@ -1161,22 +1161,26 @@ hipError_t launch_gemm_plain(const half_t* W, long w_gstride, int ldw, int N, co
   return launch_gemm<TL, EpiStore, TileTail>(g, rows, epi, st);
 }
 
-// packed[c][(k / 32) * N + n][k % 32] = base[c][n][k]: one thread moves 8 elements.
+// packed[c][(k / 32) * N + n][k % 32] = base[c][n][k].  A workgroup takes 64 rows n (four
+// threads per row, 16 bytes each) and walks the 32-column blocks of a quarter of K: every
+// store instruction of the workgroup writes 4 KiB of contiguous memory.
 __global__ __launch_bounds__(256) void pack_base_kernel(const half_t* __restrict__ base, int N, int K,
                                                         half_t* __restrict__ packed) {
   const size_t mat = (size_t)N * K;
-  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;   // element index inside the cluster's matrix
-  if (i >= mat) return;
-  const size_t c = blockIdx.y;
-  const int n = (int)(i / K), k = (int)(i % K);
-  *(half8*)(packed + c * mat + ((size_t)(k >> 5) * N + n) * 32 + (k & 31)) = *(const half8*)(base + c * mat + i);
+  const int n = blockIdx.x * 64 + (threadIdx.x >> 2), c8 = (threadIdx.x & 3) * 8;
+  if (n >= N) return;
+  const half_t* src = base + blockIdx.z * mat + (size_t)n * K + c8;
+  half_t* dst = packed + blockIdx.z * mat + (size_t)n * 32 + c8;
+  const int nb = K / 32, per = (nb + 3) / 4, b0 = blockIdx.y * per, b1 = min(nb, b0 + per);
+#pragma unroll 4
+  for (int kb = b0; kb < b1; ++kb) *(half8*)(dst + (size_t)kb * N * 32) = *(const half8*)(src + kb * 32);
 }
 
 hipError_t launch_pack_bases(const cmoe_dims& dm, const cmoe_weights& w, half_t* packed, hipStream_t st) {
   const size_t mat = (size_t)dm.d * dm.d_ff;
-  const dim3 grid((unsigned)((mat / 8 + 255) / 256), dm.G);
-  hipLaunchKernelGGL(pack_base_kernel, grid, dim3(256), 0, st, (const half_t*)w.w1_base, dm.d_ff, dm.d, packed);
-  hipLaunchKernelGGL(pack_base_kernel, grid, dim3(256), 0, st, (const half_t*)w.w2_base, dm.d, dm.d_ff,
-                     packed + mat * dm.G);
+  hipLaunchKernelGGL(pack_base_kernel, dim3((dm.d_ff + 63) / 64, 4, dm.G), dim3(256), 0, st, (const half_t*)w.w1_base,
+                     dm.d_ff, dm.d, packed);
+  hipLaunchKernelGGL(pack_base_kernel, dim3((dm.d + 63) / 64, 4, dm.G), dim3(256), 0, st, (const half_t*)w.w2_base,
+                     dm.d, dm.d_ff, packed + mat * dm.G);
   return hipGetLastError();
 }
