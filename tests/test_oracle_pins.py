@@ -674,3 +674,104 @@ def test_backward_sampled_is_a_slice_of_the_full_backward():
     assert np.allclose(got["du1"], full["du1"][:, :, hidden], rtol=1e-11, atol=1e-13)
     assert np.allclose(got["dv2"], full["dv2"][:, :, hidden], rtol=1e-11, atol=1e-13)
     assert np.abs(full["dgate_logits"]).max() > 1e-3 and np.abs(full["du1"]).max() > 1e-3
+
+
+# ------------------------------------------------------------------ the bars themselves
+def test_error_metrics_hand_values():
+    # y_ref = (3, 4), y = (3, 5): one element off by 1; RMS(y_ref) = sqrt((9 + 16) / 2) = sqrt(12.5),
+    # sum |y_ref| = 7.  RMS(y) would be sqrt(17) and sum |y| = 8: a metric normalised by y instead
+    # of y_ref, or by a plain mean of |y_ref| (3.5), gives other numbers.
+    m = orc.error_metrics(np.array([3.0, 5.0]), np.array([3.0, 4.0]))
+    assert m["max_over_rms"] == pytest.approx(1.0 / math.sqrt(12.5), rel=1e-15)
+    assert m["mean_rel"] == pytest.approx(1.0 / 7.0, rel=1e-15)
+    assert m["rms"] == pytest.approx(math.sqrt(12.5), rel=1e-15)
+    # two dimensions, signs, and an FP16 input: the maximum runs over every element, the RMS and
+    # the sums over the whole array (not per row, not per column)
+    y_ref = np.array([[1.0, -2.0, 2.0], [-4.0, 0.0, 0.0]])
+    y = np.array([[1.0, -2.5, 2.0], [-4.0, 0.25, 0.0]], dtype=np.float16)
+    m = orc.error_metrics(y, y_ref)
+    assert m["max_over_rms"] == pytest.approx(0.5 / math.sqrt(25.0 / 6.0), rel=1e-15)
+    assert m["mean_rel"] == pytest.approx(0.75 / 9.0, rel=1e-15)
+    # identical arrays: zero; empty arrays: zero, no division
+    assert orc.error_metrics(y_ref, y_ref)["max_over_rms"] == 0.0 and orc.error_metrics(y_ref, y_ref)["mean_rel"] == 0.0
+    e = orc.error_metrics(np.zeros((0, 4)), np.zeros((0, 4)))
+    assert e["max_over_rms"] == 0.0 and e["mean_rel"] == 0.0
+
+
+def test_error_metrics_cases_the_bars_must_reject():
+    # the bars of the GPU tests: max / RMS <= 1e-2 and mean-rel <= 2e-3
+    rng = np.random.default_rng(17)
+    y_ref = rng.standard_normal((64, 32))
+    rms = math.sqrt(float((y_ref ** 2).mean()))
+    # one element off by 2 % of the RMS: only the maximum bar trips
+    y = y_ref.copy()
+    y[5, 7] += 0.02 * rms
+    m = orc.error_metrics(y, y_ref)
+    assert m["max_over_rms"] == pytest.approx(0.02, rel=1e-12) and m["max_over_rms"] > 1e-2 and m["mean_rel"] < 2e-3
+    # every element off by 0.5 % of its own size: only the mean-relative bar trips
+    y = y_ref * 1.005
+    m = orc.error_metrics(y, y_ref)
+    assert m["mean_rel"] == pytest.approx(0.005, rel=1e-9) and m["mean_rel"] > 2e-3
+    assert m["max_over_rms"] == pytest.approx(0.005 * np.abs(y_ref).max() / rms, rel=1e-9)
+    # FP16 rounding of the reference passes both, a dropped 10 % term fails both
+    m = orc.error_metrics(y_ref.astype(np.float16), y_ref)
+    assert m["max_over_rms"] < 1e-2 and m["mean_rel"] < 2e-3
+    m = orc.error_metrics(0.9 * y_ref, y_ref)
+    assert m["max_over_rms"] > 1e-2 and m["mean_rel"] > 2e-3
+
+
+def test_residual_exact_case_and_sign():
+    # Eq. 7's residual is W_e - W_base (not the reverse), in float64, exact on FP16 inputs
+    W_e = np.array([[1.5, -2.0, 0.0]], dtype=np.float16)
+    base = np.array([[0.25, 1.0, -3.0]], dtype=np.float16)
+    d = orc.residual(W_e, base)
+    assert d.dtype == np.float64 and d.tolist() == [[1.25, -3.0, 3.0]]
+    # base + residual gives the expert back exactly, for values whose FP16 sum would round
+    rng = np.random.default_rng(23)
+    W_e = rng.standard_normal((8, 8)).astype(np.float16)
+    base = (rng.standard_normal((8, 8)) * 1e-3).astype(np.float16)
+    assert np.array_equal(base.astype(np.float64) + orc.residual(W_e, base), W_e.astype(np.float64))
+
+
+def test_base_and_quantiser_meet_their_definitions_in_fp64():
+    """Eq. 6 and the quantiser of Sec. 3.4 written out in FP64, independent of the order and
+    precision in which base_mean / quantize_int4_f32 take their steps: the stored base is a
+    nearest FP16 neighbour of the exact mean, the scale the FP16 rounding of absmax / 7, every
+    code the integer nearest to w / scale (either neighbour at a tie), clipped to [-7, 7]."""
+    rng = np.random.default_rng(31)
+    G, K = 3, 5
+    W = rng.standard_normal((G * K, 12, 20)).astype(np.float16)
+    base = orc.base_mean(W, G, K).astype(np.float64)
+    exact = W.astype(np.float64).reshape(G, K, 12, 20).sum(axis=1) / K
+    # the two FP16 neighbours that bracket the exact mean
+    f = exact.astype(np.float16).astype(np.float64)
+    below = np.where(f <= exact, f, np.nextafter(exact.astype(np.float16), np.float16(-np.inf)).astype(np.float64))
+    above = np.where(f >= exact, f, np.nextafter(exact.astype(np.float16), np.float16(np.inf)).astype(np.float64))
+    assert np.all(below <= exact) and np.all(exact <= above)
+    nearest = np.where(exact - below <= above - exact, below, above)
+    tie = np.abs((exact - below) - (above - exact)) <= 2.0 ** -24 * np.abs(exact) * 8   # FP32 sum rounding
+    assert np.all((base == nearest) | (tie & ((base == below) | (base == above))))
+    # and it is the correctly rounded (ties to even) FP16 value of the exact mean almost everywhere:
+    # only the double rounding through FP32 can differ, next to a tie
+    assert np.mean(base == f) > 0.999
+
+    q = 8
+    w = (rng.standard_normal((7, 64)) * 0.03).astype(np.float32)
+    w[2, :q] = 0.0
+    packed, scale = orc.quantize_int4_f32(w, q)
+    codes = orc.unpack_int4(packed).astype(np.float64)
+    w64 = w.astype(np.float64).reshape(7, 64 // q, q)
+    absmax = np.abs(w64).max(axis=-1)
+    assert np.array_equal(scale, (absmax / 7.0).astype(np.float16))          # FP64 quotient, rounded once
+    s = scale.astype(np.float64)
+    c = codes.reshape(7, 64 // q, q)
+    assert np.all(np.abs(c) <= 7)
+    live = s > 0
+    ratio = w64[live] / s[live][:, None]
+    want = np.clip(ratio, -7.0, 7.0)
+    # nearest integer to the clipped ratio; at a tie (within FP32 rounding of the division) either neighbour
+    assert np.all(np.abs(c[live] - want) <= 0.5 + 1e-6)
+    assert np.all(c[~live] == 0)
+    # the reconstruction w ~ scale * code is within half a step wherever no clipping took place
+    inside = np.abs(ratio) <= 7.0
+    assert np.all(np.abs(s[live][:, None] * c[live] - w64[live])[inside] <= 0.5 * np.broadcast_to(s[live][:, None], ratio.shape)[inside] * (1 + 1e-6))
