@@ -86,19 +86,26 @@ def route(x, router_cluster, router_expert, K, k, cluster_bias=None):
         z = z + cluster_bias.astype(np.float64)[None, :]
     # Eq. 9: p_g = softmax(z)_g; the largest p_g is the largest z_g.  argmax
     # returns the first maximum = lowest index on ties.
-    cluster_id = np.argmax(z, axis=1).astype(np.int32)
+    cluster_id = np.argmax(_rank_key(z), axis=1).astype(np.int32)
     l = np.empty((T, K), dtype=np.float64)
     for c in range(U.shape[0]):
         rows = np.nonzero(cluster_id == c)[0]
         if len(rows):
             l[rows] = X[rows] @ V[c * K:(c + 1) * K].T
     # Eq. 10 then top-k: stable sort of -l lists equal logits by ascending index
-    order = np.argsort(-l, axis=1, kind="stable")[:, :k]
+    order = np.argsort(-_rank_key(l), axis=1, kind="stable")[:, :k]
     lsel = np.take_along_axis(l, order, axis=1)
     ex = np.exp(lsel - lsel[:, :1])
     gate = ex / ex.sum(axis=1, keepdims=True)
     expert_idx = (cluster_id[:, None].astype(np.int64) * K + order).astype(np.int32)
     return cluster_id, expert_idx, gate, z, l
+
+
+def _rank_key(logits):
+    """Sec. 3.3 ranks finite logits and says nothing about NaN.  Reading taken: a NaN ranks
+    below every number (as -inf), equal ranks go to the lowest index, so a selection always
+    names distinct experts of one cluster whatever the inputs hold."""
+    return np.where(np.isnan(logits), -np.inf, logits)
 
 
 def route_multi(x, router_cluster, router_expert, K, k, top_g=1, temperature=1.0, scale_by_cluster_prob=False,
@@ -122,7 +129,7 @@ def route_multi(x, router_cluster, router_expert, K, k, top_g=1, temperature=1.0
     zt = z / temperature
     pe = np.exp(zt - zt.max(axis=1, keepdims=True))
     p = pe / pe.sum(axis=1, keepdims=True)
-    cluster_ids = np.argsort(-z, axis=1, kind="stable")[:, :top_g].astype(np.int32)
+    cluster_ids = np.argsort(-_rank_key(z), axis=1, kind="stable")[:, :top_g].astype(np.int32)
     psel = np.take_along_axis(p, cluster_ids.astype(np.int64), axis=1)
     wgt = psel if scale_by_cluster_prob else psel / psel.sum(axis=1, keepdims=True)
     expert_idx = np.empty((T, top_g, k), dtype=np.int32)
@@ -133,7 +140,7 @@ def route_multi(x, router_cluster, router_expert, K, k, top_g=1, temperature=1.0
             if len(rows) == 0:
                 continue
             l = X[rows] @ V[c * K:(c + 1) * K].T
-            order = np.argsort(-l, axis=1, kind="stable")[:, :k]
+            order = np.argsort(-_rank_key(l), axis=1, kind="stable")[:, :k]
             lsel = np.take_along_axis(l, order, axis=1) / temperature
             ex = np.exp(lsel - lsel[:, :1])
             gate[rows, a] = wgt[rows, a][:, None] * ex / ex.sum(axis=1, keepdims=True)

@@ -83,9 +83,19 @@ extern "C" int cmoe_destroy(cmoe_handle* h) {
   return CMOE_OK;
 }
 
+// A call with T tokens carves the layout of T, and the two paths (weight streaming up to
+// SKINNY_T tokens, matrix cores above) lay the buffer out differently, so a buffer "for up to
+// T_max tokens" must hold the larger of the two: each layout grows with T inside its own
+// range, hence the largest weight-streaming layout is that of min(T_max, SKINNY_T).
+static size_t workspace_for_up_to(const cmoe_dims& dm, int T_max) {
+  const size_t big = cmoe_layout(dm, T_max).total;
+  const size_t small = cmoe_layout(dm, T_max < SKINNY_T ? T_max : SKINNY_T).total;
+  return big > small ? big : small;
+}
+
 extern "C" size_t cmoe_workspace_bytes(const cmoe_handle* h, int32_t T_max) {
   if (!handle_ok(h) || T_max < 0) return 0;
-  return cmoe_layout(h->dm, T_max).total;
+  return workspace_for_up_to(h->dm, T_max);
 }
 
 extern "C" int cmoe_last_hip_error(const cmoe_handle* h) { return handle_ok(h) ? h->last_hip_error : 0; }
@@ -262,7 +272,6 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   half_t* a = (half_t*)(ws + L.a);
   float* spart = (float*)(ws + L.spart);
   if (T <= SKINNY_T) {
-    // few tokens: the layer is bound by streaming the base matrices once
     // few tokens: the layer is bound by streaming the base matrices once; the small
     // per-expert products ride along in the two stream launches
     const int n_parts = (dm.d_ff + SKINNY_SN - 1) / SKINNY_SN;
@@ -359,7 +368,7 @@ extern "C" size_t cmoe_workspace_bytes_multi(const cmoe_handle* h, int32_t T_max
   if (!handle_ok(h) || T_max < 0 || top_g < 1 || top_g > 8 || top_g > h->dm.G) return 0;
   if ((int64_t)T_max * top_g > INT32_MAX) return 0;
   const int Tv = T_max * top_g;
-  return align_up(cmoe_layout(h->dm, Tv).total, 256) + rep_bytes(h->dm, (size_t)Tv);
+  return align_up(workspace_for_up_to(h->dm, Tv), 256) + rep_bytes(h->dm, (size_t)Tv);
 }
 
 extern "C" int cmoe_forward_multi(cmoe_handle* h, const cmoe_weights* w, const cmoe_route_options* opt,

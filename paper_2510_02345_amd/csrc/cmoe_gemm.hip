@@ -493,15 +493,17 @@ struct EpiRoute {
       int selj[8];
       float den = 0.f;
       for (int a = 0; a < k; ++a) {
-        float bl = -INFINITY;
-        int bj = 0;
-        for (int j = 0; j < K; ++j)
+        // lowest slot not taken yet, replaced by any later slot with a larger logit: a NaN
+        // never wins a comparison, so it ranks below every number and the k slots are distinct
+        int bj = __ffsll((long long)~taken) - 1;
+        float bl = l[bj] == l[bj] ? l[bj] : -INFINITY;
+        for (int j = bj + 1; j < K; ++j)
           if (!((taken >> j) & 1ull) && l[j] > bl) {
             bl = l[j];
             bj = j;
           }
         taken |= 1ull << bj;
-        sel[a] = bl;
+        sel[a] = l[bj];
         selj[a] = bj;
       }
       const float lmax = sel[0];
@@ -566,16 +568,16 @@ struct EpiRouteMulti {
       float selp[8];
       float psum = 0.f;
       for (int a = 0; a < top_g; ++a) {
-        float bz = -INFINITY;
-        int bg = 0;
-        for (int g = 0; g < G; ++g)
+        int bg = __ffsll((long long)~ctaken) - 1;
+        float bz = row[bg] == row[bg] ? row[bg] : -INFINITY;
+        for (int g = bg + 1; g < G; ++g)
           if (!((ctaken >> g) & 1ull) && row[g] > bz) {
             bz = row[g];
             bg = g;
           }
         ctaken |= 1ull << bg;
         selc[a] = bg;
-        selp[a] = expf((bz - zmax) * inv_tau) / zden;
+        selp[a] = expf((row[bg] - zmax) * inv_tau) / zden;
         psum += selp[a];
       }
       for (int a = 0; a < top_g; ++a) {
@@ -586,15 +588,15 @@ struct EpiRouteMulti {
         float sel[8];
         int selj[8];
         for (int b = 0; b < k; ++b) {
-          float bl = -INFINITY;
-          int bj = 0;
-          for (int j = 0; j < K; ++j)
+          int bj = __ffsll((long long)~taken) - 1;
+          float bl = l[bj] == l[bj] ? l[bj] : -INFINITY;
+          for (int j = bj + 1; j < K; ++j)
             if (!((taken >> j) & 1ull) && l[j] > bl) {
               bl = l[j];
               bj = j;
             }
           taken |= 1ull << bj;
-          sel[b] = bl;
+          sel[b] = l[bj];
           selj[b] = bj;
         }
         const float lmax = sel[0];

@@ -16,6 +16,22 @@ __device__ __forceinline__ float dot8(half8 a, half8 b, float acc) {
   return acc;
 }
 
+// Ranking key of a logit: a NaN ranks below every number (as -inf), so that the selection
+// rounds below always return distinct, valid slots whatever the input holds.
+__device__ __forceinline__ float rank_key(float v) { return v == v ? v : -INFINITY; }
+
+// One round of (largest key, lowest lane) over the first n lanes, skipping lanes already
+// taken.  Returns the winning lane; marks it taken.
+__device__ __forceinline__ int select_round(float key, bool& taken, int lane, int n) {
+  float m = (lane < n && !taken) ? key : -INFINITY;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  const unsigned long long who = __ballot(lane < n && !taken && key == m);
+  const int j = who ? __ffsll((long long)who) - 1 : 0;   // who is non-empty while fewer than n lanes are taken
+  if (lane == j) taken = true;
+  return j;
+}
+
 constexpr int ROUTE_WAVES = 4;
 
 // One wavefront per token.  The token's row stays in registers for both stages: z_g over
@@ -71,20 +87,17 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void route_kernel(
   float sel_l[8];
   int sel_j[8];
   float lmax = 0.f;
+  const float key = rank_key(mine);
+  bool taken = false;
 #pragma unroll
   for (int a = 0; a < 8; ++a) {
     sel_l[a] = 0.f;
     sel_j[a] = 0;
     if (a < k) {
-      float m = mine;
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-      unsigned long long who = __ballot(mine == m);
-      int j = __ffsll((long long)who) - 1;
-      sel_l[a] = m;
+      const int j = select_round(key, taken, lane, K);
+      sel_l[a] = __shfl(mine, j, 64);
       sel_j[a] = j;
-      if (a == 0) lmax = m;
-      if (lane == j) mine = -INFINITY;
+      if (a == 0) lmax = sel_l[a];
     }
   }
   if (lane == 0) {
@@ -156,18 +169,17 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void route_multi_kernel(
   int sel_c[8];
   float sel_p[8];
   float psum = 0.f;
-  float zrem = zmine;
+  const float zkey = rank_key(zmine);
+  bool ztaken = false;
 #pragma unroll
   for (int a = 0; a < 8; ++a) {
     sel_c[a] = 0;
     sel_p[a] = 0.f;
     if (a < top_g) {
-      const float m = wave_max(zrem);
-      const int g = __ffsll((long long)__ballot(zrem == m)) - 1;
+      const int g = select_round(zkey, ztaken, lane, G);
       sel_c[a] = g;
       sel_p[a] = __shfl(pz, g, 64);
       psum += sel_p[a];
-      if (lane == g) zrem = -INFINITY;
     }
   }
 #pragma unroll
@@ -182,16 +194,16 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void route_multi_kernel(
     }
     float sel_l[8];
     int sel_j[8];
+    const float key = rank_key(mine);
+    bool taken = false;
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
       sel_l[b] = 0.f;
       sel_j[b] = 0;
       if (b < k) {
-        const float m = wave_max(mine);
-        const int j = __ffsll((long long)__ballot(mine == m)) - 1;
-        sel_l[b] = m;
+        const int j = select_round(key, taken, lane, K);
+        sel_l[b] = __shfl(mine, j, 64);
         sel_j[b] = j;
-        if (lane == j) mine = -INFINITY;
       }
     }
     if (lane == 0) {
@@ -358,24 +370,21 @@ __global__ __launch_bounds__(RS_WAVES * 64) void route_small_kernel(
   }
   __syncthreads();
   if (wave != 0) return;
-  float mine = (lane < K) ? ls[lane] : -INFINITY;
+  const float mine = (lane < K) ? ls[lane] : -INFINITY;
   float sel_l[8];
   int sel_j[8];
   float lmax = 0.f;
+  const float key = rank_key(mine);
+  bool taken = false;
 #pragma unroll
   for (int a = 0; a < 8; ++a) {
     sel_l[a] = 0.f;
     sel_j[a] = 0;
     if (a < k) {
-      float m = mine;
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-      unsigned long long who = __ballot(mine == m);
-      int j = __ffsll((long long)who) - 1;
-      sel_l[a] = m;
+      const int j = select_round(key, taken, lane, K);
+      sel_l[a] = __shfl(mine, j, 64);
       sel_j[a] = j;
-      if (a == 0) lmax = m;
-      if (lane == j) mine = -INFINITY;
+      if (a == 0) lmax = sel_l[a];
     }
   }
   if (lane == 0) {

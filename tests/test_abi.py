@@ -63,6 +63,29 @@ def test_workspace_bytes_monotone_and_covers_intermediates():
     L.cmoe_destroy(h)
 
 
+def test_workspace_for_t_max_serves_every_smaller_t():
+    # the weight-streaming path (up to 256 tokens) and the matrix-core path lay the workspace
+    # out differently; a buffer sized for T_max must still be large enough for any T <= T_max
+    L = cm.lib()
+    shapes = [dict(d=4096, d_ff=14336, G=8, K=8, r=32, top_k=2, q_group=128),
+              dict(d=768, d_ff=3072, G=2, K=4, r=8, top_k=2, q_group=32),
+              dict(d=8192, d_ff=128, G=64, K=2, r=4, top_k=2, q_group=128),
+              dict(d=128, d_ff=512, G=2, K=4, r=4, top_k=1, q_group=32)]
+    for kw in shapes:
+        rc, h = _create(**kw)
+        assert rc == B.OK
+        ts = [0, 1, 16, 64, 255, 256, 257, 258, 300, 511, 512, 513, 1000, 1024, 4096]
+        sizes = [L.cmoe_workspace_bytes(h, t) for t in ts]
+        for i in range(1, len(ts)):
+            assert sizes[i] >= sizes[i - 1], (kw, ts[i - 1], ts[i], sizes[i - 1], sizes[i])
+        for top_g in (1, 2):
+            m = [L.cmoe_workspace_bytes_multi(h, t, top_g) for t in ts]
+            for i in range(1, len(ts)):
+                assert m[i] >= m[i - 1], (kw, top_g, ts[i])
+            assert all(a >= b for a, b in zip(m, sizes))
+        L.cmoe_destroy(h)
+
+
 def test_calls_reject_bad_arguments_without_touching_the_gpu():
     rc, h = _create()
     L = cm.lib()

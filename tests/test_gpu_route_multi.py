@@ -84,6 +84,46 @@ def test_route_and_forward_multi(cfg, top_g, tau, scale):
     layer.close()
 
 
+def test_forward_multi_at_the_largest_configuration():
+    """cmoe_forward_multi at C3 size with two clusters per token (65536 virtual tokens through
+    the matrix-core kernels, operand rows gathered as vt / top_g): routing outputs bit-exact on
+    every well-separated token, the permutation of the virtual tokens in full, y on a sample of
+    tokens against the dense definition."""
+    import torch
+    import paper_2510_02345_amd as cm
+    cfg = ci.config(3)
+    top_g, tau, scale = 2, 0.7, True
+    w = ci.generate(cfg)
+    keep = _well_separated(w, cfg, top_g)
+    assert len(keep) >= 0.9 * cfg.T
+    x_np = np.ascontiguousarray(w["x"][keep])
+    T = len(keep)
+    print(f"C3 with top_g = 2: {T} of {cfg.T} tokens kept", flush=True)
+    cids, eidx, gate, _ = orc.route_multi(x_np, w["router_cluster"], w["router_expert"], cfg.K, cfg.k, top_g, tau,
+                                          scale, w["cluster_bias"])
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, T * top_g)
+    out = layer.forward_multi(_dev(x_np), top_g, tau, scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), cids)
+    assert np.array_equal(out["expert_idx"].cpu().numpy(), eidx)
+    assert np.allclose(out["gate"].cpu().numpy(), gate, rtol=1e-5, atol=1e-7)
+    offsets, perm, inv = orc.permute(cids.reshape(-1), cfg.G)
+    assert np.array_equal(out["offsets"].cpu().numpy(), offsets)
+    assert np.array_equal(out["perm"].cpu().numpy(), perm)
+    assert np.array_equal(out["inv_perm"].cpu().numpy(), inv)
+    rng = np.random.default_rng(9)
+    rows = np.sort(rng.choice(T, size=512, replace=False))
+    y_ref = orc.ffn_naive(w, x_np[rows], eidx[rows].reshape(len(rows), top_g * cfg.k),
+                          gate[rows].reshape(len(rows), top_g * cfg.k), cfg.K, cfg.q)
+    y = out["y"].cpu().numpy()
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    m = orc.error_metrics(y[rows], y_ref)
+    print(f"forward_multi C3 sampled {len(rows)} tokens: max/rms={m['max_over_rms']:.3e} mean_rel={m['mean_rel']:.3e}",
+          flush=True)
+    assert m["max_over_rms"] <= MAX_OVER_RMS and m["mean_rel"] <= MEAN_REL
+    layer.close()
+
+
 def test_top_g_one_equals_forward():
     import torch
     import paper_2510_02345_amd as cm

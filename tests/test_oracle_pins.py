@@ -775,3 +775,34 @@ def test_base_and_quantiser_meet_their_definitions_in_fp64():
     # the reconstruction w ~ scale * code is within half a step wherever no clipping took place
     inside = np.abs(ratio) <= 7.0
     assert np.all(np.abs(s[live][:, None] * c[live] - w64[live])[inside] <= 0.5 * np.broadcast_to(s[live][:, None], ratio.shape)[inside] * (1 + 1e-6))
+
+
+def test_route_nan_logits_rank_last_and_slots_stay_distinct():
+    # reading for non-finite inputs: NaN ranks below every number, lowest index among equals
+    G, K, k, d = 3, 4, 3, 8
+    rng = np.random.default_rng(77)
+    rc = rng.standard_normal((G, d)).astype(np.float16)
+    re = rng.standard_normal((G * K, d)).astype(np.float16)
+    x = rng.standard_normal((4, d)).astype(np.float16)
+    x[0, :] = np.float16(np.nan)                       # every logit of token 0 is NaN
+    with np.errstate(invalid="ignore"):
+        cid, eidx, gate, z, l = orc.route(x, rc, re, K, k)
+    assert cid[0] == 0 and eidx[0].tolist() == [0, 1, 2]
+    # one NaN router row: that expert is chosen only when nothing else is left
+    re2 = re.copy()
+    c1 = int(cid[1])
+    best = int(eidx[1, 0])
+    re2[best, 0] = np.float16(np.nan)                  # the former winner of token 1 now has a NaN logit
+    with np.errstate(invalid="ignore"):
+        cid2, eidx2, _, _, l2 = orc.route(x[1:2], rc, re2, K, k)
+    assert cid2[0] == c1 and best not in eidx2[0].tolist()
+    assert eidx2[0].tolist() == [e for e in eidx[1].tolist() if e != best] + [e for e in range(c1 * K, c1 * K + K)
+                                                                           if e not in eidx[1].tolist()][:1]
+    # k = K with one NaN: all K experts are named once, the NaN one last
+    with np.errstate(invalid="ignore"):
+        _, eidx3, _, _, _ = orc.route(x[1:2], rc, re2, K, K)
+    assert sorted(eidx3[0].tolist()) == list(range(c1 * K, c1 * K + K)) and eidx3[0, -1] == best
+    # the variants follow the same rule for clusters
+    with np.errstate(invalid="ignore"):
+        cids, e4, _, _ = orc.route_multi(x[:1], rc, re, K, k, top_g=2)
+    assert cids[0].tolist() == [0, 1] and e4[0].tolist() == [[0, 1, 2], [4, 5, 6]]
