@@ -125,6 +125,19 @@ int cmoe_permute(cmoe_handle *h, const int32_t *cluster_id, int32_t T, int32_t *
                  int32_t *inv_perm, int32_t *offsets, void *workspace, size_t workspace_bytes,
                  void *stream);
 
+/* cmoe_permute for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * outputs as cmoe_permute; the per-block histogram that cmoe_permute keeps in the workspace
+ * lives in a device array inside the library (256 KiB per GPU, held until the process ends),
+ * which limits the call to CMOE_PERMUTE_STATIC_MAX_TOKENS tokens: more returns
+ * CMOE_ERR_UNSUPPORTED before any HIP call.  The call allocates and frees nothing; the
+ * first call on a device looks up the array's address on that device.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race
+ * and must be serialised by the caller.  Nothing in the array is carried from call to call. */
+#define CMOE_PERMUTE_STATIC_MAX_TOKENS 1048576
+int cmoe_permute_static(cmoe_handle *h, const int32_t *cluster_id, int32_t T, int32_t *perm,
+                        int32_t *inv_perm, int32_t *offsets, void *stream);
+
 /* Expert computation with base reuse (Sec. 3.2), in cluster-sorted row order p
  * (token t = perm[p], cluster c, experts e_j, gates g_j):
  *   Hb = W1_base(c) x_t;  a_j = GELU(Hb + U1_{e_j}(V1_{e_j} x_t));  A = sum_j g_j a_j

@@ -16,7 +16,7 @@ _lib = None
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
-EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute",
+EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", "cmoe_permute", "cmoe_permute_static",
            "cmoe_ffn_forward", "cmoe_combine", "cmoe_forward", "cmoe_route_multi", "cmoe_workspace_bytes_multi",
            "cmoe_forward_multi", "cmoe_route_stats", "cmoe_compress_workspace_bytes", "cmoe_compress",
            "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_backward_workspace_bytes", "cmoe_backward",
@@ -74,6 +74,7 @@ def lib():
     L.cmoe_workspace_bytes.restype = sz
     L.cmoe_route.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp]
     L.cmoe_permute.argtypes = [vp, vp, i32, vp, vp, vp, vp, sz, vp]
+    L.cmoe_permute_static.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     L.cmoe_ffn_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.cmoe_combine.argtypes = [vp, C.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.cmoe_forward.argtypes = [vp, C.POINTER(Weights), vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -269,6 +270,18 @@ class Layer:
         offsets = self._empty((self.cfg.G + 1,), t.int32)
         self._check(lib().cmoe_permute(self._h, _ptr(cluster_id), T, _ptr(perm), _ptr(inv), _ptr(offsets),
                                        _ptr(self.ws), self.ws.numel(), self._stream()), "cmoe_permute")
+        return perm, inv, offsets
+
+    def permute_static(self, cluster_id, perm=None, inv=None, offsets=None):
+        """cmoe_permute_static: no workspace argument, no allocation inside the call when the
+        output tensors are passed in."""
+        t = self.torch
+        T = cluster_id.shape[0]
+        perm = perm if perm is not None else self._empty((T,), t.int32)
+        inv = inv if inv is not None else self._empty((T,), t.int32)
+        offsets = offsets if offsets is not None else self._empty((self.cfg.G + 1,), t.int32)
+        self._check(lib().cmoe_permute_static(self._h, _ptr(cluster_id), T, _ptr(perm), _ptr(inv), _ptr(offsets),
+                                              self._stream()), "cmoe_permute_static")
         return perm, inv, offsets
 
     def ffn_forward(self, x, perm, offsets, expert_idx, gate):

@@ -232,6 +232,17 @@ extern "C" int cmoe_permute(cmoe_handle* h, const int32_t* cluster_id, int32_t T
   return CMOE_OK;
 }
 
+extern "C" int cmoe_permute_static(cmoe_handle* h, const int32_t* cluster_id, int32_t T, int32_t* perm,
+                                   int32_t* inv_perm, int32_t* offsets, void* stream) {
+  if (!handle_ok(h) || T < 0) return CMOE_ERR_INVALID_ARG;
+  if (!ptr_ok(offsets)) return CMOE_ERR_INVALID_ARG;
+  if (T > 0 && (!ptr_ok(cluster_id) || !ptr_ok(perm) || !ptr_ok(inv_perm))) return CMOE_ERR_INVALID_ARG;
+  if (T > CMOE_PERMUTE_STATIC_MAX_TOKENS) return CMOE_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  CMOE_LAUNCH(TS_PERMUTE, launch_permute_static(h->dm, cluster_id, T, perm, inv_perm, offsets, st));
+  return CMOE_OK;
+}
+
 // y_fused != NULL: when the shapes allow it, the down-projection also applies the residual of
 // the second matrix and writes y in token order (y_base_sorted is then not produced);
 // *fused tells the caller whether that happened.

@@ -86,6 +86,8 @@ hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const h
                              int* expert_idx, float* gate, hipStream_t st);
 hipError_t launch_permute(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm, int* offsets,
                           int* blk_counts, hipStream_t st);
+hipError_t launch_permute_static(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm,
+                                 int* offsets, hipStream_t st);
 hipError_t launch_permute_bins(int bins, const int* keys, int T, int* perm, int* inv_perm, int* offsets,
                                int* blk_counts, hipStream_t st);
 hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* offsets, const int* expert_idx, int T,

@@ -1,5 +1,7 @@
 // Two-stage hierarchical router (Sec. 3.3, Eq. 9 and Eq. 10) and the stable
 // token-to-cluster permutation (the single-device part of group-level dispatch).
+#include <mutex>
+
 #include "cmoe_internal.h"
 
 namespace {
@@ -599,6 +601,48 @@ hipError_t launch_permute_bins(int bins, const int* cluster_id, int T, int* perm
   hipLaunchKernelGGL(permute_rank_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
                      blk_counts, perm, inv_perm);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- permutation without a workspace argument
+// The per-block histogram of the three-pass permutation lives in a file-scope device array
+// instead of the caller's workspace, for callers that cannot allocate device memory.  Every
+// GPU holds its own copy of the array at its own address; the host resolves that address
+// once per device and passes it to the kernels like any other buffer.
+static const int kStaticBlocks = CMOE_PERMUTE_STATIC_MAX_TOKENS / PERMUTE_BLOCK;
+static __device__ __align__(256) int scratch[(size_t)kStaticBlocks * 64];
+static const int kMaxDevices = 64;
+static int* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (resolved on the first call per device).
+static hipError_t scratch_address(int** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    int* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t launch_permute_static(const cmoe_dims& dm, const int* cluster_id, int T, int* perm, int* inv_perm,
+                                 int* offsets, hipStream_t st) {
+  int* blk_counts = nullptr;
+  // up to PERMUTE_BLOCK tokens run in one workgroup and need no histogram buffer
+  if (T > PERMUTE_BLOCK) {
+    hipError_t e = scratch_address(&blk_counts);
+    if (e != hipSuccess) return e;
+  }
+  // every entry the later passes read is written by the first pass of the same call: nothing
+  // has to start at zero, whatever an earlier call left behind
+  return launch_permute_bins(dm.G, cluster_id, T, perm, inv_perm, offsets, blk_counts, st);
 }
 
 hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
