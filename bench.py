@@ -80,13 +80,20 @@ def run_config(cfg, steps, warmup, want_stats=False):
     out = layer.forward_buffers(cfg.T)
     for _ in range(warmup):
         layer.forward(x, out)
+    # an event after every step (on the launch stream) gives the spread next to the mean
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         layer.forward(x, out)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    ms_median = per_step[len(per_step) // 2] if steps % 2 else 0.5 * (per_step[steps // 2 - 1] + per_step[steps // 2])
+    ms_min = per_step[0]
 
     # second pass over the same steps with per-kernel HIP events on the launch stream
     layer.timing_enable(True)
@@ -116,12 +123,11 @@ def run_config(cfg, steps, warmup, want_stats=False):
     multi_ms = None
     if want_stats:
         # routing variant: two clusters per token, temperature, cluster-probability scaling
-        om = layer.forward_multi(x, 2, 0.7, True)
+        om = layer.forward_multi(x, 2, 0.7, True)      # allocates the workspace and the outputs once
         torch.cuda.synchronize()
-        del om
         t0 = time.perf_counter()
         for _ in range(max(steps // 2, 3)):
-            om = layer.forward_multi(x, 2, 0.7, True)
+            layer.forward_multi(x, 2, 0.7, True, out=om)
         torch.cuda.synchronize()
         multi_ms = (time.perf_counter() - t0) / max(steps // 2, 3) * 1e3
         del om
@@ -149,7 +155,7 @@ def run_config(cfg, steps, warmup, want_stats=False):
     clusters_hit = int((np.diff(offs) > 0).sum())
     experts_hit = int(len(np.unique(eidx)))
     layer.close()
-    return dict(ms_per_step=ms_per_step, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
+    return dict(ms_per_step=ms_per_step, ms_median=ms_median, ms_min=ms_min, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
                 experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms, backward_ms=backward_ms, pack_ms=pack_ms)
 
 
@@ -235,7 +241,8 @@ def cpu_baseline(cfg, w, sample):
     orc.forward_naive(ws, x, cfg.K, cfg.k, cfg.q)
     dt = time.perf_counter() - t0
     return {"value": round(sample / dt, 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {sample} of {cfg.T} tokens of {cfg.name}, forward_naive (FP64, numpy/OpenBLAS), {dt:.1f} s"}
+            "sample": f"first {sample} of {cfg.T} tokens of {cfg.name}, forward_naive (FP64, numpy/OpenBLAS), {dt:.1f} s "
+                      f"of which a few seconds build the dense FP64 matrices of the experts hit, whatever the sample size"}
 
 
 def main():
@@ -249,7 +256,9 @@ def main():
     ap.add_argument("--no-compress", action="store_true", help="skip the compression-pipeline leg")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the routing-statistics and routing-variant legs (profiling runs of the layer alone)")
-    ap.add_argument("--cpu-sample", type=int, default=1024)
+    ap.add_argument("--cpu-sample", type=int, default=4096)
+    ap.add_argument("--no-calibration", action="store_true",
+                    help="skip the matrix-core calibration leg (sustained MFMA rate with no memory traffic)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one 256 MiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -287,6 +296,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(res["ms_per_step"], 4),
+        "ms_per_step_median": round(res["ms_median"], 4), "ms_per_step_min": round(res["ms_min"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} G={cfg.G} K={cfg.K} r={cfg.r} "
@@ -307,8 +317,8 @@ def main():
                                  "scale_by_cluster_prob": True,
                                  "tokens_per_s": round(cfg.T / (res["multi_ms"] * 1e-3), 1),
                                  "vs_two_single_cluster_steps": round(res["multi_ms"] / (2 * res["ms_per_step"]), 3),
-                                 "note": "cmoe_forward_multi, workspace allocated per call by the binding (inside "
-                                         "the timed region); 2 T virtual tokens through the same kernels"}
+                                 "note": "cmoe_forward_multi, workspace and outputs allocated before the timed "
+                                         "loop; 2 T virtual tokens through the same kernels"}
     if res["backward_ms"]:
         M = cfg.T * cfg.k
         flops = 5 * 2.0 * cfg.T * cfg.d * cfg.d_ff + 2.0 * M * cfg.r * (5 * cfg.d + 6 * cfg.d_ff)
@@ -319,6 +329,19 @@ def main():
                             "note": "cmoe_backward for the frozen selection of the step: five shared-base products "
                                     "of 2 T d d_ff flops (once per token) and eleven rank-r products per (token, "
                                     "expert) pair; all launches timed together; not part of ms_per_step"}
+    if not args.no_calibration:
+        import paper_2510_02345_amd as cm
+        tf, ghz = cm.calibrate_mfma()
+        rf = line["roofline"]
+        line["mfma_sustained"] = {
+            "value": round(tf, 1), "unit": "TFLOP/s", "shader_clock_GHz": round(ghz, 3),
+            "frac_of_peak": round(tf / PEAK_F16_TFLOPS, 4),
+            "dominant_kernel_vs_sustained": round(rf["achieved"] / tf, 4) if rf["bound"] == "mfma" else None,
+            "note": "cmoe_calibrate_mfma in this run: the grouped products' inner schedule (32 x 32 x 16 FP16 MFMAs, "
+                    "fragments of random mantissas read from LDS, two wavefront sets) with no global traffic and "
+                    "every matrix-core issue slot used on all 256 CUs; the rate is what the power management "
+                    "sustains, the ceiling of any FP16 product on this box. roofline.frac stays against the "
+                    "published 2.5 PFLOP/s"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
     del res
@@ -329,6 +352,7 @@ def main():
             "workload": f"{c4.name}: T={c4.T} d={c4.d} d_ff={c4.d_ff} G={c4.G} K={c4.K} r={c4.r} top_k={c4.k} q={c4.q}",
             "value": round(c4.T / (r4["ms_per_step"] * 1e-3), 1), "unit": "tokens/s",
             "ms_per_step": round(r4["ms_per_step"], 4),
+            "ms_per_step_median": round(r4["ms_median"], 4), "ms_per_step_min": round(r4["ms_min"], 4),
             "clusters_hit": r4["clusters_hit"], "experts_hit": r4["experts_hit"],
             "roofline": roofline(c4, r4, "hbm", traffic_table)}
     if not args.no_compress:

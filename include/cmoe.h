@@ -1,6 +1,7 @@
 /*
- * cmoe.h -- C ABI of the clustered, compressed Mixture-of-Experts FFN layer (forward)
- * for AMD MI355X (gfx950).
+ * cmoe.h -- C ABI of the clustered, compressed Mixture-of-Experts FFN layer for AMD MI355X
+ * (gfx950): forward pass, routing variants and statistics, construction of the stored form
+ * from dense experts, and the backward pass.
  *
  * The layer (notation of the paper, arXiv 2510.02345):
  *   - E = G*K experts are organised in G clusters of uniform size K (Sec. 3.1).
@@ -261,7 +262,7 @@ int cmoe_reconstruction_error(const cmoe_compress_config *cfg, const cmoe_f16 *W
                               void *stream);
 
 /* ---- Backward pass for a frozen selection (training step of Sec. 3.5) ----
- * Gradients of L = sum(dy * y), y = the layer output of Sec. 3.2 / Eq. 8 for the given
+ * Gradients of L = sum(dy * y), y = the layer output of Sec. 3.2 / Eq. 7 for the given
  * expert_idx [T][top_k] and gate [T][top_k] (the softmax of Eq. 10 over the selected
  * logits, as cmoe_route returns them).  The selection itself (cluster and expert argmax)
  * is piecewise constant and carries no gradient; the cluster router receives none.
@@ -305,6 +306,17 @@ const char *cmoe_status_string(int status);
 int cmoe_timing_enable(cmoe_handle *h, int on);
 int cmoe_timing_read(cmoe_handle *h, double *ms_sum, int32_t *count, int32_t n_max);
 const char *cmoe_timing_name(int32_t slot);
+
+/* Benchmark calibration: n_workgroups workgroups (one per compute unit: 256) run iters
+ * iterations of the grouped products' inner schedule - 32 FP16 matrix-core instructions
+ * (32 x 32 x 16) per iteration and SIMD on operands of random mantissas read from LDS - with no
+ * global memory traffic, so that every matrix-core issue slot is used.  FLOPs = n_workgroups *
+ * 8 * iters * 16 * 32768; the rate over the call's duration is what the power management lets
+ * the matrix cores sustain on this machine.  ticks [2] u64 (device, zeroed by the caller): sums
+ * over the workgroups of shader-clock cycles and of constant-rate (100 MHz) ticks spent in the
+ * loop; sink [n_workgroups * 512] f32 (device) receives the accumulators.  Not for production
+ * use. */
+int cmoe_calibrate_mfma(int32_t n_workgroups, int32_t iters, uint64_t *ticks, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,7 @@ EXPORTS = ("cmoe_create", "cmoe_destroy", "cmoe_workspace_bytes", "cmoe_route", 
            "cmoe_quantize_int4", "cmoe_reconstruction_error", "cmoe_backward_workspace_bytes", "cmoe_backward",
            "cmoe_packed_bytes", "cmoe_pack_weights",
            "cmoe_last_hip_error", "cmoe_status_string",
-           "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name")
+           "cmoe_timing_enable", "cmoe_timing_read", "cmoe_timing_name", "cmoe_calibrate_mfma")
 
 
 class CmoeError(RuntimeError):
@@ -102,6 +102,7 @@ def lib():
     L.cmoe_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32), i32]
     L.cmoe_timing_name.argtypes = [i32]
     L.cmoe_timing_name.restype = C.c_char_p
+    L.cmoe_calibrate_mfma.argtypes = [i32, i32, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
                         "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi",
@@ -177,6 +178,27 @@ def reconstruction_error(W, base, u_q, u_s, v_q, v_s, G: int, K: int, r: int, q:
          "cmoe_reconstruction_error")
     torch.cuda.current_stream().synchronize()   # the workspace is freed on return
     return err
+
+
+def calibrate_mfma(n_workgroups: int = 256, iters: int = 40000, device="cuda:0"):
+    """cmoe_calibrate_mfma between two events: (TFLOP/s sustained by the matrix cores with every
+    issue slot used and no memory traffic, shader clock in GHz during the loop)."""
+    import torch
+    ticks = torch.zeros((2,), dtype=torch.int64, device=device)
+    sink = torch.empty((n_workgroups * 512,), dtype=torch.float32, device=device)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    _chk(lib().cmoe_calibrate_mfma(n_workgroups, max(iters // 20, 1), _ptr(ticks), _ptr(sink), _cur_stream()),
+         "cmoe_calibrate_mfma")        # warm-up
+    torch.cuda.synchronize()
+    ticks.zero_()
+    e0.record()
+    _chk(lib().cmoe_calibrate_mfma(n_workgroups, iters, _ptr(ticks), _ptr(sink), _cur_stream()), "cmoe_calibrate_mfma")
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    t = ticks.cpu().tolist()
+    flops = n_workgroups * 8.0 * iters * 16 * 32768
+    return flops / (ms * 1e-3) / 1e12, (t[0] / t[1] * 0.1 if t[1] else 0.0)
 
 
 def _ptr(t) -> Optional[int]:
@@ -315,8 +337,9 @@ class Layer:
                                            _ptr(gate), self._stream()), "cmoe_route_multi")
         return cid, eidx, gate
 
-    def forward_multi(self, x, top_g=1, temperature=1.0, scale_by_cluster_prob=False):
-        """cmoe_forward_multi; allocates its own workspace.  Returns a dict like forward(), with the
+    def forward_multi(self, x, top_g=1, temperature=1.0, scale_by_cluster_prob=False, out=None):
+        """cmoe_forward_multi; allocates its own workspace and outputs unless `out` (the dict an
+        earlier call returned for the same T and top_g) is passed for reuse.  Returns a dict like forward(), with the
         routing outputs per (token, selected cluster) and perm / inv_perm over the virtual tokens."""
         t = self.torch
         T, k = x.shape[0], self.cfg.top_k
@@ -324,11 +347,15 @@ class Layer:
         nbytes = lib().cmoe_workspace_bytes_multi(self._h, T, top_g)
         if nbytes == 0:
             raise CmoeError(-1, "cmoe_workspace_bytes_multi")
-        ws = self._empty((nbytes,), t.uint8)
-        o = dict(y=self._empty((T, self.cfg.d), t.float16), cluster_id=self._empty((T, top_g), t.int32),
-                 expert_idx=self._empty((T, top_g, k), t.int32), gate=self._empty((T, top_g, k), t.float32),
-                 perm=self._empty((T * top_g,), t.int32), inv_perm=self._empty((T * top_g,), t.int32),
-                 offsets=self._empty((self.cfg.G + 1,), t.int32))
+        if out is not None:                      # buffers of an earlier call of the same shape
+            o, ws = out, out["_workspace"]
+            assert ws.numel() >= nbytes and o["y"].shape[0] == T and o["cluster_id"].shape[1] == top_g
+        else:
+            ws = self._empty((nbytes,), t.uint8)
+            o = dict(y=self._empty((T, self.cfg.d), t.float16), cluster_id=self._empty((T, top_g), t.int32),
+                     expert_idx=self._empty((T, top_g, k), t.int32), gate=self._empty((T, top_g, k), t.float32),
+                     perm=self._empty((T * top_g,), t.int32), inv_perm=self._empty((T * top_g,), t.int32),
+                     offsets=self._empty((self.cfg.G + 1,), t.int32))
         self._check(lib().cmoe_forward_multi(self._h, C.byref(self.w), C.byref(opt), _ptr(x), T, _ptr(o["y"]),
                                              _ptr(o["cluster_id"]), _ptr(o["expert_idx"]), _ptr(o["gate"]),
                                              _ptr(o["perm"]), _ptr(o["inv_perm"]), _ptr(o["offsets"]), _ptr(ws),

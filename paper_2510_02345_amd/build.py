@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcmoe.so")
 SOURCES = ("cmoe_api.hip", "cmoe_route.hip", "cmoe_dequant.hip", "cmoe_gemm.hip", "cmoe_skinny.hip",
-           "cmoe_stats.hip", "cmoe_compress.hip", "cmoe_backward.hip")
+           "cmoe_stats.hip", "cmoe_compress.hip", "cmoe_backward.hip", "cmoe_calibrate.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

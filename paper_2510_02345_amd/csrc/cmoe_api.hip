@@ -317,7 +317,7 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, gate, u1t, v2p,
                                      t1ext, a, spart, st));
-  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st, true));
+  CMOE_LAUNCH(TS_SREDUCE, launch_sreduce(dm, T, rperm, spart, (dm.d_ff + G1_BN - 1) / G1_BN, s_down, st));
   if (fuse) {
     CMOE_LAUNCH(TS_GEMM2, launch_gemm2_combine(dm, *w, a, T, offsets, rperm, u2t, s_down, expert_idx, gate,
                                                (half_t*)y_fused, st));

@@ -1,6 +1,6 @@
 // Backward pass of the layer for a frozen selection (the training step of Sec. 3.5): the
 // gradients of L = sum(dy * y) with respect to x, the expert-router rows, the shared bases
-// and the dequantised low-rank factors, for y of Sec. 3.2 / Eq. 8 with the gates of Eq. 10.
+// and the dequantised low-rank factors, for y of Sec. 3.2 / Eq. 7 with the gates of Eq. 10.
 //
 // The base reuse of Sec. 3.2 carries over to every product of the chain rule.  With
 // W_e = B_c + U_e V_e, tokens sorted by cluster and (token, expert) pairs m = t k + j sorted

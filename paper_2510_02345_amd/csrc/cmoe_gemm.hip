@@ -672,7 +672,7 @@ struct EpiFusedUp {
   const int* expert_idx;
   const float* gate;
   half_t* A;          // [T][d_ff]
-  half_t* spart;      // [n_tiles][T][k][r] partials of V2 a over the tile's 256 rows of d_ff, FP16 (summed in FP32)
+  float* spart;       // [n_tiles][T][k][r] partials of V2 a over the tile's 256 rows of d_ff, FP32
   int T, k, K, KRp, d_ff;
   using FU = FusedUp<R, KMAX>;
 
@@ -995,10 +995,10 @@ hipError_t launch_gemm1_rk(const cmoe_dims& dm, const GemmArgs& g, int T, const 
                            float* spart, hipStream_t st) {
   using TL = TileUp;
   if (dm.KRp <= 128) {
-    EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, (half_t*)spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+    EpiFusedUp<R, KMAX, true> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
     return launch_gemm<TL>(g, T, epi, st);
   }
-  EpiFusedUp<R, KMAX, false> epi{u1t, v2p, t1, perm, expert_idx, gate, a, (half_t*)spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
+  EpiFusedUp<R, KMAX, false> epi{u1t, v2p, t1, perm, expert_idx, gate, a, spart, T, dm.k, dm.K, dm.KRp, dm.d_ff};
   return launch_gemm<TL>(g, T, epi, st);
 }
 
@@ -1052,21 +1052,14 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
 }
 
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
-                          float* s_down, hipStream_t st, bool half_in) {
+                          float* s_down, hipStream_t st) {
   int kr = dm.k * dm.r;
   size_t n = (size_t)T * kr;
   const dim3 grid((unsigned)((n + 63) / 64));
-  if (half_in) {   // the fused up-projection leaves FP16 partials in the same buffer
-    const half_t* sp = (const half_t*)spart;
-    if (n_parts > 128)
-      hipLaunchKernelGGL((sreduce_kernel<16, half_t>), grid, dim3(1024), 0, st, sp, perm, T, kr, n_parts, s_down);
-    else
-      hipLaunchKernelGGL((sreduce_kernel<4, half_t>), grid, dim3(256), 0, st, sp, perm, T, kr, n_parts, s_down);
-  } else if (n_parts > 128) {
+  if (n_parts > 128)
     hipLaunchKernelGGL((sreduce_kernel<16, float>), grid, dim3(1024), 0, st, spart, perm, T, kr, n_parts, s_down);
-  } else {
+  else
     hipLaunchKernelGGL((sreduce_kernel<4, float>), grid, dim3(256), 0, st, spart, perm, T, kr, n_parts, s_down);
-  }
   return hipGetLastError();
 }
 

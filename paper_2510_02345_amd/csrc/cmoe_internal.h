@@ -66,7 +66,7 @@ struct cmoe_ws_layout {
   size_t ures;        // f32 [T][d]            residual-down term, sorted rows (weight-streaming path only)
   size_t stats_part;  // f32 [slots][K][d]     routing statistics: per-slot sums of x per expert
   size_t stats_cnt;   // i32 [slots][K]        and their row counts
-  size_t spart;       // f32 [n_parts][T][k][r] partial V2 a per row tile of d_ff (f16 on the matrix-core path)
+  size_t spart;       // f32 [n_parts][T][k][r] partial V2 a per row tile of d_ff
   size_t yb;          // f16 [T][d]            cmoe_forward only: y_base_sorted
   size_t sdown;       // f32 [T][k][r]         cmoe_forward only: s_down
   size_t total;
@@ -102,7 +102,7 @@ hipError_t launch_gemm1(const cmoe_dims& dm, const cmoe_weights& w, const half_t
                         const int* offsets, const int* expert_idx, const float* gate, const half_t* u1t,
                         const half_t* v2p, const half_t* t1ext, half_t* a, float* spart, hipStream_t st);
 hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const float* spart, int n_parts,
-                          float* s_down, hipStream_t st, bool half_in = false);
+                          float* s_down, hipStream_t st);
 hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int x_div, int T, const int* perm,
                             const int* offsets, const int* expert_idx, half_t* t1, half_t* hb, hipStream_t st);
 hipError_t launch_route_multi(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,

@@ -38,6 +38,42 @@ def test_quantiser_bit_exact(rows, L, q):
     want_codes, want_scales = orc.quantize_int4_f32(w, q)
     assert np.array_equal(scales.cpu().numpy().view(np.uint16), want_scales.view(np.uint16))
     assert np.array_equal(codes.cpu().numpy(), want_codes)
+    _check_quantiser_definition(w, q, codes.cpu().numpy(), scales.cpu().numpy())
+
+
+def _check_quantiser_definition(w, q, codes, scales):
+    """The quantiser of Sec. 3.4 written out in FP64, with no reference to the order or precision
+    of the kernel's steps: scale = the FP16 value nearest to absmax / 7 (either neighbour where
+    the quotient sits within FP32 rounding of the midpoint), code = the integer nearest to
+    w / scale clipped to [-7, 7] (either neighbour within FP32 rounding of a tie), zeros where the
+    scale is zero."""
+    rows, L = w.shape
+    w64 = w.astype(np.float64).reshape(rows, L // q, q)
+    quot = np.abs(w64).max(axis=-1) / 7.0
+    s = scales.astype(np.float64)
+    near = quot.astype(np.float16).astype(np.float64)
+    other = np.where(near <= quot, np.nextafter(quot.astype(np.float16), np.float16(np.inf)),
+                     np.nextafter(quot.astype(np.float16), np.float16(-np.inf))).astype(np.float64)
+    tie = np.abs(np.abs(quot - near) - np.abs(quot - other)) <= 2.0 ** -22 * np.abs(quot)
+    assert np.all((s == near) | (tie & (s == other)))
+    c = orc.unpack_int4(codes).astype(np.float64).reshape(rows, L // q, q)
+    live = s > 0
+    assert np.all(c[~live] == 0) and np.all(np.abs(c) <= 7)
+    ratio = np.clip(w64[live] / s[live][:, None], -7.0, 7.0)
+    assert np.all(np.abs(c[live] - ratio) <= 0.5 + 2.0 ** -20 * (1.0 + np.abs(ratio)))
+
+
+def _check_base_definition(W, G, K, base):
+    """Eq. 6 in FP64: the stored base is the FP16 value nearest to the exact mean of the cluster's
+    experts; the other FP16 neighbour only where the mean sits within FP32 rounding of the midpoint."""
+    exact = W.astype(np.float64).reshape((G, K) + W.shape[1:]).sum(axis=1) / K
+    b = base.astype(np.float64)
+    near = exact.astype(np.float16).astype(np.float64)
+    other = np.where(near <= exact, np.nextafter(exact.astype(np.float16), np.float16(np.inf)),
+                     np.nextafter(exact.astype(np.float16), np.float16(-np.inf))).astype(np.float64)
+    tie = np.abs(np.abs(exact - near) - np.abs(exact - other)) <= 2.0 ** -21 * np.abs(exact) + 1e-30
+    assert np.all((b == near) | (tie & (b == other)))
+    assert np.mean(b == near) > 0.999
 
 
 def test_reconstruction_error_of_a_given_stored_form():
@@ -77,23 +113,41 @@ def test_compress_against_truncated_svd(case):
     _sync()
     base = orc.base_mean(W, G, K)
     assert np.array_equal(o["base"].cpu().numpy().view(np.uint16), base.view(np.uint16))
+    _check_base_definition(W, G, K, o["base"].cpu().numpy())
     rep = o["report"].cpu().numpy()
     uq, us = o["u_q"].cpu().numpy(), o["u_s"].cpu().numpy()
     vq, vs = o["v_q"].cpu().numpy(), o["v_s"].cpu().numpy()
     for e in range(G * K):
         delta = orc.residual(W[e], base[e // K])
-        _, _, opt, _ = orc.truncated_svd_factors(delta, r)
+        U_svd, V_svd, opt, _ = orc.truncated_svd_factors(delta, r)
         wn = np.linalg.norm(W[e].astype(np.float64))
         opt_rel, floor = opt / wn, 2.0 ** -10 * np.linalg.norm(delta) / wn
-        print(f"  e{e}: rank-{r} error {rep[e, 1]:.5f} (optimum {opt_rel:.5f}), stored {rep[e, 0]:.5f}", flush=True)
+        # what the layer would compute with: the returned codes and scales, dequantised and
+        # measured by the oracle, not by the library
+        U = orc.dequant_int4(uq[e], us[e], q).T          # [out][r]
+        V = orc.dequant_int4(vq[e], vs[e], q)            # [r][in]
+        stored = orc.reconstruction_error(W[e], base[e // K], U, V)
+        # the yardstick for the stored form: the truncated SVD's own factors through the same
+        # INT4 format (rank-major rows, FP16 scale per q codes), quantised by the oracle
+        Uq = orc.dequant_int4(*orc.quantize_int4_f32(U_svd.T.astype(np.float32), q), q).T
+        Vq = orc.dequant_int4(*orc.quantize_int4_f32(V_svd.astype(np.float32), q), q)
+        svd_stored = orc.reconstruction_error(W[e], base[e // K], Uq, Vq)
+        # the split of the singular values between the factors: all on U (above), or all on V
+        # as the library does; the better of the two is the yardstick
+        sv = np.linalg.norm(U_svd, axis=0)
+        sv = np.where(sv > 0, sv, 1.0)
+        Uq2 = orc.dequant_int4(*orc.quantize_int4_f32((U_svd / sv).T.astype(np.float32), q), q).T
+        Vq2 = orc.dequant_int4(*orc.quantize_int4_f32((V_svd * sv[:, None]).astype(np.float32), q), q)
+        svd_stored = min(svd_stored, orc.reconstruction_error(W[e], base[e // K], Uq2, Vq2))
+        print(f"  e{e}: rank-{r} error {rep[e, 1]:.5f} (optimum {opt_rel:.5f}); stored form {stored:.5f} "
+              f"(library reports {rep[e, 0]:.5f}; INT4 truncated SVD {svd_stored:.5f})", flush=True)
         assert rep[e, 1] <= opt_rel * 1.02 + floor
         assert rep[e, 1] >= opt_rel * 0.995 - floor
         assert rep[e, 2] == pytest.approx(orc.cosine_to_base(delta, base[e // K]), abs=1e-4)
         assert rep[e, 3] == 0.0
-        # the stored form: the quantised factors cannot beat the unquantised ones by more than
-        # rounding, and lose at most the INT4 step (half a step per element of both factors)
-        assert rep[e, 0] >= rep[e, 1] * 0.98 - floor
-        assert rep[e, 0] <= rep[e, 1] + 0.35 * np.linalg.norm(delta) / wn + floor
+        assert rep[e, 0] == pytest.approx(stored, rel=1e-3, abs=1e-6)      # the report is the error of the output
+        assert stored <= 1.1 * svd_stored + floor
+        assert stored >= opt_rel * 0.995 - floor                          # nothing of rank r beats the optimum
     # the error the library reports for its own output is the error of that output
     again = cm.reconstruction_error(_dev(W), _dev(base), o["u_q"], o["u_s"], o["v_q"], o["v_s"], G, K, r, q)
     _sync()
