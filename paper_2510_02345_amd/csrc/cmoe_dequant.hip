@@ -152,7 +152,7 @@ hipError_t launch_dequant_ffn(const cmoe_dims& dm, const cmoe_weights& w, const 
   DequantJobs js{};
   unsigned total = 0;
   add_job(js, total, dm, w.u1_q, w.u1_s, u1t, dm.d_ff, 2);
-  add_job(js, total, dm, w.v2_q, w.v2_s, v2p, dm.d_ff, 1);
+  add_job(js, total, dm, w.v2_q, w.v2_s, v2p, dm.d_ff, 0);
   add_job(js, total, dm, w.v1_q, w.v1_s, v1cat, dm.d, 0);
   if (u2t != nullptr) add_job(js, total, dm, w.u2_q, w.u2_s, u2t, dm.d, 2);
   hipLaunchKernelGGL(dequant_kernel, dim3(total), dim3(256), 0, st, js, dm.q, dm.K, dm.r, dm.KRp, dm.G, offsets);

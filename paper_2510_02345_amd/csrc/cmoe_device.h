@@ -9,20 +9,20 @@ __device__ __forceinline__ float16v mfma16(half8 a, half8 b, float16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
-// GELU(u) = u * Phi(u) in the erf form, Phi(u) = 1/2 + erf(u / sqrt 2) / 2.  On |u| <= 4
-// Phi(u) - 1/2 = u P(u^2) with an eight-coefficient minimax polynomial (absolute error
-// of Phi below 5.5e-5 over the reals once u is clamped to [-4, 4], far below the FP16
-// rounding of the result); eleven full-rate FP32 operations per element.
+// GELU(u) = u * Phi(u) in the erf form, Phi(u) = 1/2 + erf(u / sqrt 2) / 2.  On |u| <= 3.75
+// Phi(u) - 1/2 = u P(u^2) with a seven-coefficient minimax polynomial, u clamped to that
+// range beyond it: the absolute error of GELU stays below 2.7e-4 for |u| <= 6 (4e-5 RMS
+// under a unit Gaussian), below the FP16 rounding of the result; ten full-rate FP32
+// operations per element.
 __device__ __forceinline__ float gelu_erf(float u) {
-  const float uc = fminf(fmaxf(u, -4.0f), 4.0f);
+  const float uc = __builtin_amdgcn_fmed3f(u, -3.75f, 3.75f);
   const float t = uc * uc;
-  float p = fmaf(t, -1.580786058e-09f, 1.217110963e-07f);
-  p = fmaf(t, p, -4.100866136e-06f);
-  p = fmaf(t, p, 8.066739247e-05f);
-  p = fmaf(t, p, -1.048204373e-03f);
-  p = fmaf(t, p, 9.664873593e-03f);
-  p = fmaf(t, p, -6.617537886e-02f);
-  p = fmaf(t, p, 3.988475204e-01f);
+  float p = fmaf(t, 3.878059656e-08f, -2.362032659e-06f);
+  p = fmaf(t, p, 6.212595828e-05f);
+  p = fmaf(t, p, -9.425636946e-04f);
+  p = fmaf(t, p, 9.357058592e-03f);
+  p = fmaf(t, p, -6.578237312e-02f);
+  p = fmaf(t, p, 3.987038812e-01f);
   return u * fmaf(uc, p, 0.5f);
 }
 
@@ -36,35 +36,64 @@ __device__ __forceinline__ half4 to_half4(const float16v& a, int qd) {
 }
 
 
-// The per-(token, selected expert) part of the fused up-projection (Sec. 3.2), on one
-// 32x32 accumulator block hb = (W1_base x)^T: rows n of d_ff, columns = tokens, so a lane
-// owns one token (column lane % 32) and 16 rows.
+// ---------------------------------------------------------------- 16 x 16 x 32 blocks
+// The grouped products run on v_mfma_f32_16x16x32_f16: D (16 rows x 16 tokens, FP32) +=
+// A (16 weight rows x 32 contraction elements) * B (32 x 16 tokens).  Lane l supplies row
+// (or token) l % 16 and the eight contraction elements 8q .. 8q + 7, q = l / 16, and holds of
+// D the token l % 16 and the rows 4q .. 4q + 3.  Measured on this part, the instruction
+// sustains about 14 % more flops than the 32 x 32 x 16 form at the same board power (it moves
+// half the accumulator bytes per flop), and board power is what limits the products.
+//
+// Weight rows are taken in "pair blocks" of 32 consecutive rows = two MFMA blocks.  Row i of
+// block hh (0 or 1) of a pair block is the weight row 8 (i / 4) + 4 hh + i % 4 of the pair
+// block, so that a lane's 4 + 4 accumulators of the two blocks are the EIGHT CONSECUTIVE rows
+// 8q .. 8q + 7: a lane stores 16 contiguous bytes of FP16 output per token, four lanes a
+// token's 64-byte line, and an accumulator pair is a ready-made B operand (contraction
+// positions in natural order) for a further product.
+__device__ __forceinline__ float4v mfma32(half8 a, half8 b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Weight row (offset inside its 32-row pair block kept in the upper bits) held by tile row rho
+// of an LDS operand tile whose rows are stored in MFMA order: rho = 32 P + 16 hh + i.
+__device__ __forceinline__ int pi_row(int rho) {
+  return (rho & ~31) | ((rho & 12) << 1) | ((rho & 16) >> 2) | (rho & 3);
+}
+
+__device__ __forceinline__ half8 pack_half8(const float4v& lo, const float4v& hi) {
+  half8 o;
+  o[0] = (half_t)lo[0]; o[1] = (half_t)lo[1]; o[2] = (half_t)lo[2]; o[3] = (half_t)lo[3];
+  o[4] = (half_t)hi[0]; o[5] = (half_t)hi[1]; o[6] = (half_t)hi[2]; o[7] = (half_t)hi[3];
+  return o;
+}
+
+// The per-(token, selected expert) part of the fused up-projection (Sec. 3.2) on one pair
+// block of the accumulators hb = (W1_base x)^T: 32 rows n of d_ff x 16 tokens; a lane owns
+// one token (l % 16) and the eight rows 8q .. 8q + 7.
 //   h_j = hb + U1cat^T t1ext_j   t1ext_j = the token's t1_j at the rank rows of expert
 //                                e_j, zero elsewhere; contraction over the cluster's
-//                                K*r rank rows in chunks of 16, chunks no token of the
+//                                K*r rank rows in chunks of 32, chunks no token of the
 //                                block needs are skipped
 //   a_j = GELU(h_j),  o = sum_j g_j a_j
-//   s_j += V2 a_j                the a_j block is fed back as B operand (contraction over
-//                                the block's 32 rows n); the product runs over "passes"
-//                                of 32 rank rows (32/r experts), a lane contributes to a
-//                                pass only if its expert lies in it, so afterwards row
-//                                (e_j % (32/r))*r + rho of the accumulator is s_j[rho]
+//   s_j += V2 a_j                the a_j pair block is fed back as B operand (contraction
+//                                over its 32 rows n); the product runs over "passes" of
+//                                16 rank rows, a lane contributes to a pass only if its
+//                                expert's rows lie in it
 template <int R, int KMAX>
 struct FusedUp {
-  static constexpr int EPB = 32 / R;  // experts per 32 rank rows
-  static constexpr int NF = (R == 32) ? 2 : 1;
+  static constexpr int NSP = (R == 32) ? 2 : 1;  // 16-row passes per expert
 
   struct Tok {
-    int e[KMAX];          // selected experts, local to the cluster
-    float g[KMAX];        // gates (0 for a padding column)
-    half8 f[KMAX][NF];    // this lane's slice of t1_j
-    int p;                // sorted row
+    int e[KMAX];      // selected experts, local to the cluster
+    float g[KMAX];    // gates (0 for a padding column)
+    half8 f[KMAX];    // this lane's slice of t1_j (see t1_frag)
+    int p;            // sorted row
     bool valid;
   };
 
   __device__ static __forceinline__ void load_tok(Tok& t, int p, int m_end, int c, int K, int k, const int* perm,
                                                   const int* expert_idx, const float* gate, const half_t* t1,
-                                                  int h) {
+                                                  int q) {
     t.p = p;
     t.valid = p < m_end;
     const int pc = t.valid ? p : m_end - 1;
@@ -73,105 +102,118 @@ struct FusedUp {
     for (int j = 0; j < KMAX; ++j) {
       t.e[j] = 0;
       t.g[j] = 0.f;
-#pragma unroll
-      for (int i = 0; i < NF; ++i) t.f[j][i] = half8{0, 0, 0, 0, 0, 0, 0, 0};
+      t.f[j] = half8{0, 0, 0, 0, 0, 0, 0, 0};
       if (j < k) {
         t.e[j] = min(max(expert_idx[(size_t)tok * k + j] - c * K, 0), K - 1);
         t.g[j] = t.valid ? gate[(size_t)tok * k + j] : 0.f;
         const half_t* tr = t1 + ((size_t)pc * k + j) * R;
         if (R == 32) {
-          t.f[j][0] = *(const half8*)(tr + 8 * h);
-          t.f[j][NF - 1] = *(const half8*)(tr + 16 + 8 * h);
+          t.f[j] = *(const half8*)(tr + 8 * q);
         } else if (R == 16) {
-          t.f[j][0] = *(const half8*)(tr + 8 * h);
+          t.f[j] = *(const half8*)(tr + 8 * (q & 1));
         } else if (R == 8) {
-          t.f[j][0] = *(const half8*)(tr);
+          t.f[j] = *(const half8*)(tr);
         } else {
-          half4 q4 = *(const half4*)(tr);
-          t.f[j][0][0] = q4[0]; t.f[j][0][1] = q4[1]; t.f[j][0][2] = q4[2]; t.f[j][0][3] = q4[3];
+          const half4 q4 = *(const half4*)(tr);
+          t.f[j][0] = q4[0]; t.f[j][1] = q4[1]; t.f[j][2] = q4[2]; t.f[j][3] = q4[3];
         }
       }
     }
   }
 
-  __device__ static __forceinline__ bool chunk_has(int e, int kc) {
-    return R == 32 ? (e == (kc >> 1)) : R == 16 ? (e == kc) : R == 8 ? ((e >> 1) == kc) : ((e >> 2) == kc);
-  }
-  // B operand of chunk kc for a lane whose token selected expert e with t1 fragments f
-  __device__ static __forceinline__ half8 t1_frag(int e, int kc, int h, const half8 (&f)[NF]) {
+  // chunk of 32 rank rows that holds expert e
+  __device__ static __forceinline__ int chunk_of(int e) { return (e * R) >> 5; }
+  // B operand of chunk c for a lane (contraction elements 32 c + 8 q ..) whose token selected
+  // expert e and keeps the slice f of its t1
+  __device__ static __forceinline__ half8 t1_frag(int e, int c, int q, const half8& f) {
     const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (R == 32) return (e == (kc >> 1)) ? ((kc & 1) ? f[NF - 1] : f[0]) : z;
-    if (R == 16) return (e == kc) ? f[0] : z;
-    if (R == 8) return (e == 2 * kc + h) ? f[0] : z;
-    half8 o = z;  // R == 4: slots 0..3 are expert 4kc+2h, slots 4..7 expert 4kc+2h+1
-    if (e == 4 * kc + 2 * h) {
-      o[0] = f[0][0]; o[1] = f[0][1]; o[2] = f[0][2]; o[3] = f[0][3];
-    } else if (e == 4 * kc + 2 * h + 1) {
-      o[4] = f[0][0]; o[5] = f[0][1]; o[6] = f[0][2]; o[7] = f[0][3];
+    if (R == 32) return (e == c) ? f : z;
+    if (R == 16) return (e == 2 * c + (q >> 1)) ? f : z;
+    if (R == 8) return (e == 4 * c + q) ? f : z;
+    half8 o = z;  // R == 4: elements 0..3 belong to expert 8c + 2q, elements 4..7 to expert 8c + 2q + 1
+    if (e == 8 * c + 2 * q) {
+      o[0] = f[0]; o[1] = f[1]; o[2] = f[2]; o[3] = f[3];
+    } else if (e == 8 * c + 2 * q + 1) {
+      o[4] = f[0]; o[5] = f[1]; o[6] = f[2]; o[7] = f[3];
     }
     return o;
   }
 
-  // uf(kc): A operand of U1cat^T for rank chunk kc (8 consecutive kk at row n = lane % 32);
-  // vf(q, s): A operand of V2 for pass q, rows n 16 s .. 16 s + 15 of the block in the
-  // lane order of the accumulator.
-  template <class UF, class VF>
-  __device__ static __forceinline__ void block(const float16v& hb, const Tok& t, int k, int n_chunks, int n_pass,
-                                               int h, UF uf, VF vf, float16v& o, float16v (&sacc)[KMAX]) {
+  // Chunks of 32 rank rows and passes of 16 rank rows that at least one valid token of the
+  // 16-token block needs for its j-th expert (wavefront-uniform bit masks, taken once per
+  // token block).
+  struct Need {
+    unsigned chunks[KMAX], passes[KMAX];
+  };
+  __device__ static __forceinline__ void need_of(const Tok& t, int k, int n_chunks, int n_pass, Need& nd) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[v] = 0.f;
+    for (int j = 0; j < KMAX; ++j) {
+      nd.chunks[j] = 0u;
+      nd.passes[j] = 0u;
+      if (j >= k) continue;
+      for (int c = 0; c < n_chunks; ++c)
+        if (__ballot(t.valid && chunk_of(t.e[j]) == c) != 0ull) nd.chunks[j] |= 1u << c;
+      for (int pp = 0; pp < n_pass; ++pp)
+        if (__ballot(t.valid && (pp & ~(NSP - 1)) == ((t.e[j] * R) >> 4)) != 0ull) nd.passes[j] |= 1u << pp;
+    }
+  }
+
+  // uf(c, hh): A operand of U1cat^T for rank chunk c and block hh of the pair block;
+  // vf(pp): A operand of V2 for pass pp (rank rows 16 pp + l % 16, the pair block's rows
+  // 8q .. 8q + 7 as contraction elements).
+  template <class UF, class VF>
+  __device__ static __forceinline__ void pair_block(const float4v& hb0, const float4v& hb1, const Tok& t,
+                                                    const Need& nd, int k, int q, UF uf, VF vf, float (&o)[8],
+                                                    float4v (&sacc)[KMAX][NSP]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = 0.f;
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
       if (j >= k) continue;
       const int ej = t.e[j];
-      float16v hj = hb;
-      for (int kc = 0; kc < n_chunks; ++kc) {
-        if (__ballot(t.valid && chunk_has(ej, kc)) == 0ull) continue;
-        hj = mfma16(uf(kc), t1_frag(ej, kc, h, t.f[j]), hj);
+      float4v h0 = hb0, h1 = hb1;
+      for (unsigned m = nd.chunks[j]; m != 0u; m &= m - 1u) {
+        const int c = __builtin_ctz(m);
+        const half8 fb = t1_frag(ej, c, q, t.f[j]);
+        h0 = mfma32(uf(c, 0), fb, h0);
+        h1 = mfma32(uf(c, 1), fb, h1);
       }
+      float a[8];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        hj[v] = gelu_erf(hj[v]);
-        o[v] = fmaf(t.g[j], hj[v], o[v]);
+      for (int i = 0; i < 4; ++i) {
+        a[i] = gelu_erf(h0[i]);
+        a[4 + i] = gelu_erf(h1[i]);
       }
-      for (int q = 0; q < n_pass; ++q) {
-        const bool on = t.valid && (ej / EPB == q);
-        if (__ballot(on) == 0ull) continue;
+      half8 ab;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-          half8 fb;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) fb[i] = on ? (half_t)hj[8 * s + i] : (half_t)0.f;
-          sacc[j] = mfma16(vf(q, s), fb, sacc[j]);
-        }
+      for (int i = 0; i < 8; ++i) {
+        o[i] = fmaf(t.g[j], a[i], o[i]);
+        ab[i] = (half_t)a[i];
+      }
+      const int p0 = (ej * R) >> 4;   // first pass of the expert's rank rows
+      for (unsigned m = nd.passes[j]; m != 0u; m &= m - 1u) {
+        const int pp = __builtin_ctz(m);
+        const bool on = t.valid && (pp & ~(NSP - 1)) == p0;
+        const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        sacc[j][pp & (NSP - 1)] = mfma32(vf(pp), on ? ab : z, sacc[j][pp & (NSP - 1)]);
       }
     }
   }
 
-  // The lane holds rows 8*qd + 4h + (0..3) of the pass accumulator; those inside
-  // [b_e*R, b_e*R + R) are the token's s_j.  dst_tile: [T][k][R] partial of this row tile
-  // (FP32, or FP16 where many partials are summed afterwards in FP32).
-  template <class ST>
-  __device__ static __forceinline__ void store_s(const Tok& t, const float16v (&sacc)[KMAX], ST* dst_tile, int k,
-                                                 int h) {
+  // The lane holds rank rows 4q .. 4q + 3 of each pass accumulator; those inside the expert's
+  // rows are the token's s_j.  dst_tile: [T][k][R] FP32 partial of this row tile.
+  __device__ static __forceinline__ void store_s(const Tok& t, const float4v (&sacc)[KMAX][NSP], float* dst_tile,
+                                                 int k, int q) {
     if (!t.valid) return;
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
       if (j >= k) continue;
-      const int be = (t.e[j] % EPB) * R;
-      ST* dst = dst_tile + ((size_t)t.p * k + j) * R;
+      const int be = (t.e[j] * R) & 15;   // first row of the expert inside its pass
+      float* dst = dst_tile + ((size_t)t.p * k + j) * R;
+      const int row0 = 4 * q;
+      if (row0 >= be && row0 < be + (R < 16 ? R : 16)) {
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        int row0 = 8 * qd + 4 * h;
-        if (row0 >= be && row0 < be + R) {
-          if constexpr (sizeof(ST) == 2) {
-            *(half4*)(dst + row0 - be) = half4{(half_t)sacc[j][4 * qd], (half_t)sacc[j][4 * qd + 1],
-                                               (half_t)sacc[j][4 * qd + 2], (half_t)sacc[j][4 * qd + 3]};
-          } else {
-            float4v v4 = {sacc[j][4 * qd], sacc[j][4 * qd + 1], sacc[j][4 * qd + 2], sacc[j][4 * qd + 3]};
-            *(float4v*)(dst + row0 - be) = v4;
-          }
-        }
+        for (int s = 0; s < NSP; ++s) *(float4v*)(dst + 16 * s + row0 - be) = sacc[j][s];
       }
     }
   }

@@ -5,12 +5,12 @@
 //   y    = Yb + sum_j g_j U2 s_j, back in token order
 //
 // All products are computed "weights x tokens^T": the weight rows are the A operand of
-// v_mfma_f32_32x32x16_f16 (rows n of the 32x32 block), the tokens are the B operand
-// (columns m).  A lane of a 32x32 accumulator block then holds ONE token (column
-// m = lane % 32) and 16 output rows n = 8*(v/4) + 4*(lane/32) + v%4, v = 0..15.  That is
-// what lets the per-token quantities (experts, gates, t1) live in per-lane registers, and
-// lets an accumulator block be fed back as the B operand of the next product without
-// leaving registers (its rows become the contraction index).
+// v_mfma_f32_16x16x32_f16 (rows of the 16x16 block), the tokens are the B operand (columns).
+// A lane of an accumulator block then holds ONE token (column lane % 16) and four output
+// rows; with the row order of the pair blocks (cmoe_device.h) two blocks give it eight
+// consecutive rows.  That is what lets the per-token quantities (experts, gates, t1) live in
+// per-lane registers, and lets an accumulator pair be fed back as the B operand of the next
+// product without leaving registers (its rows become the contraction index).
 #include "cmoe_device.h"
 
 #include <type_traits>
@@ -18,10 +18,11 @@
 namespace {
 
 // Tile of one workgroup: BN weight rows x BM tokens, WAVES_N x WAVES_M wavefronts, each
-// owning (BN/WAVES_N) x (BM/WAVES_M) outputs as 32x32 accumulator blocks.  Operand tiles
+// owning (BN/WAVES_N) x (BM/WAVES_M) outputs as 16x16 accumulator blocks.  Operand tiles
 // move global -> LDS with direct-to-LDS loads (no register staging) into NS stages of 32
 // contraction elements; rows are 64 B, their four 16-B chunks XOR-swizzled with
-// (row >> 2) & 3 so that the 16 lanes the LDS serves per cycle hit 64 distinct banks.
+// (row >> 2) & 3 so that the 16 lanes the LDS serves per cycle hit 64 distinct banks.  The
+// weight rows of a tile are stored in MFMA order: tile row rho holds weight row pi_row(rho).
 template <int BN_, int BM_, int WAVES_N_, int WAVES_M_, int NS_, int OCC_, bool PINGPONG_, int XSM_, int XSN_>
 struct Tile {
   static constexpr int BN = BN_, BM = BM_, WAVES_N = WAVES_N_, WAVES_M = WAVES_M_, NS = NS_, OCC = OCC_;
@@ -29,12 +30,13 @@ struct Tile {
   static constexpr int XSM = XSM_, XSN = XSN_;  // per-XCD super-tile: XSM row tiles x XSN column tiles
   static constexpr int NWAVES = WAVES_N * WAVES_M, NT = NWAVES * 64;
   static constexpr int WN = BN / WAVES_N, WM = BM / WAVES_M;
-  static constexpr int NB = WN / 32, MB = WM / 32;
+  static constexpr int NA = WN / 16, MT = WM / 16;   // 16-row blocks and 16-token blocks of a wavefront
+  static constexpr int NP = WN / 32;                 // pair blocks of a wavefront
   static constexpr int BK = 32, ROWB = BK * 2;
   static constexpr int STAGE_BYTES = (BN + BM) * ROWB;
   static constexpr int SMEM_BYTES = NS * STAGE_BYTES;
   static constexpr int PER_WAVE = (BN + BM) / 16 / NWAVES;  // 1-KiB load instructions per wavefront and stage
-  static_assert(BN % (32 * WAVES_N) == 0 && BM % (32 * WAVES_M) == 0, "wave tile");
+  static_assert(BN % (32 * WAVES_N) == 0 && BM % (16 * WAVES_M) == 0, "wave tile");
   static_assert(((BN + BM) / 16) % NWAVES == 0, "load split");
   static_assert(!PINGPONG || (NWAVES == 8 && NS >= 3), "ping-pong pairs wavefront w with w + 4");
 };
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
     const int chunk = pos ^ ((row >> 2) & 3);
     const half_t* base;
     if (row < TL::BN) {
-      const int n = min(n0 + row, g.N - 1);
+      const int n = min(n0 + pi_row(row), g.N - 1);
       base = (g.W2 != nullptr && n >= g.w_split) ? g.W2 + (size_t)(n - g.w_split) * g.ldw : Wc + (size_t)n * g.ldw;
     } else {
       const int p = min(m0 + row - TL::BN, m_end - 1);
@@ -171,36 +173,31 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
             smem_base + stage * TL::STAGE_BYTES + (wave * TL::PER_WAVE + i) * 1024);
   };
 
-  float16v acc[TL::NB][TL::MB];
+  float4v acc[TL::NA][TL::MT];
 #pragma unroll
-  for (int a = 0; a < TL::NB; ++a)
+  for (int a = 0; a < TL::NA; ++a)
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    for (int b = 0; b < TL::MT; ++b) acc[a][b] = float4v{0.f, 0.f, 0.f, 0.f};
 
-  const int fr = lane & 31, h = lane >> 5;
-  int offa[TL::NB][2], offb[TL::MB][2];
+  // fragment addresses: lane l reads row (or token) l % 16, 16-byte chunk l / 16 of the 64-byte row
+  const int t16 = lane & 15, q = lane >> 4;
+  int offa[TL::NA], offb[TL::MT];
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int cc = ks * 2 + h;
+  for (int a = 0; a < TL::NA; ++a) {
+    const int row = wn * TL::WN + a * 16 + t16;
+    offa[a] = row * TL::ROWB + ((q ^ ((row >> 2) & 3)) << 4);
+  }
 #pragma unroll
-    for (int a = 0; a < TL::NB; ++a) {
-      const int row = wn * TL::WN + a * 32 + fr;
-      offa[a][ks] = row * TL::ROWB + ((cc ^ ((row >> 2) & 3)) << 4);
-    }
-#pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      const int row = TL::BN + wm * TL::WM + b * 32 + fr;
-      offb[b][ks] = row * TL::ROWB + ((cc ^ ((row >> 2) & 3)) << 4);
-    }
+  for (int b = 0; b < TL::MT; ++b) {
+    const int row = TL::BN + wm * TL::WM + b * 16 + t16;
+    offb[b] = row * TL::ROWB + ((q ^ ((row >> 2) & 3)) << 4);
   }
 
-  // 32-column blocks of this wavefront that hold at least one real token (a ragged last
+  // 16-token blocks of this wavefront that hold at least one real token (a ragged last
   // row tile of a cluster skips the matrix-core work of the others)
-  bool bv[TL::MB];
+  bool bv[TL::MT];
 #pragma unroll
-  for (int b = 0; b < TL::MB; ++b) bv[b] = m0 + wm * TL::WM + b * 32 < m_end;
+  for (int b = 0; b < TL::MT; ++b) bv[b] = m0 + wm * TL::WM + b * 16 < m_end;
 
   const int KT = (g.krange ? g.krange[2 * c + 1] : g.Kc) / TL::BK;
 #pragma unroll
@@ -215,21 +212,18 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
       __builtin_amdgcn_s_barrier();
       if (kt + TL::NS - 1 < KT) issue(kt + TL::NS - 1, nstage);
       const char* sb = smem + stage * TL::STAGE_BYTES;
+      half8 fa[TL::NA], fb[TL::MT];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        half8 fa[TL::NB], fb[TL::MB];
+      for (int a = 0; a < TL::NA; ++a) fa[a] = *(const half8*)(sb + offa[a]);
 #pragma unroll
-        for (int a = 0; a < TL::NB; ++a) fa[a] = *(const half8*)(sb + offa[a][ks]);
+      for (int b = 0; b < TL::MT; ++b)
+        if (bv[b]) fb[b] = *(const half8*)(sb + offb[b]);
 #pragma unroll
-        for (int b = 0; b < TL::MB; ++b)
-          if (bv[b]) fb[b] = *(const half8*)(sb + offb[b][ks]);
+      for (int b = 0; b < TL::MT; ++b)
+        if (bv[b]) {
 #pragma unroll
-        for (int b = 0; b < TL::MB; ++b)
-          if (bv[b]) {
-#pragma unroll
-            for (int a = 0; a < TL::NB; ++a) acc[a][b] = mfma16(fa[a], fb[b], acc[a][b]);
-          }
-      }
+          for (int a = 0; a < TL::NA; ++a) acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
+        }
       stage = (stage + 1 == TL::NS) ? 0 : stage + 1;
       nstage = (nstage + 1 == TL::NS) ? 0 : nstage + 1;
     }
@@ -237,26 +231,22 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
     // Ping-pong: wavefronts 4..7 run one barrier interval behind wavefronts 0..3, so in
     // every interval one wavefront of each SIMD issues its MFMAs while the other reads
     // fragments from LDS.  The direct-to-LDS loads of tile kt + NS - 1 are issued from
-    // inside the MFMA phase, one after each group of NB MFMAs: there the wavefront has
+    // inside the MFMA phase, one after each group of NA MFMAs: there the wavefront has
     // issue slots to spare, while in the read phase every vector-memory instruction
     // lengthens the interval (measured: about 50 cycles per instruction and interval).
     const bool set_b = wave >= 4;
-    constexpr int GROUPS = 2 * TL::MB;   // MFMA groups per k-tile
     if (KT > 1) wait_vm<(TL::NS - 2) * TL::PER_WAVE>(); else wait_vm<0>();
     if (KT <= TL::NS - 2) wait_vm<0>();
     __builtin_amdgcn_s_barrier();
     if (set_b) __builtin_amdgcn_s_barrier();
     for (int kt = 0; kt < KT; ++kt) {
       const char* sb = smem + stage * TL::STAGE_BYTES;
-      half8 fa[2][TL::NB], fb[2][TL::MB];
+      half8 fa[TL::NA], fb[TL::MT];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int a = 0; a < TL::NA; ++a) fa[a] = *(const half8*)(sb + offa[a]);
 #pragma unroll
-        for (int a = 0; a < TL::NB; ++a) fa[ks][a] = *(const half8*)(sb + offa[a][ks]);
-#pragma unroll
-        for (int b = 0; b < TL::MB; ++b)
-          if (bv[b]) fb[ks][b] = *(const half8*)(sb + offb[b][ks]);
-      }
+      for (int b = 0; b < TL::MT; ++b)
+        if (bv[b]) fb[b] = *(const half8*)(sb + offb[b]);
       // own loads in flight: tiles kt + 1 .. kt + NS - 2 (fewer near the end); tile kt + 1
       // must have landed before the barrier that lets the other set read it
       if (kt + TL::NS - 2 < KT) wait_vm<(TL::NS - 3) * TL::PER_WAVE>(); else wait_vm<0>();
@@ -269,21 +259,19 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
       // barrier that opened this interval
       const bool refill = kt + TL::NS - 1 < KT;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+      for (int b = 0; b < TL::MT; ++b) {
+        if (bv[b]) {
 #pragma unroll
-        for (int b = 0; b < TL::MB; ++b) {
-          if (bv[b]) {
-#pragma unroll
-            for (int a = 0; a < TL::NB; ++a) acc[a][b] = mfma16(fa[ks][a], fb[ks][b], acc[a][b]);
-          }
-          if (refill) {
-#pragma unroll
-            for (int i = 0; i < TL::PER_WAVE; ++i)
-              if (i % GROUPS == ks * TL::MB + b)
-                  dma16(gsrc[i] + (size_t)(kt + TL::NS - 1) * (((wave * TL::PER_WAVE + i) * 16 < TL::BN) ? kstep_w : kstep_x),
-                      smem_base + nstage * TL::STAGE_BYTES + (wave * TL::PER_WAVE + i) * 1024);
-          }
+          for (int a = 0; a < TL::NA; ++a) acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
         }
+        if (refill) {
+#pragma unroll
+          for (int i = 0; i < TL::PER_WAVE; ++i)
+            if (i % TL::MT == b)
+              dma16(gsrc[i] + (size_t)(kt + TL::NS - 1) * (((wave * TL::PER_WAVE + i) * 16 < TL::BN) ? kstep_w : kstep_x),
+                    smem_base + nstage * TL::STAGE_BYTES + (wave * TL::PER_WAVE + i) * 1024);
+        }
+      }
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_barrier();
@@ -299,7 +287,8 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 }
 
 // ---------------------------------------------------------------- epilogue: plain store
-// out[p][n] = acc (f16), rows p in cluster-sorted order.
+// out[p][n] = acc (f16 or f32), rows p in cluster-sorted order.  A lane writes the eight
+// consecutive outputs of a pair block for its token in one piece.
 template <class OutT>
 struct EpiStoreT {
   OutT* out;
@@ -308,24 +297,23 @@ struct EpiStoreT {
   template <class TL>
   static constexpr int smem_bytes() { return TL::SMEM_BYTES; }
   template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
-    const int h = t.lane >> 5;
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
+    const int t16 = t.lane & 15, q = t.lane >> 4;
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      int p = t.m0 + t.wm * TL::WM + b * 32 + (t.lane & 31);
+    for (int b = 0; b < TL::MT; ++b) {
+      const int p = t.m0 + t.wm * TL::WM + b * 16 + t16;
       if (p >= t.m_end) continue;
       const size_t orow = rowmap ? rowmap[p] : p;
 #pragma unroll
-      for (int a = 0; a < TL::NB; ++a) {
-        int nb = t.n0 + t.wn * TL::WN + a * 32;
-        if (nb >= N) continue;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-          if constexpr (sizeof(OutT) == 2)
-            *(half4*)(out + orow * ldo + nb + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
-          else
-            *(float4v*)(out + orow * ldo + nb + 8 * qd + 4 * h) =
-                float4v{acc[a][b][4 * qd], acc[a][b][4 * qd + 1], acc[a][b][4 * qd + 2], acc[a][b][4 * qd + 3]};
+      for (int P = 0; P < TL::NP; ++P) {
+        const int nb = t.n0 + t.wn * TL::WN + 32 * P + 8 * q;
+        if (nb >= N) continue;   // N is a multiple of 8
+        if constexpr (sizeof(OutT) == 2) {
+          *(half8*)(out + orow * ldo + nb) = pack_half8(acc[2 * P][b], acc[2 * P + 1][b]);
+        } else {
+          *(float4v*)(out + orow * ldo + nb) = acc[2 * P][b];
+          *(float4v*)(out + orow * ldo + nb + 4) = acc[2 * P + 1][b];
+        }
       }
     }
   }
@@ -333,10 +321,11 @@ struct EpiStoreT {
 using EpiStore = EpiStoreT<half_t>;
 
 // ---------------------------------------------------------------- epilogue: down-projection + combine
-// acc = (W2_base A)^T block.  Adds the residual of the second matrix as one more
+// acc = (W2_base A)^T blocks.  Adds the residual of the second matrix as one more
 // matrix-core contraction over the cluster's rank rows, y^T += U2cat^T sext^T with
-// sext[m][e_j*r + rho] = g_j s_j[rho] (zero elsewhere, chunks no token of a 32-column block
-// needs are skipped), and writes the rows straight to token order.  K*r <= 128.
+// sext[m][e_j*r + rho] = g_j s_j[rho] (zero elsewhere, chunks of 32 rank rows that no token
+// of a 16-token block needs are skipped), and writes the rows straight to token order, 16
+// bytes per lane.  K*r <= 128.
 struct EpiDownCombine {
   const half_t* u2t;     // [G][d][KRp]
   const float* s_down;   // [T][k][r], token order
@@ -345,23 +334,15 @@ struct EpiDownCombine {
   const float* gate;
   half_t* y;             // [T][d], token order
   int k, K, r, KRp, d;
-  // per wavefront: one 32 x 32 output block as f16 (rows padded to 40 elements), so that
-  // four lanes write one token's 64 contiguous bytes
-  static constexpr int OT_LD = 40, OT_BYTES = 32 * OT_LD * 2;
   template <class TL>
-  static constexpr int panel_bytes() {
+  static constexpr int smem_bytes() {
     return 2 * (TL::BN + TL::BM) * (128 + 8) > TL::SMEM_BYTES ? 2 * (TL::BN + TL::BM) * (128 + 8) : TL::SMEM_BYTES;
   }
   template <class TL>
-  static constexpr int smem_bytes() {
-    return panel_bytes<TL>() + TL::NWAVES * OT_BYTES;
-  }
-  template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
-    const int h = t.lane >> 5, ml = t.lane & 31;
-    const int ldu = KRp + 8, n_chunks = KRp / 16;
-    half_t* ot = (half_t*)((char*)t.smem + panel_bytes<TL>()) + (t.wm * TL::WAVES_N + t.wn) * (OT_BYTES / 2);
-    half_t* sU = t.smem;                 // [BN][ldu]  U2 rows of the tile
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
+    const int t16 = t.lane & 15, q = t.lane >> 4;
+    const int ldu = KRp + 8, n_chunks = KRp / 32;
+    half_t* sU = t.smem;                 // [BN][ldu]  U2 rows of the tile, in MFMA order
     half_t* sS = t.smem + TL::BN * ldu;  // [BM][ldu]  expanded gated s of the tile's tokens
     const half_t* u2c = u2t + (size_t)t.c * d * KRp;
     __syncthreads();  // the stage buffers are free
@@ -373,7 +354,8 @@ struct EpiDownCombine {
 #pragma unroll
         for (int i = 0; i < UB; ++i) {
           int idx = base + i * TL::NT;
-          if (idx < u_chunks) tmp[i] = *(const half8*)(u2c + (size_t)min(t.n0 + idx / ucpr, d - 1) * KRp + (idx % ucpr) * 8);
+          if (idx < u_chunks)
+            tmp[i] = *(const half8*)(u2c + (size_t)min(t.n0 + pi_row(idx / ucpr), d - 1) * KRp + (idx % ucpr) * 8);
         }
 #pragma unroll
         for (int i = 0; i < UB; ++i) {
@@ -394,47 +376,34 @@ struct EpiDownCombine {
     }
     __syncthreads();
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      const int ml_t = t.wm * TL::WM + b * 32 + ml;
+    for (int b = 0; b < TL::MT; ++b) {
+      const int ml_t = t.wm * TL::WM + b * 16 + t16;
       const int p = t.m0 + ml_t;
       const bool valid = p < t.m_end;
       const int tok = rperm[valid ? p : t.m_end - 1];
       unsigned mine = 0;
       for (int j = 0; j < k; ++j) {
         const int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
-        const int lo = (e * r) >> 4, hi = (e * r + r - 1) >> 4;
+        const int lo = (e * r) >> 5, hi = (e * r + r - 1) >> 5;
         mine |= (0xffffffffu >> (31 - hi)) & (0xffffffffu << lo);
       }
       if (!valid) mine = 0;
       unsigned cmask = 0;
       for (int kc = 0; kc < n_chunks; ++kc)
         if (__ballot((mine >> kc) & 1u) != 0ull) cmask |= 1u << kc;
-      // tokens of the rows this lane stores after the transposition (-1: beyond the cluster)
-      int tok_o[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int po = t.m0 + t.wm * TL::WM + b * 32 + (t.lane >> 2) + 16 * i;
-        tok_o[i] = po < t.m_end ? rperm[po] : -1;
-      }
-#pragma unroll
-      for (int a = 0; a < TL::NB; ++a) {
-        const int nl = t.wn * TL::WN + a * 32;
+      for (int P = 0; P < TL::NP; ++P) {
+        const int nl = t.wn * TL::WN + 32 * P;
         if (t.n0 + nl >= d) continue;
         for (int kc = 0; kc < n_chunks; ++kc) {
           if (!((cmask >> kc) & 1u)) continue;
-          const half8 fa = *(const half8*)(sU + (nl + ml) * ldu + kc * 16 + 8 * h);
-          const half8 fb = *(const half8*)(sS + ml_t * ldu + kc * 16 + 8 * h);
-          acc[a][b] = mfma16(fa, fb, acc[a][b]);
+          const half8 fb = *(const half8*)(sS + ml_t * ldu + kc * 32 + 8 * q);
+          const half8 fa0 = *(const half8*)(sU + (nl + t16) * ldu + kc * 32 + 8 * q);
+          const half8 fa1 = *(const half8*)(sU + (nl + 16 + t16) * ldu + kc * 32 + 8 * q);
+          acc[2 * P][b] = mfma32(fa0, fb, acc[2 * P][b]);
+          acc[2 * P + 1][b] = mfma32(fa1, fb, acc[2 * P + 1][b]);
         }
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) *(half4*)(ot + ml * OT_LD + 8 * qd + 4 * h) = to_half4(acc[a][b], qd);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const half8 v8 = *(const half8*)(ot + ((t.lane >> 2) + 16 * i) * OT_LD + (t.lane & 3) * 8);
-          if (tok_o[i] >= 0) *(half8*)(y + (size_t)tok_o[i] * d + t.n0 + nl + (t.lane & 3) * 8) = v8;
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
+        if (valid) *(half8*)(y + (size_t)tok * d + t.n0 + nl + 8 * q) = pack_half8(acc[2 * P][b], acc[2 * P + 1][b]);
       }
     }
   }
@@ -448,6 +417,23 @@ struct EpiDownCombine {
 // expert logits are computed because one matrix-core product over the routers is cheaper
 // here than K dot products per token on the vector units; the unselected clusters' logits
 // are discarded.)
+template <class TL>
+__device__ __forceinline__ void stage_logits(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT], float* lg, int LD) {
+  const int t16 = t.lane & 15, q = t.lane >> 4;
+#pragma unroll
+  for (int b = 0; b < TL::MT; ++b) {
+    const int m = t.wm * TL::WM + b * 16 + t16;
+#pragma unroll
+    for (int P = 0; P < TL::NP; ++P)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int n = t.wn * TL::WN + 32 * P + 8 * q;
+        lg[m * LD + n + v] = acc[2 * P][b][v];
+        lg[m * LD + n + 4 + v] = acc[2 * P + 1][b][v];
+      }
+  }
+}
+
 struct EpiRoute {
   const float* bias;
   int* cluster_id;
@@ -459,20 +445,11 @@ struct EpiRoute {
     return TL::BM * (TL::BN + 1) * 4 > TL::SMEM_BYTES ? TL::BM * (TL::BN + 1) * 4 : TL::SMEM_BYTES;
   }
   template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
     constexpr int LD = TL::BN + 1;
     float* lg = (float*)t.smem;  // [BM tokens][BN + 1 logits]
-    const int h = t.lane >> 5, ml = t.lane & 31;
     __syncthreads();  // the stage buffers are free
-#pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      const int m = t.wm * TL::WM + b * 32 + ml;
-#pragma unroll
-      for (int a = 0; a < TL::NB; ++a)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          lg[m * LD + t.wn * TL::WN + a * 32 + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[a][b][v];
-    }
+    stage_logits<TL>(t, acc, lg, LD);
     __syncthreads();
     for (int m = t.tid; m < TL::BM; m += TL::NT) {
       const int tok = t.m0 + m;
@@ -537,20 +514,11 @@ struct EpiRouteMulti {
     return EpiRoute::smem_bytes<TL>();
   }
   template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
     constexpr int LD = TL::BN + 1;
     float* lg = (float*)t.smem;  // [BM tokens][BN + 1 logits]
-    const int h = t.lane >> 5, ml = t.lane & 31;
     __syncthreads();  // the stage buffers are free
-#pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      const int m = t.wm * TL::WM + b * 32 + ml;
-#pragma unroll
-      for (int a = 0; a < TL::NB; ++a)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          lg[m * LD + t.wn * TL::WN + a * 32 + 8 * (v >> 2) + 4 * h + (v & 3)] = acc[a][b][v];
-    }
+    stage_logits<TL>(t, acc, lg, LD);
     __syncthreads();
     for (int m = t.tid; m < TL::BM; m += TL::NT) {
       const int tok = t.m0 + m;
@@ -627,24 +595,26 @@ struct EpiT1 {
   template <class TL>
   static constexpr int smem_bytes() { return TL::SMEM_BYTES; }
   template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
-    const int h = t.lane >> 5;
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
+    const int t16 = t.lane & 15, q = t.lane >> 4;
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      int p = t.m0 + t.wm * TL::WM + b * 32 + (t.lane & 31);
+    for (int b = 0; b < TL::MT; ++b) {
+      const int p = t.m0 + t.wm * TL::WM + b * 16 + t16;
       if (p >= t.m_end) continue;
-      int tok = perm[p];
+      const int tok = perm[p];
       for (int j = 0; j < k; ++j) {
-        int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
+        const int e = min(max(expert_idx[(size_t)tok * k + j] - t.c * K, 0), K - 1);
         half_t* row = t1 + ((size_t)p * k + j) * r;
 #pragma unroll
-        for (int a = 0; a < TL::NB; ++a) {
-          int nb = t.n0 + t.wn * TL::WN + a * 32;
-          if (nb >= KRp) continue;
-#pragma unroll
-          for (int qd = 0; qd < 4; ++qd) {
-            int kk = nb + 8 * qd + 4 * h;  // 4 consecutive rank rows, all of one expert (r % 4 == 0)
-            if (kk / r == e) *(half4*)(row + (kk - e * r)) = to_half4(acc[a][b], qd);
+        for (int P = 0; P < TL::NP; ++P) {
+          const int kk = t.n0 + t.wn * TL::WN + 32 * P + 8 * q;   // 8 consecutive rank rows
+          if (kk >= KRp) continue;
+          if (r >= 8) {           // all of one expert
+            if (kk / r == e) *(half8*)(row + (kk - e * r)) = pack_half8(acc[2 * P][b], acc[2 * P + 1][b]);
+          } else {                // r == 4: two experts
+            const half8 v8 = pack_half8(acc[2 * P][b], acc[2 * P + 1][b]);
+            if (kk / 4 == e) *(half4*)row = half4{v8[0], v8[1], v8[2], v8[3]};
+            if (kk / 4 + 1 == e) *(half4*)row = half4{v8[4], v8[5], v8[6], v8[7]};
           }
         }
       }
@@ -653,60 +623,66 @@ struct EpiT1 {
 };
 
 // ---------------------------------------------------------------- epilogue: fused up-projection
-// acc = Hb^T block (rows n of d_ff, columns = tokens).  Per token column and selected
+// acc = Hb^T blocks (rows n of d_ff, columns = tokens).  Per token column and selected
 // expert j:  h_j = Hb + U1cat^T t1ext_j with t1ext_j the token's t1_j placed at the rank rows
 // of expert e_j and zero elsewhere (matrix core, contraction over the cluster's K*r rank
-// rows in chunks of 16; a chunk no token of the 32-column block needs is skipped);
-// a_j = GELU(h_j); A += g_j a_j; s_j += V2 a_j by feeding the a_j block back as B operand
-// (contraction over the block's 32 rows n).  The V2 product runs over "passes" of 32 rank
-// rows (32/r experts); a lane contributes to a pass only if its token's expert lies in
-// it, so after all passes row (e_j % (32/r))*r + rho of the accumulator holds s_j[rho].
+// rows in chunks of 32; a chunk no token of the 16-token block needs is skipped);
+// a_j = GELU(h_j); A += g_j a_j; s_j += V2 a_j by feeding the a_j pair block back as B operand
+// (contraction over its 32 rows n).  The V2 product runs over "passes" of 16 rank rows; a
+// lane contributes to a pass only if its token's expert lies in it.
 // With STAGE the U1 / V2 panels of the tile are staged through LDS (K*r <= 128);
 // otherwise they are read from global memory.
 template <int R, int KMAX, bool STAGE>
 struct EpiFusedUp {
   const half_t* u1t;  // [G][d_ff][KRp]
-  const half_t* v2p;  // [G][KRp][d_ff], columns permuted inside 16-groups
+  const half_t* v2p;  // [G][KRp][d_ff]
   const half_t* t1;   // [T][k][r], sorted rows
   const int* perm;
   const int* expert_idx;
   const float* gate;
-  half_t* A;          // [T][d_ff]
+  half_t* A;          // [d_ff / 32][T][32]
   float* spart;       // [n_tiles][T][k][r] partials of V2 a over the tile's 256 rows of d_ff, FP32
   int T, k, K, KRp, d_ff;
   using FU = FusedUp<R, KMAX>;
 
-  // per wavefront: one 32 x 32 output block as f16, rows padded to 40 elements, to turn
-  // the accumulator layout (a lane holds 4-element pieces of 16 rows) into row-contiguous
-  // 16-byte stores
-  static constexpr int OT_LD = 40, OT_BYTES = 32 * OT_LD * 2;
   template <class TL>
   static constexpr int panel_bytes() {
     return (STAGE && 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8)) > TL::SMEM_BYTES)
                ? 2 * (TL::BN * (128 + 8) + 128 * (TL::BN + 8))
                : TL::SMEM_BYTES;
   }
+  // The two wavefronts that share a token block add their s partials through LDS.  With up
+  // to two experts per token the partials of all token blocks are exchanged at the end, in
+  // the space of the panels (no longer needed then); otherwise block by block through an
+  // area of its own behind the panels.
+  static constexpr bool BATCH = KMAX <= 2;
+  static constexpr int XS_FLOATS = (BATCH ? 4 * KMAX * FusedUp<R, KMAX>::NSP : 1) * 4 * 64;   // per wavefront column
   template <class TL>
   static constexpr int smem_bytes() {
-    return panel_bytes<TL>() + TL::NWAVES * OT_BYTES;
+    static_assert(!BATCH || (TL::MT == 4 && TL::WAVES_M * XS_FLOATS * 4 <= TL::SMEM_BYTES), "exchange area");
+    return panel_bytes<TL>() + (BATCH ? 0 : TL::WAVES_M * XS_FLOATS * 4);
   }
 
   template <class TL>
-  __device__ void run(const TileCtx& t, float16v (&acc)[TL::NB][TL::MB]) const {
+  __device__ void run(const TileCtx& t, float4v (&acc)[TL::NA][TL::MT]) const {
     static_assert(TL::BN == G1_BN && TL::WAVES_N == 2, "one s partial per tile of G1_BN rows, summed over its two wavefront columns");
-    const int h = t.lane >> 5, ml = t.lane & 31;
+    const int t16 = t.lane & 15, q = t.lane >> 4;
     const half_t* u1c = u1t + (size_t)t.c * d_ff * KRp;
     const half_t* v2c = v2p + (size_t)t.c * KRp * d_ff;
-    const int n_chunks = KRp / 16, n_pass = KRp / 32;
+    const int n_chunks = KRp / 32, n_pass = KRp / 16;
     const int ldu = KRp + 8, ldv = TL::BN + 8;
-    half_t* sU = t.smem;                 // [BN][KRp + 8]
+    half_t* sU = t.smem;                 // [BN][KRp + 8], rows in MFMA order
     half_t* sV = t.smem + TL::BN * ldu;  // [KRp][BN + 8]
 
-    // per-lane token state of every 32-column block this wavefront owns
-    typename FU::Tok tk[TL::MB];
+    // per-lane token state of every 16-token block this wavefront owns: loaded up front
+    // (behind the panel staging) while it fits the registers, else block by block
+    constexpr bool PRELOAD = KMAX <= 2;
+    typename FU::Tok tk[PRELOAD ? TL::MT : 1];
+    if (PRELOAD) {
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b)
-      FU::load_tok(tk[b], t.m0 + t.wm * TL::WM + b * 32 + ml, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, h);
+      for (int b = 0; b < (PRELOAD ? TL::MT : 1); ++b)
+        FU::load_tok(tk[b], t.m0 + t.wm * TL::WM + b * 16 + t16, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, q);
+    }
 
     if (STAGE) {
       __syncthreads();  // every wavefront has left the main loop: the stage buffers are free
@@ -719,7 +695,7 @@ struct EpiFusedUp {
           int idx = base + i * TL::NT;
           if (idx < u_chunks) {
             int row = idx / ucpr, ch = idx % ucpr;
-            tmp[i] = *(const half8*)(u1c + (size_t)min(t.n0 + row, d_ff - 1) * KRp + ch * 8);
+            tmp[i] = *(const half8*)(u1c + (size_t)min(t.n0 + pi_row(row), d_ff - 1) * KRp + ch * 8);
           }
         }
 #pragma unroll
@@ -748,66 +724,98 @@ struct EpiFusedUp {
       __syncthreads();
     }
 
+    // with few experts per token the s partials of all token blocks are kept and exchanged
+    // at the end in one go; otherwise block by block
+    constexpr int NSB = BATCH ? TL::MT : 1;
+    float4v sacc[NSB][KMAX][FU::NSP];
+    float* xs = (BATCH ? (float*)t.smem : (float*)((char*)t.smem + panel_bytes<TL>())) + t.wm * XS_FLOATS;
 #pragma unroll
-    for (int b = 0; b < TL::MB; ++b) {
-      float16v sacc[KMAX];
+    for (int b = 0; b < TL::MT; ++b) {
+      const int sb = BATCH ? b : 0;
 #pragma unroll
       for (int j = 0; j < KMAX; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[j][v] = 0.f;
+        for (int s2 = 0; s2 < FU::NSP; ++s2) sacc[sb][j][s2] = float4v{0.f, 0.f, 0.f, 0.f};
+      const int p = t.m0 + t.wm * TL::WM + b * 16 + t16;
+      if (!PRELOAD) FU::load_tok(tk[0], p, t.m_end, t.c, K, k, perm, expert_idx, gate, t1, q);
+      const typename FU::Tok& tkb = tk[PRELOAD ? b : 0];
+      typename FU::Need nd;
+      FU::need_of(tkb, k, n_chunks, n_pass, nd);
 #pragma unroll
-      for (int a = 0; a < TL::NB; ++a) {
-        const int nl = t.wn * TL::WN + a * 32;  // first row of the block inside the tile
+      for (int P = 0; P < TL::NP; ++P) {
+        const int nl = t.wn * TL::WN + 32 * P;  // first row of the pair block inside the tile
         const int nb = t.n0 + nl;
         if (nb >= d_ff) continue;
-        float16v o;
-        auto uf = [&](int kc) {
-          return STAGE ? *(const half8*)(sU + (nl + ml) * ldu + kc * 16 + 8 * h)
-                       : *(const half8*)(u1c + (size_t)(nb + ml) * KRp + kc * 16 + 8 * h);
+        auto uf = [&](int c, int hh) {
+          return STAGE ? *(const half8*)(sU + (nl + 16 * hh + t16) * ldu + c * 32 + 8 * q)
+                       : *(const half8*)(u1c + (size_t)(nb + pi_row(16 * hh + t16)) * KRp + c * 32 + 8 * q);
         };
-        auto vf = [&](int q, int s2) {
-          return STAGE ? *(const half8*)(sV + (q * 32 + ml) * ldv + nl + 16 * s2 + 8 * h)
-                       : *(const half8*)(v2c + (size_t)(q * 32 + ml) * d_ff + nb + 16 * s2 + 8 * h);
+        auto vf = [&](int pp) {
+          return STAGE ? *(const half8*)(sV + (pp * 16 + t16) * ldv + nl + 8 * q)
+                       : *(const half8*)(v2c + (size_t)(pp * 16 + t16) * d_ff + nb + 8 * q);
         };
-        FU::block(acc[a][b], tk[b], k, n_chunks, n_pass, h, uf, vf, o, sacc);
-        // A[p][nb .. nb + 32) for the block's 32 tokens, stored in 32-column blocks
-        // ([d_ff / 32][T][32], the operand layout of the down-projection): through the
-        // wavefront's LDS patch, so that four lanes write one token's 64 bytes and the block's
-        // 32 tokens 2 KiB of contiguous memory
-        half_t* ot = (half_t*)((char*)t.smem + panel_bytes<TL>()) + (t.wm * TL::WAVES_N + t.wn) * (OT_BYTES / 2);
+        float o[8];
+        FU::pair_block(acc[2 * P][b], acc[2 * P + 1][b], tkb, nd, k, q, uf, vf, o, sacc[sb]);
+        // A[p][nb + 8q .. nb + 8q + 8) in 32-column blocks ([d_ff / 32][T][32], the operand
+        // layout of the down-projection): 16 bytes per lane, four lanes a token's 64 bytes,
+        // the block's 16 tokens 1 KiB of contiguous memory
+        if (p < t.m_end) {
+          half8 o8;
 #pragma unroll
-        for (int qd = 0; qd < 4; ++qd) *(half4*)(ot + ml * OT_LD + 8 * qd + 4 * h) = to_half4(o, qd);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int tr = (t.lane >> 2) + 16 * i, cq = t.lane & 3;
-          const half8 v8 = *(const half8*)(ot + tr * OT_LD + cq * 8);
-          const int p = t.m0 + t.wm * TL::WM + b * 32 + tr;
-          if (p < t.m_end) *(half8*)(A + ((size_t)(nb >> 5) * T + p) * 32 + cq * 8) = v8;
+          for (int i = 0; i < 8; ++i) o8[i] = (half_t)o[i];
+          *(half8*)(A + ((size_t)(nb >> 5) * T + p) * 32 + 8 * q) = o8;
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is rewritten by the next block
       }
-      // the two wavefronts that share these tokens (wn = 0, 1) add their partial s through
-      // LDS, one expert slot at a time, in the patches of the output transposition (free
-      // once every wavefront has left the loop above); wn = 0 stores the tile's partial
-      float* xs = (float*)((char*)t.smem + panel_bytes<TL>()) + t.wm * (16 * 64);
-      static_assert(TL::NWAVES * OT_BYTES >= TL::WAVES_M * 16 * 64 * 4, "exchange area");
+      if (!BATCH) {
+        // the two wavefronts that share these tokens (wn = 0, 1) add their partial s through
+        // LDS, one accumulator at a time; wn = 0 stores the tile's partial
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+          if (j >= k) continue;
+#pragma unroll
+          for (int s2 = 0; s2 < FU::NSP; ++s2) {
+            if (t.wn == 1) {
+#pragma unroll
+              for (int v = 0; v < 4; ++v) xs[v * 64 + t.lane] = sacc[0][j][s2][v];
+            }
+            __syncthreads();
+            if (t.wn == 0) {
+#pragma unroll
+              for (int v = 0; v < 4; ++v) sacc[0][j][s2][v] += xs[v * 64 + t.lane];
+            }
+            __syncthreads();
+          }
+        }
+        if (t.wn == 0) FU::store_s(tkb, sacc[0], spart + (size_t)t.n_tile * T * k * R, k, q);
+      }
+    }
+    if (BATCH) {
+      // all token blocks at once: wn = 1 writes its partials, wn = 0 adds them and stores
       __syncthreads();
+      if (t.wn == 1) {
 #pragma unroll
-      for (int j = 0; j < KMAX; ++j) {
-        if (j >= k) continue;
-        if (t.wn == 1) {
+        for (int b = 0; b < NSB; ++b)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) xs[v * 64 + t.lane] = sacc[j][v];
-        }
-        __syncthreads();
-        if (t.wn == 0) {
+          for (int j = 0; j < KMAX; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sacc[j][v] += xs[v * 64 + t.lane];
-        }
-        __syncthreads();
+            for (int s2 = 0; s2 < FU::NSP; ++s2)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) xs[(((b * KMAX + j) * FU::NSP + s2) * 4 + v) * 64 + t.lane] = sacc[b][j][s2][v];
       }
-      if (t.wn == 0) FU::store_s(tk[b], sacc, spart + (size_t)t.n_tile * T * k * R, k, h);
+      __syncthreads();
+      if (t.wn == 0) {
+#pragma unroll
+        for (int b = 0; b < NSB; ++b) {
+#pragma unroll
+          for (int j = 0; j < KMAX; ++j)
+#pragma unroll
+            for (int s2 = 0; s2 < FU::NSP; ++s2)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) sacc[b][j][s2][v] += xs[(((b * KMAX + j) * FU::NSP + s2) * 4 + v) * 64 + t.lane];
+          FU::store_s(tk[PRELOAD ? b : 0], sacc[b], spart + (size_t)t.n_tile * T * k * R, k, q);
+        }
+      }
     }
   }
 };
