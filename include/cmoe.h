@@ -92,17 +92,21 @@ typedef struct cmoe_handle cmoe_handle;
 int cmoe_create(const cmoe_config *cfg, cmoe_handle **out);
 int cmoe_destroy(cmoe_handle *h);
 
-/* One-time re-tiling of the two bases into the layout the matrix-core kernels load
- * fastest (weights are static across forward calls, Sec. 3.4; the canonical layouts above
- * stay the interface).  packed holds, per cluster, W1_base as [d/32][d_ff][32] and W2_base as
- * [d_ff/32][d][32]: the 32 contraction elements of consecutive rows are contiguous, so one
- * direct-to-LDS load instruction fetches 1 KiB of contiguous memory instead of 16 pieces a
- * row apart.  cmoe_packed_bytes = 4 * G * d * d_ff (0 for a bad handle); packed is a
- * caller-owned device buffer, 256-byte aligned.  Set cmoe_weights.packed to it and the
- * calls that take more than 256 tokens read the bases from it (cmoe_ffn_forward,
- * cmoe_forward, cmoe_forward_multi, cmoe_backward); with fewer tokens, or packed == NULL,
- * the canonical arrays are read.  The canonical arrays must stay valid either way, and the
- * caller packs again after changing a base.  Packing reads every cluster's bases. */
+/* One-time preparation of the stored parameters for the matrix-core kernels (weights are
+ * static across forward calls, Sec. 3.4; the canonical layouts above stay the interface).
+ * packed holds, per cluster, W1_base as [d/32][d_ff][32] and W2_base as [d_ff/32][d][32]: the 32
+ * contraction elements of consecutive rows are contiguous, so one direct-to-LDS load
+ * instruction fetches 1 KiB of contiguous memory instead of 16 pieces a row apart; and the
+ * FP16 operand panels of the four INT4 factor tensors of every cluster (2 * KRp * (d + d_ff)
+ * FP16 values per cluster, KRp = K*r rounded up to 32), so that no call dequantises them
+ * again.  cmoe_packed_bytes is the size of that buffer (about 4*G*d*d_ff + 4*G*KRp*(d + d_ff)
+ * bytes; 0 for a bad handle); packed is a caller-owned device buffer, 256-byte aligned.  Set
+ * cmoe_weights.packed to it and the calls that take more than 256 tokens read bases and
+ * factors from it (cmoe_ffn_forward, cmoe_combine, cmoe_forward, cmoe_forward_multi; the
+ * bases also cmoe_backward); with fewer tokens, or packed == NULL, the canonical arrays are
+ * read (and the factors of the clusters that received tokens dequantised per call).  The
+ * canonical arrays must stay valid either way, and the caller packs again after changing a
+ * base or a factor.  Packing reads every cluster's bases and factors. */
 size_t cmoe_packed_bytes(const cmoe_handle *h);
 int cmoe_pack_weights(cmoe_handle *h, const cmoe_weights *w, void *packed, size_t packed_bytes,
                       void *stream);

@@ -276,9 +276,13 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   const cmoe_dims& dm = h->dm;
   cmoe_ws_layout L = cmoe_layout(dm, T);
   char* ws = (char*)workspace;
-  half_t* v1cat = (half_t*)(ws + L.v1cat);
-  half_t* u1t = (half_t*)(ws + L.u1t);
-  half_t* v2p = (half_t*)(ws + L.v2p);
+  // factor panels: from the packed buffer when there is one, else dequantised per call
+  const bool pk = w->packed != nullptr;
+  const cmoe_packed_layout PL = cmoe_packed(dm);
+  const char* pkb = (const char*)w->packed;
+  half_t* v1cat = pk ? (half_t*)(pkb + PL.v1cat) : (half_t*)(ws + L.v1cat);
+  half_t* u1t = pk ? (half_t*)(pkb + PL.u1t) : (half_t*)(ws + L.u1t);
+  half_t* v2p = pk ? (half_t*)(pkb + PL.v2p) : (half_t*)(ws + L.v2p);
   half_t* t1ext = (half_t*)(ws + L.t1ext);
   half_t* a = (half_t*)(ws + L.a);
   float* spart = (float*)(ws + L.spart);
@@ -312,8 +316,8 @@ static int ffn_impl(cmoe_handle* h, const cmoe_weights* w, const cmoe_f16* x, in
   const int* rowmap = rm;
   // when the combine is fused into the down-projection its U2 panel joins the same launch
   const bool fuse = y_fused != nullptr && dm.KRp <= 128 && weights_combine_ok(w);
-  half_t* u2t = fuse ? (half_t*)(ws + L.u2t) : nullptr;
-  CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, u2t, st));
+  half_t* u2t = !fuse ? nullptr : pk ? (half_t*)(pkb + PL.u2t) : (half_t*)(ws + L.u2t);
+  if (!pk) CMOE_LAUNCH(TS_DEQUANT, launch_dequant_ffn(dm, *w, offsets, v1cat, u1t, v2p, u2t, st));
   CMOE_LAUNCH(TS_T1, launch_t1(dm, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, v1cat, t1ext, st));
   CMOE_LAUNCH(TS_GEMM1, launch_gemm1(dm, *w, (const half_t*)x, x_div, T, rperm, offsets, expert_idx, gate, u1t, v2p,
                                      t1ext, a, spart, st));
@@ -349,7 +353,10 @@ extern "C" int cmoe_combine(cmoe_handle* h, const cmoe_weights* w, const cmoe_f1
     return CMOE_OK;
   }
   half_t* u2t = (half_t*)((char*)workspace + L.u2t);
-  CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
+  if (w->packed != nullptr)
+    u2t = (half_t*)((const char*)w->packed + cmoe_packed(dm).u2t);
+  else
+    CMOE_LAUNCH(TS_DEQUANT, launch_dequant_u2(dm, *w, offsets, u2t, st));
   CMOE_LAUNCH(TS_COMBINE, launch_combine(dm, u2t, (const half_t*)y_base_sorted, s_down, perm, offsets, expert_idx,
                                          gate, T, (half_t*)y, st));
   return CMOE_OK;
@@ -448,12 +455,15 @@ extern "C" int cmoe_route_stats(cmoe_handle* h, const cmoe_f16* x, int32_t T, co
 
 extern "C" size_t cmoe_packed_bytes(const cmoe_handle* h) {
   if (!handle_ok(h)) return 0;
-  return (size_t)4 * h->dm.G * h->dm.d * h->dm.d_ff;
+  return cmoe_packed(h->dm).total;
 }
 
 extern "C" int cmoe_pack_weights(cmoe_handle* h, const cmoe_weights* w, void* packed, size_t packed_bytes,
                                  void* stream) {
   if (!handle_ok(h) || w == nullptr || !ptr_ok(w->w1_base) || !ptr_ok(w->w2_base)) return CMOE_ERR_INVALID_ARG;
+  if (!ptr_ok(w->v1_q) || !ptr_ok(w->u1_q) || !ptr_ok(w->v2_q) || !ptr_ok(w->u2_q) || !ptr_ok(w->v1_s) ||
+      !ptr_ok(w->u1_s) || !ptr_ok(w->v2_s) || !ptr_ok(w->u2_s))
+    return CMOE_ERR_INVALID_ARG;
   if (packed == nullptr || (reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return CMOE_ERR_INVALID_ARG;
   if (packed_bytes < cmoe_packed_bytes(h)) return CMOE_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;

@@ -1,7 +1,8 @@
 // INT4 group-wise factors (Sec. 3.4) -> FP16 operand panels in the layouts the matrix-core
 // kernels consume.  value = scale[n / q] * code[n]; code = two's-complement nibble,
 // even n in the low nibble of byte n / 2.  Clusters that received no token are skipped,
-// so their stored factors are never read.
+// so their stored factors are never read (offsets == NULL: every cluster, for the one-time
+// packing of the weights).
 #include "cmoe_internal.h"
 
 namespace {
@@ -18,7 +19,7 @@ template <bool PERMUTE16>
 __device__ __forceinline__ void dequant_rows(int bx, int kk, int c, const uint8_t* __restrict__ qv,
                                              const half_t* __restrict__ sv, int L, int q, int K, int r, int KRp,
                                              const int* __restrict__ offsets, half_t* __restrict__ out) {
-  if (offsets[c + 1] == offsets[c]) return;
+  if (offsets != nullptr && offsets[c + 1] == offsets[c]) return;
   const int n8 = (bx * 256 + threadIdx.x) * 8;  // 8 consecutive output positions
   if (n8 >= L) return;
   half8 o = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -64,7 +65,7 @@ __device__ __forceinline__ void dequant_transpose(int bx, int c, const uint8_t* 
                                                   const half_t* __restrict__ sv, int L, int q, int K, int r, int KRp,
                                                   const int* __restrict__ offsets, half_t* __restrict__ out,
                                                   half_t* __restrict__ tile) {
-  if (offsets[c + 1] == offsets[c]) return;
+  if (offsets != nullptr && offsets[c + 1] == offsets[c]) return;
   const int n0 = bx * DT_N, ld = KRp + 8, KR = K * r;
   // two threads per rank row: 32 n (16 code bytes) each
   for (int idx = threadIdx.x; idx < KRp * 2; idx += 256) {

@@ -920,6 +920,9 @@ __global__ __launch_bounds__(CB_WAVES * 64) void combine_kernel(
 // per workgroup, four wavefronts side by side along the tokens (each 128 x 64), two
 // workgroups per CU.
 using TileMain = Tile<128, 256, 1, 4, 3, 2, false, 8, 8>;
+// The router's product (all router rows in one 128-row tile): 128-token tiles, twice the
+// workgroups of TileMain for this short, x-streaming launch (64-token tiles measured slower).
+using TileRoute = Tile<128, 128, 1, 4, 3, 2, false, 8, 8>;
 // The two big products: 256 x 256 per workgroup, eight wavefronts (2 x 4, each 128 x 64) in
 // ping-pong, one workgroup per CU: half the operand bytes per flop of the tile above.
 using TileBig = Tile<256, 256, 2, 4, 4, 1, true, 4, 8>;
@@ -1028,8 +1031,8 @@ hipError_t launch_t1(const cmoe_dims& dm, const half_t* x, int x_div, int T, con
 // [d_ff/32][d][32]) the weight operand is read from it: row stride 32, block stride rows * 32.
 static void use_packed_base(GemmArgs& g, const cmoe_dims& dm, const cmoe_weights& w, bool second) {
   if (w.packed == nullptr) return;
-  const size_t mat = (size_t)dm.d * dm.d_ff;
-  g.W = (const half_t*)w.packed + (second ? mat * dm.G : 0);
+  const cmoe_packed_layout PL = cmoe_packed(dm);
+  g.W = (const half_t*)((const char*)w.packed + (second ? PL.w2 : PL.w1));
   g.ldw = 32;
   g.kstep_w = (long)(second ? dm.d : dm.d_ff) * 32;
 }
@@ -1091,8 +1094,7 @@ hipError_t launch_combine(const cmoe_dims& dm, const half_t* u2t, const half_t* 
 // Matrix-core router for large T (G + G*K logits per token fit one 128-row tile).
 hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int* cluster_id,
                              int* expert_idx, float* gate, hipStream_t st) {
-  // 128-token tiles: twice the workgroups of TileMain for this short, x-streaming launch
-  using TL = Tile<128, 128, 1, 4, 3, 2, false, 8, 8>;
+  using TL = TileRoute;
   const int rows = dm.G + dm.G * dm.K;
   GemmArgs g{(const half_t*)w.router_cluster, 0, dm.d, rows, x, dm.d, nullptr, dm.d, nullptr, 1, 1, 0, 0,
              (const half_t*)w.router_expert, dm.G, T};
@@ -1109,7 +1111,7 @@ hipError_t launch_route_mfma(const cmoe_dims& dm, const cmoe_weights& w, const h
 hipError_t launch_route_multi_mfma(const cmoe_dims& dm, const cmoe_weights& w, const half_t* x, int T, int top_g,
                                    float temperature, int scale, int* cluster_id, int* expert_idx, float* gate,
                                    hipStream_t st) {
-  using TL = Tile<128, 128, 1, 4, 3, 2, false, 8, 8>;
+  using TL = TileRoute;
   const int rows = dm.G + dm.G * dm.K;
   GemmArgs ga{(const half_t*)w.router_cluster, 0, dm.d, rows, x, dm.d, nullptr, dm.d, nullptr, 1, 1, 0, 0,
               (const half_t*)w.router_expert, dm.G, T};
@@ -1182,10 +1184,16 @@ __global__ __launch_bounds__(256) void pack_base_kernel(const half_t* __restrict
 }
 
 hipError_t launch_pack_bases(const cmoe_dims& dm, const cmoe_weights& w, half_t* packed, hipStream_t st) {
-  const size_t mat = (size_t)dm.d * dm.d_ff;
+  const cmoe_packed_layout PL = cmoe_packed(dm);
+  char* pk = (char*)packed;
   hipLaunchKernelGGL(pack_base_kernel, dim3((dm.d_ff + 63) / 64, 4, dm.G), dim3(256), 0, st, (const half_t*)w.w1_base,
-                     dm.d_ff, dm.d, packed);
+                     dm.d_ff, dm.d, (half_t*)(pk + PL.w1));
   hipLaunchKernelGGL(pack_base_kernel, dim3((dm.d + 63) / 64, 4, dm.G), dim3(256), 0, st, (const half_t*)w.w2_base,
-                     dm.d, dm.d_ff, packed + mat * dm.G);
-  return hipGetLastError();
+                     dm.d, dm.d_ff, (half_t*)(pk + PL.w2));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // the FP16 panels of all clusters' factors (Sec. 3.4: INT4 is the stored form; the panels are
+  // what the matrix cores read)
+  return launch_dequant_ffn(dm, w, nullptr, (half_t*)(pk + PL.v1cat), (half_t*)(pk + PL.u1t), (half_t*)(pk + PL.v2p),
+                            (half_t*)(pk + PL.u2t), st);
 }

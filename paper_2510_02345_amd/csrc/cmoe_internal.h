@@ -72,6 +72,32 @@ struct cmoe_ws_layout {
   size_t total;
 };
 
+// The caller's buffer filled by cmoe_pack_weights (byte offsets, 256-byte aligned): the two
+// bases in 32-column blocks, then the FP16 operand panels of the four INT4 factors of every
+// cluster (the layouts of v1cat / u1t / v2p / u2t above), so that a forward call neither
+// re-tiles nor dequantises anything that does not change between calls.
+struct cmoe_packed_layout {
+  size_t w1, w2, v1cat, u1t, v2p, u2t, total;
+};
+inline cmoe_packed_layout cmoe_packed(const cmoe_dims& dm) {
+  cmoe_packed_layout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = (off + bytes + 255) / 256 * 256;
+    return at;
+  };
+  const size_t mat = sizeof(half_t) * dm.G * (size_t)dm.d * dm.d_ff;
+  L.w1 = take(mat);
+  L.w2 = take(mat);
+  L.v1cat = take(sizeof(half_t) * dm.G * (size_t)dm.KRp * dm.d);
+  L.u1t = take(sizeof(half_t) * dm.G * (size_t)dm.d_ff * dm.KRp);
+  L.v2p = take(sizeof(half_t) * dm.G * (size_t)dm.KRp * dm.d_ff);
+  L.u2t = take(sizeof(half_t) * dm.G * (size_t)dm.d * dm.KRp);
+  L.total = off;
+  return L;
+}
+
 static const int PERMUTE_BLOCK = 1024;  // tokens per workgroup in the permutation kernels
 static const int G1_BN = 256;           // rows of d_ff per workgroup tile (= per s partial) in the fused up-projection
 static const int SKINNY_T = 256;        // at most this many tokens: weight-streaming kernels

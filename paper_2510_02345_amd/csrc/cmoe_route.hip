@@ -260,26 +260,38 @@ __global__ __launch_bounds__(PERMUTE_BLOCK) void permute_hist_kernel(const int* 
 }
 
 // Pass 2: one workgroup.  offsets = exclusive scan of the cluster totals; each block's
-// count is replaced by the first sorted row that block may write for that cluster.
-__global__ __launch_bounds__(64) void permute_scan_kernel(int n_blocks, int G, int* __restrict__ blk_counts,
-                                                          int* __restrict__ offsets) {
+// count is replaced by the first sorted row that block may write for that cluster.  The
+// blocks are cut into SCAN_SEG segments, one wavefront per segment and one lane per cluster:
+// segment totals first (independent loads), then the walk inside each segment.
+constexpr int SCAN_SEG = 16;
+__global__ __launch_bounds__(SCAN_SEG * 64) void permute_scan_kernel(int n_blocks, int G,
+                                                                     int* __restrict__ blk_counts,
+                                                                     int* __restrict__ offsets) {
+  __shared__ int segsum[SCAN_SEG][64];
   __shared__ int total[64];
-  int g = threadIdx.x;
-  if (g < G) {
+  const int g = threadIdx.x & 63, seg = threadIdx.x >> 6;
+  const int per = (n_blocks + SCAN_SEG - 1) / SCAN_SEG;
+  const int b0 = min(seg * per, n_blocks), b1 = min(b0 + per, n_blocks);
+  int sum = 0;
+  if (g < G)
+    for (int b = b0; b < b1; ++b) sum += blk_counts[(size_t)b * G + g];
+  segsum[seg][g] = sum;
+  __syncthreads();
+  if (seg == 0) {
     int run = 0;
-    for (int b = 0; b < n_blocks; ++b) {
-      int v = blk_counts[(size_t)b * G + g];
-      blk_counts[(size_t)b * G + g] = run;
+    for (int s2 = 0; s2 < SCAN_SEG; ++s2) {   // exclusive over the segments of cluster g
+      const int v = segsum[s2][g];
+      segsum[s2][g] = run;
       run += v;
     }
-    total[g] = run;
+    total[g] = g < G ? run : 0;
   }
   __syncthreads();
-  if (g == 0) {
+  if (threadIdx.x == 0) {
     int run = 0;
     for (int c = 0; c < G; ++c) {
       offsets[c] = run;
-      int v = total[c];
+      const int v = total[c];
       total[c] = run;
       run += v;
     }
@@ -287,8 +299,12 @@ __global__ __launch_bounds__(64) void permute_scan_kernel(int n_blocks, int G, i
   }
   __syncthreads();
   if (g < G) {
-    int base = total[g];
-    for (int b = 0; b < n_blocks; ++b) blk_counts[(size_t)b * G + g] += base;
+    int run = total[g] + segsum[seg][g];
+    for (int b = b0; b < b1; ++b) {
+      const int v = blk_counts[(size_t)b * G + g];
+      blk_counts[(size_t)b * G + g] = run;
+      run += v;
+    }
   }
 }
 
@@ -597,7 +613,7 @@ hipError_t launch_permute_bins(int bins, const int* cluster_id, int T, int* perm
   int n_blocks = (T + PERMUTE_BLOCK - 1) / PERMUTE_BLOCK;
   hipLaunchKernelGGL(permute_hist_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
                      blk_counts);
-  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(64), 0, st, n_blocks, dm.G, blk_counts, offsets);
+  hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(SCAN_SEG * 64), 0, st, n_blocks, dm.G, blk_counts, offsets);
   hipLaunchKernelGGL(permute_rank_kernel, dim3(n_blocks), dim3(PERMUTE_BLOCK), 0, st, cluster_id, T, dm.G,
                      blk_counts, perm, inv_perm);
   return hipGetLastError();

@@ -194,7 +194,8 @@ def test_pack_weights_rejects_bad_arguments_without_touching_the_gpu():
     w2 = B.Weights(*([fake] * 13))
     assert w2.packed is None                                    # canonical arrays only by default
     need = L.cmoe_packed_bytes(h)
-    assert need == 4 * 2 * 768 * 3072 and L.cmoe_packed_bytes(None) == 0
+    # both bases in FP16 blocks plus the FP16 panels of the four factor tensors (K*r = 32 rank rows per cluster)
+    assert need == 4 * 2 * 768 * 3072 + 2 * 2 * 32 * 2 * (768 + 3072) and L.cmoe_packed_bytes(None) == 0
     assert L.cmoe_pack_weights(h, C.byref(w2), None, need, None) == B.ERR_INVALID_ARG
     assert L.cmoe_pack_weights(h, C.byref(w2), 0x1010, need, None) == B.ERR_INVALID_ARG      # not 256-byte aligned
     assert L.cmoe_pack_weights(h, C.byref(w2), fake, need - 1, None) == B.ERR_WORKSPACE
@@ -202,6 +203,9 @@ def test_pack_weights_rejects_bad_arguments_without_touching_the_gpu():
     nobase = B.Weights(*([fake] * 13))
     nobase.w2_base = None
     assert L.cmoe_pack_weights(h, C.byref(nobase), fake, need, None) == B.ERR_INVALID_ARG
+    nofactor = B.Weights(*([fake] * 13))
+    nofactor.u2_s = None
+    assert L.cmoe_pack_weights(h, C.byref(nofactor), fake, need, None) == B.ERR_INVALID_ARG
     # a misaligned packed pointer is refused by the calls that would read it
     bad = B.Weights(*([fake] * 13))
     bad.packed = 0x1008
