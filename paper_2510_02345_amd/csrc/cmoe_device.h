@@ -60,6 +60,15 @@ __device__ __forceinline__ int pi_row(int rho) {
   return (rho & ~31) | ((rho & 12) << 1) | ((rho & 16) >> 2) | (rho & 3);
 }
 
+// Position (XOR mask over the four 16-byte chunks of a 64-byte operand-tile row) at which
+// tile row `row` keeps its chunks.  A 16x16x32 fragment read has lane l fetch 16 bytes of row
+// l % 16, chunk l / 16; the LDS serves such a read in groups of sixteen lanes
+// {0-3, 12-15, 20-23, 24-27} and {4-7, 8-11, 16-19, 28-31} (and the same plus 32), so the
+// four row quads of one group need four different chunk positions: quads 0,1,2,3 use
+// masks 0,3,2,1.  Measured on gfx950: the plain mask (row >> 2) & 3 serves a 32-row fragment
+// read without conflicts but gives two-way conflicts on every 16-row read.
+__device__ __forceinline__ int swz(int row) { return ((row >> 2) & 3) ^ ((row >> 1) & 2); }
+
 __device__ __forceinline__ half8 pack_half8(const float4v& lo, const float4v& hi) {
   half8 o;
   o[0] = (half_t)lo[0]; o[1] = (half_t)lo[1]; o[2] = (half_t)lo[2]; o[3] = (half_t)lo[3];

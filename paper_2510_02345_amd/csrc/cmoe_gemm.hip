@@ -154,7 +154,7 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
   for (int i = 0; i < TL::PER_WAVE; ++i) {
     const int ii = wave * TL::PER_WAVE + i;
     const int row = ii * 16 + (lane >> 2), pos = lane & 3;
-    const int chunk = pos ^ ((row >> 2) & 3);
+    const int chunk = pos ^ swz(row);
     const half_t* base;
     if (row < TL::BN) {
       const int n = min(n0 + pi_row(row), g.N - 1);
@@ -185,12 +185,12 @@ __global__ __launch_bounds__(TL::NT, TL::OCC) void gemm_nt_kernel(GemmArgs g, Ep
 #pragma unroll
   for (int a = 0; a < TL::NA; ++a) {
     const int row = wn * TL::WN + a * 16 + t16;
-    offa[a] = row * TL::ROWB + ((q ^ ((row >> 2) & 3)) << 4);
+    offa[a] = row * TL::ROWB + ((q ^ swz(row)) << 4);
   }
 #pragma unroll
   for (int b = 0; b < TL::MT; ++b) {
     const int row = TL::BN + wm * TL::WM + b * 16 + t16;
-    offb[b] = row * TL::ROWB + ((q ^ ((row >> 2) & 3)) << 4);
+    offb[b] = row * TL::ROWB + ((q ^ swz(row)) << 4);
   }
 
   // 16-token blocks of this wavefront that hold at least one real token (a ragged last
