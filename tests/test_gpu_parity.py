@@ -131,6 +131,18 @@ def test_small_shapes_every_entry_point(cfg):
     _stepwise(cfg)
 
 
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[7]], ids=lambda c: c.name)
+def test_pre_activations_far_outside_the_gelu_polynomial_range(cfg):
+    # x scaled by 6: the pre-activations have a standard deviation of about 6, so most of them
+    # lie beyond the interval on which the kernels evaluate Phi by a polynomial, on both sides
+    # (the logits and their gaps scale with x, the routing decisions stay the generator's)
+    w = ci.generate(cfg)
+    w["x"] = (w["x"].astype(np.float32) * 6.0).astype(np.float16)
+    h = w["w1_base"][0].astype(np.float64) @ w["x"][: min(cfg.T, 64)].astype(np.float64).T
+    assert np.mean(np.abs(h) > 3.75) > 0.4
+    _stepwise(cfg, w=w)
+
+
 @pytest.mark.parametrize("cfg", [SMALL[0], SMALL[9], SMALL[12]], ids=lambda c: c.name)
 def test_canonical_bases_without_the_packed_copy(cfg):
     # the layer reads the caller's row-major bases when no packed copy is given
