@@ -60,7 +60,7 @@ def kernel_work(cfg, kernel, clusters_hit, experts_hit):
     return flops, byts
 
 
-def run_config(cfg, steps, warmup, want_stats=False):
+def run_config(cfg, steps, warmup, want_stats=False, pack=True):
     import numpy as np
     import torch
 
@@ -68,15 +68,20 @@ def run_config(cfg, steps, warmup, want_stats=False):
     import paper_2510_02345_amd as cm
 
     w = ci.generate(cfg)
-    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T, device="cuda:0")
+    layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T, device="cuda:0", pack=pack)
     x = torch.from_numpy(w["x"]).to("cuda:0")
     # the one-time re-tiling of the bases (done by the constructor, weights being static across
-    # steps) timed on its own; it is not part of a step
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    layer.pack()
-    torch.cuda.synchronize()
-    pack_ms = (time.perf_counter() - t0) * 1e3
+    # steps) timed on its own; it is not part of a step.  The canonical base arrays are freed
+    # afterwards: every kernel reads the packed buffer, the only resident copy of the bases.
+    pack_ms = 0.0
+    if pack:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        layer.pack()
+        torch.cuda.synchronize()
+        pack_ms = (time.perf_counter() - t0) * 1e3
+        layer.drop_canonical_bases()
+    resident = layer.resident_weight_bytes()
     out = layer.forward_buffers(cfg.T)
     for _ in range(warmup):
         layer.forward(x, out)
@@ -156,7 +161,7 @@ def run_config(cfg, steps, warmup, want_stats=False):
     experts_hit = int(len(np.unique(eidx)))
     layer.close()
     return dict(ms_per_step=ms_per_step, ms_median=ms_median, ms_min=ms_min, per_kernel_ms=per_kernel, clusters_hit=clusters_hit,
-                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms, backward_ms=backward_ms, pack_ms=pack_ms)
+                experts_hit=experts_hit, inputs=w, stats_ms=stats_ms, multi_ms=multi_ms, backward_ms=backward_ms, pack_ms=pack_ms, resident=resident)
 
 
 def roofline(cfg, res, bound, traffic_table):
@@ -259,6 +264,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=4096)
     ap.add_argument("--no-calibration", action="store_true",
                     help="skip the matrix-core calibration leg (sustained MFMA rate with no memory traffic)")
+    ap.add_argument("--no-pack", action="store_true",
+                    help="read the canonical row-major bases instead of the packed copy (and dequantise the factor "
+                         "panels per step above 256 tokens)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one 256 MiB device-to-device copy (a kernel of known traffic, to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -288,7 +296,7 @@ def main():
         del src, dst
 
     cfg = ci.config(args.config)
-    res = run_config(cfg, args.steps, args.warmup, want_stats=not args.no_variants)
+    res = run_config(cfg, args.steps, args.warmup, want_stats=not args.no_variants, pack=not args.no_pack)
     bound = "hbm" if cfg.name == "C4" else "mfma"
     line = {
         "metric": "tokens/s through clustered-MoE FFN layer (1 GPU)",
@@ -304,6 +312,7 @@ def main():
                    "clusters_hit": res["clusters_hit"], "experts_hit": res["experts_hit"]},
         "roofline": roofline(cfg, res, bound, traffic_table),
         "pack_weights_ms": round(res["pack_ms"], 4),
+        "resident_weight_MB": round(res["resident"] / 1e6, 1),
     }
     if res["stats_ms"]:
         _, sb = kernel_work(cfg, "route_stats", res["clusters_hit"], res["experts_hit"])
@@ -337,7 +346,7 @@ def main():
             "value": round(tf, 1), "unit": "TFLOP/s", "shader_clock_GHz": round(ghz, 3),
             "frac_of_peak": round(tf / PEAK_F16_TFLOPS, 4),
             "dominant_kernel_vs_sustained": round(rf["achieved"] / tf, 4) if rf["bound"] == "mfma" else None,
-            "note": "cmoe_calibrate_mfma in this run: the grouped products' inner schedule (32 x 32 x 16 FP16 MFMAs, "
+            "note": "cmoe_calibrate_mfma in this run: the grouped products' inner schedule (16 x 16 x 32 FP16 MFMAs, "
                     "fragments of random mantissas read from LDS, two wavefront sets) with no global traffic and "
                     "every matrix-core issue slot used on all 256 CUs; the rate is what the power management "
                     "sustains, the ceiling of any FP16 product on this box. roofline.frac stays against the "
@@ -347,7 +356,7 @@ def main():
     del res
     if not args.no_weight_bound and cfg.name != "C4":
         c4 = ci.config(4)
-        r4 = run_config(c4, max(args.steps, 20), max(args.warmup, 5))
+        r4 = run_config(c4, max(args.steps, 20), max(args.warmup, 5), pack=not args.no_pack)
         line["weight_bound"] = {
             "workload": f"{c4.name}: T={c4.T} d={c4.d} d_ff={c4.d_ff} G={c4.G} K={c4.K} r={c4.r} top_k={c4.k} q={c4.q}",
             "value": round(c4.T / (r4["ms_per_step"] * 1e-3), 1), "unit": "tokens/s",

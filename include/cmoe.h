@@ -76,8 +76,8 @@ typedef struct {
   const cmoe_f16 *router_cluster; /* [G][d]       group prototypes u_g (Sec. 3.3)          */
   const cmoe_f16 *router_expert;  /* [G*K][d]     expert routing vectors v_i               */
   const float *cluster_bias;      /* [G] or NULL  added to z_g; NULL = the paper's router  */
-  const cmoe_f16 *w1_base;        /* [G][d_ff][d]                                          */
-  const cmoe_f16 *w2_base;        /* [G][d][d_ff]                                          */
+  const cmoe_f16 *w1_base;        /* [G][d_ff][d]   (may be NULL when packed is set)       */
+  const cmoe_f16 *w2_base;        /* [G][d][d_ff]   (may be NULL when packed is set)       */
   const uint8_t *v1_q, *u1_q, *v2_q, *u2_q; /* [G*K][r][L/2]                                */
   const cmoe_f16 *v1_s, *u1_s, *v2_s, *u2_s; /* [G*K][r][L/q_group]                         */
   const void *packed; /* NULL, or the buffer cmoe_pack_weights filled from THESE bases (below)  */
@@ -101,12 +101,15 @@ int cmoe_destroy(cmoe_handle *h);
  * FP16 values per cluster, KRp = K*r rounded up to 32), so that no call dequantises them
  * again.  cmoe_packed_bytes is the size of that buffer (about 4*G*d*d_ff + 4*G*KRp*(d + d_ff)
  * bytes; 0 for a bad handle); packed is a caller-owned device buffer, 256-byte aligned.  Set
- * cmoe_weights.packed to it and the calls that take more than 256 tokens read bases and
- * factors from it (cmoe_ffn_forward, cmoe_combine, cmoe_forward, cmoe_forward_multi; the
- * bases also cmoe_backward); with fewer tokens, or packed == NULL, the canonical arrays are
- * read (and the factors of the clusters that received tokens dequantised per call).  The
- * canonical arrays must stay valid either way, and the caller packs again after changing a
- * base or a factor.  Packing reads every cluster's bases and factors. */
+ * cmoe_weights.packed to it and every call reads the bases from it, whatever the token count
+ * (cmoe_ffn_forward, cmoe_forward, cmoe_forward_multi, cmoe_backward); the calls that take
+ * more than 256 tokens also read the factor panels from it (cmoe_combine too), the calls
+ * with fewer tokens decode the INT4 factors on the fly.  With packed == NULL the canonical
+ * arrays are read (and, above 256 tokens, the factors of the clusters that received tokens
+ * dequantised per call).  Once packed is set, w1_base and w2_base may be NULL: the packed
+ * buffer is then the only resident copy of the bases (the INT4 factor tensors and the
+ * routers must stay valid).  The caller packs again after changing a base or a factor.
+ * Packing reads every cluster's canonical bases and factors. */
 size_t cmoe_packed_bytes(const cmoe_handle *h);
 int cmoe_pack_weights(cmoe_handle *h, const cmoe_weights *w, void *packed, size_t packed_bytes,
                       void *stream);
@@ -312,10 +315,10 @@ int cmoe_timing_read(cmoe_handle *h, double *ms_sum, int32_t *count, int32_t n_m
 const char *cmoe_timing_name(int32_t slot);
 
 /* Benchmark calibration: n_workgroups workgroups (one per compute unit: 256) run iters
- * iterations of the grouped products' inner schedule - 32 FP16 matrix-core instructions
- * (32 x 32 x 16) per iteration and SIMD on operands of random mantissas read from LDS - with no
+ * iterations of the grouped products' inner schedule - 64 FP16 matrix-core instructions
+ * (16 x 16 x 32) per iteration and SIMD on operands of random mantissas read from LDS - with no
  * global memory traffic, so that every matrix-core issue slot is used.  FLOPs = n_workgroups *
- * 8 * iters * 16 * 32768; the rate over the call's duration is what the power management lets
+ * 8 * iters * 32 * 16384; the rate over the call's duration is what the power management lets
  * the matrix cores sustain on this machine.  ticks [2] u64 (device, zeroed by the caller): sums
  * over the workgroups of shader-clock cycles and of constant-rate (100 MHz) ticks spent in the
  * loop; sink [n_workgroups * 512] f32 (device) receives the accumulators.  Not for production

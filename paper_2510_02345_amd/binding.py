@@ -197,7 +197,7 @@ def calibrate_mfma(n_workgroups: int = 256, iters: int = 40000, device="cuda:0")
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)
     t = ticks.cpu().tolist()
-    flops = n_workgroups * 8.0 * iters * 16 * 32768
+    flops = n_workgroups * 8.0 * iters * 32 * 16384
     return flops / (ms * 1e-3) / 1e12, (t[0] / t[1] * 0.1 if t[1] else 0.0)
 
 
@@ -213,8 +213,8 @@ class Layer:
 
     def __init__(self, d, d_ff, G, K, r, top_k, q_group, weights: Dict[str, object], T_max: int, device="cuda:0",
                  pack: bool = True):
-        """pack: make the one-time re-tiled copy of the bases (cmoe_pack_weights) that the calls with
-        more than 256 tokens read; pack=False keeps the canonical arrays only."""
+        """pack: make the one-time re-tiled copy of the bases and FP16 factor panels
+        (cmoe_pack_weights) that every call then reads; pack=False keeps the canonical arrays only."""
         import torch
         self.torch = torch
         self.cfg = Config(d, d_ff, G, K, r, top_k, q_group, 0)
@@ -250,6 +250,22 @@ class Layer:
         self._check(lib().cmoe_pack_weights(self._h, C.byref(self.w), _ptr(self.packed), self.packed.numel(),
                                             self._stream()), "cmoe_pack_weights")
         self.w.packed = _ptr(self.packed)
+
+    def drop_canonical_bases(self):
+        """Free w1_base / w2_base and pass NULL for them from now on: the packed buffer becomes the
+        only resident copy of the bases.  Needs a packed copy; pack() is not possible afterwards."""
+        if self.packed is None:
+            raise ValueError("drop_canonical_bases needs the packed copy (pack=True)")
+        self.torch.cuda.synchronize(self.device)
+        self.w_t["w1_base"] = None
+        self.w_t["w2_base"] = None
+        self.w.w1_base = None
+        self.w.w2_base = None
+
+    def resident_weight_bytes(self):
+        """Device bytes held for the layer's parameters (canonical tensors + packed buffer)."""
+        n = sum(t.numel() * t.element_size() for t in self.w_t.values() if t is not None)
+        return n + (self.packed.numel() if self.packed is not None else 0)
 
     def close(self):
         if self._h:

@@ -193,9 +193,15 @@ static bool weights_route_ok(const cmoe_weights* w) {
   return w != nullptr && ptr_ok(w->router_cluster) && ptr_ok(w->router_expert) &&
          (w->cluster_bias == nullptr || (reinterpret_cast<uintptr_t>(w->cluster_bias) & 3u) == 0);
 }
+// The bases: the canonical arrays, or the re-tiled copy alone (every kernel reads the copy
+// when there is one, so a caller that has packed may drop the canonical arrays).
+static bool bases_ok(const cmoe_weights* w) {
+  if (!aligned16(w->packed) || !aligned16(w->w1_base) || !aligned16(w->w2_base)) return false;
+  return w->packed != nullptr || (w->w1_base != nullptr && w->w2_base != nullptr);
+}
 static bool weights_ffn_ok(const cmoe_weights* w) {
-  return w != nullptr && aligned16(w->packed) && ptr_ok(w->w1_base) && ptr_ok(w->w2_base) && ptr_ok(w->v1_q) && ptr_ok(w->u1_q) &&
-         ptr_ok(w->v2_q) && ptr_ok(w->v1_s) && ptr_ok(w->u1_s) && ptr_ok(w->v2_s);
+  return w != nullptr && bases_ok(w) && ptr_ok(w->v1_q) && ptr_ok(w->u1_q) && ptr_ok(w->v2_q) && ptr_ok(w->v1_s) &&
+         ptr_ok(w->u1_s) && ptr_ok(w->v2_s);
 }
 static bool weights_combine_ok(const cmoe_weights* w) { return w != nullptr && ptr_ok(w->u2_q) && ptr_ok(w->u2_s); }
 

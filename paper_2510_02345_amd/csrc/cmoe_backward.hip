@@ -268,8 +268,10 @@ __global__ __launch_bounds__(256) void bw_drouter_kernel(const half_t* __restric
 // out[z][i][qc] = scale[qc] * src[z][idx[qc]][i] (zero where idx[qc] < 0; idx == NULL: row
 // qc), i < I (a multiple of 16), qc < Npad (a multiple of 64); with blocked != 0 the same
 // values in the layout [Npad / 32][I][32].  Matrices z whose group in
-// skip_off is empty are skipped.  Block (Npad / 64, ceil(I / 64), Z): 64 x 64 tile through LDS.
-__global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restrict__ src, int ld, int I,
+// skip_off is empty are skipped.  src_blk != 0: src[z] is stored as [I / 32][rows][32] with
+// src_blk = rows * 32 (the re-tiled copy of a base matrix) instead of row-major with row
+// stride ld.  Block (Npad / 64, ceil(I / 64), Z): 64 x 64 tile through LDS.
+__global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restrict__ src, int ld, long src_blk, int I,
                                                            const int* __restrict__ idx,
                                                            const float* __restrict__ scale, int Npad,
                                                            const int* __restrict__ skip_off, size_t zstride,
@@ -285,8 +287,11 @@ __global__ __launch_bounds__(256) void bw_transpose_kernel(const half_t* __restr
     const int row = idx != nullptr ? idx[q0 + ql] : q0 + ql;
     half8 a = {0, 0, 0, 0, 0, 0, 0, 0}, b = a;
     if (row >= 0 && i0 + part * 16 < I) {
-      a = *(const half8*)(src + (size_t)row * ld + i0 + part * 16);
-      b = *(const half8*)(src + (size_t)row * ld + i0 + part * 16 + 8);
+      const int col = i0 + part * 16;   // 16 columns inside one 32-column block
+      const half_t* sp = src_blk ? src + (size_t)(col >> 5) * src_blk + (size_t)row * 32 + (col & 31)
+                                 : src + (size_t)row * ld + col;
+      a = *(const half8*)sp;
+      b = *(const half8*)(sp + 8);
       if (scale != nullptr) {
         const float s = scale[q0 + ql];
 #pragma unroll
@@ -499,7 +504,7 @@ inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 void transpose(const half_t* src, int ld, int I, const int* idx, const float* scale, int Npad, half_t* out,
                hipStream_t st) {
-  hipLaunchKernelGGL(bw_transpose_kernel, dim3(Npad / 64, (I + 63) / 64, 1), dim3(256), 0, st, src, ld, I, idx, scale,
+  hipLaunchKernelGGL(bw_transpose_kernel, dim3(Npad / 64, (I + 63) / 64, 1), dim3(256), 0, st, src, ld, 0L, I, idx, scale,
                      Npad, (const int*)nullptr, (size_t)0, 1, out);
 }
 
@@ -577,7 +582,12 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
   int* krc = I(L.krange_c);
   float* dl = out.d_logits ? out.d_logits : F(L.dl);
   const long mat = (long)f * d;
-  const half_t *w1b = (const half_t*)w.w1_base, *w2b = (const half_t*)w.w2_base;
+  // the bases: from the re-tiled copy when the caller keeps one (the canonical arrays may
+  // then be absent), else the canonical arrays
+  const bool pk = w.packed != nullptr;
+  const cmoe_packed_layout PL = cmoe_packed(dm);
+  const half_t* w1b = pk ? (const half_t*)((const char*)w.packed + PL.w1) : (const half_t*)w.w1_base;
+  const half_t* w2b = pk ? (const half_t*)((const char*)w.packed + PL.w2) : (const half_t*)w.w2_base;
   hipError_t err;
 #define BW_CHECK(call)                    \
   do {                                    \
@@ -635,15 +645,15 @@ hipError_t launch_backward(const cmoe_dims& dm, const cmoe_weights& w, const hal
     hipLaunchKernelGGL(bw_panel_kernel, dim3((f + 255) / 256, E), dim3(256), 0, st, (const uint8_t*)w.v2_q,
                        (const half_t*)w.v2_s, f, q, r, offe, H(L.v2p));
     // w1bt = B1^T ([d][d_ff] per cluster), w2bt = B2^T ([d_ff][d]), both in 32-column blocks
-    hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, d, (const int*)nullptr,
-                       (const float*)nullptr, f, offc, (size_t)mat, 1, H(L.w1bt));
-    hipLaunchKernelGGL(bw_transpose_kernel, dim3(d / 64, f / 64, G), dim3(256), 0, st, w2b, f, f, (const int*)nullptr,
-                       (const float*)nullptr, d, offc, (size_t)mat, 1, H(L.w2bt));
+    hipLaunchKernelGGL(bw_transpose_kernel, dim3(f / 64, d / 64, G), dim3(256), 0, st, w1b, d, pk ? (long)f * 32 : 0L, d,
+                       (const int*)nullptr, (const float*)nullptr, f, offc, (size_t)mat, 1, H(L.w1bt));
+    hipLaunchKernelGGL(bw_transpose_kernel, dim3(d / 64, f / 64, G), dim3(256), 0, st, w2b, f, pk ? (long)d * 32 : 0L, f,
+                       (const int*)nullptr, (const float*)nullptr, d, offc, (size_t)mat, 1, H(L.w2bt));
     BW_CHECK(hipGetLastError());
 
     // h = B1 x + U1 (V1 x): base product per token (token order), rank part per pair
-    if (w.packed != nullptr)   // packed W1: [d/32][d_ff][32] per cluster
-      BW_CHECK(launch_gemm_plain((const half_t*)w.packed, mat, 32, f, x, d, permc, 1, d, offc, G, T, nullptr, permc,
+    if (pk)   // packed W1: [d/32][d_ff][32] per cluster
+      BW_CHECK(launch_gemm_plain(w1b, mat, 32, f, x, d, permc, 1, d, offc, G, T, nullptr, permc,
                                  H(L.hb), f, false, st, (long)f * 32, 0));
     else
       BW_GEMM(w1b, mat, d, f, x, d, permc, 1, d, offc, G, T, nullptr, permc, H(L.hb), f, false);

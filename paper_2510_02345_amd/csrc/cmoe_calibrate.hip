@@ -1,10 +1,11 @@
 // Calibration kernel for the benchmark: what rate do the FP16 matrix cores sustain on this
 // machine when they are never kept waiting?  The loop is the inner schedule of the grouped
 // products (eight wavefronts per workgroup in two sets that alternate LDS fragment reads and
-// v_mfma_f32_32x32x16_f16 issue, one barrier apart) with operands of random mantissas read
+// v_mfma_f32_16x16x32_f16 issue, one barrier apart) with operands of random mantissas read
 // from LDS, but with no global memory traffic, no epilogue and one workgroup per compute
-// unit.  Every matrix-core issue slot is used (1024 cycles per iteration and SIMD for 32
-// instructions of 32 cycles), so the rate that comes out is set by the clock the power
+// unit.  Every matrix-core issue slot is used (1024 cycles per iteration and SIMD for 64
+// instructions of 16 cycles, the 8 x 4 accumulator blocks of a 128 x 64 wavefront tile
+// twice), so the rate that comes out is set by the clock the power
 // management grants under this load and nothing else.
 #include "cmoe_internal.h"
 
@@ -27,11 +28,11 @@ __global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsig
   int off[12];
 #pragma unroll
   for (int i = 0; i < 12; ++i) off[i] = ((wave * 12 + i) * 1024 + lane * 16) & 32767;   // conflict-free 1-KiB reads
-  float16v acc[8];
+  float4v acc[8][4];
 #pragma unroll
   for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
+    for (int b = 0; b < 4; ++b) acc[a][b] = float4v{0.f, 0.f, 0.f, 0.f};
   half8 f[12];
 #pragma unroll
   for (int i = 0; i < 12; ++i) f[i] = *(const half8*)(smem + off[i]);
@@ -50,12 +51,10 @@ __global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsig
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-          acc[a * 2 + b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[ks * 6 + a], f[ks * 6 + 4 + b], acc[a * 2 + b], 0, 0, 0);
+      for (int a = 0; a < 8; ++a)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(f[a], f[8 + b], acc[a][b], 0, 0, 0);
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
@@ -71,7 +70,7 @@ __global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsig
 #pragma unroll
   for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s += acc[a][v];
+    for (int b = 0; b < 4; ++b) s += acc[a][b][0] + acc[a][b][1] + acc[a][b][2] + acc[a][b][3];
   sink[(size_t)blockIdx.x * 512 + tid] = s;
 }
 

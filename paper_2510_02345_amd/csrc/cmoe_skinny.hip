@@ -53,9 +53,12 @@ struct SkRing {
 //                tile at step 0, WITHOUT the chunk offset (the swizzle depends on the row);
 //                w_stride: elements between 8-row groups; brow[i]: the lane's row of token
 //                row group i (rows beyond the pass are clamped by the caller)
+//   w_blk:       elements between consecutive 32-element contraction blocks of a weight row:
+//                32 for row-major rows, rows * 32 for a matrix stored as [K / 32][rows][32]
+//                (the re-tiled copy of the bases); a step of 64 elements is two blocks
 // With COLS = 16 accumulator columns 16..31 repeat columns 0..15.
 template <int COLS>
-__device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_stride,
+__device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_stride, size_t w_blk,
                                               const half_t* const (&brow)[COLS / 8], char* ring, unsigned ring_lds,
                                               int lane, int it0, int it1, float16v (&acc)[SK_RB]) {
   using RG = SkRing<COLS>;
@@ -75,11 +78,14 @@ __device__ __forceinline__ void skinny_stream(const half_t* wrow, size_t w_strid
   // lane l of load i fills row 8i + l/8, chunk position l%8, with source chunk position ^ swizzle(row)
   const int lrow = lane >> 3, lpos = lane & 7;
   const int c0 = (lpos ^ (lrow >> 1)) << 3, c1 = (lpos ^ (lrow >> 1) ^ 4) << 3;  // even / odd groups
+  // the same chunks of the weight rows: chunk c = block c / 4 of the step, 8 (c % 4) elements into it
+  const size_t wc0 = (size_t)(c0 >> 5) * w_blk + (c0 & 31), wc1 = (size_t)(c1 >> 5) * w_blk + (c1 & 31);
+  const size_t w_step = 2 * w_blk;
   auto issue = [&](int it, int stage) {
     const unsigned dst = ring_lds + stage * RG::STAGE;
 #pragma unroll
     for (int i = 0; i < SK_ROWS / 8; ++i)
-      dma16(wrow + ((i & 1) ? c1 : c0) + (size_t)i * w_stride + (size_t)it * 64, dst + i * 1024);
+      dma16(wrow + ((i & 1) ? wc1 : wc0) + (size_t)i * w_stride + (size_t)it * w_step, dst + i * 1024);
 #pragma unroll
     for (int i = 0; i < COLS / 8; ++i)
       dma16(brow[i] + ((i & 1) ? c1 : c0) + (size_t)it * 64, dst + SK_A_BYTES + i * 1024);
@@ -301,14 +307,16 @@ struct SideArgs {
 // the experts of a cluster share, Sec. 3.2): up-projection with W = W1_base, X = x gathered
 // through perm, out = Hb; down-projection with W = W2_base, X = A, out = y_base_sorted.
 // N: rows of W per cluster, Kc: contraction length, gather: row index of X per sorted row
-// or NULL for the identity.
+// or NULL for the identity.  w_blk = 0: W[c] is row-major [N][Kc]; otherwise W[c] is stored
+// as [Kc / 32][N][32] and w_blk = N * 32 (the re-tiled copy of the bases): an 8-row load is
+// then two contiguous 256-byte pieces instead of eight 128-byte pieces a row apart.
 template <int SIDE, int COLS>
 __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(const half_t* __restrict__ X,
                                                                   const int* __restrict__ gather,
                                                                   const half_t* __restrict__ W,
                                                                   const int* __restrict__ offsets, int N, int Kc,
                                                                   half_t* __restrict__ out, int nx, int G,
-                                                                  SideArgs sa) {
+                                                                  long w_blk, SideArgs sa) {
   if (SIDE != SIDE_NONE && (int)blockIdx.x < sa.n_side) {
     const int job = blockIdx.x;
     if (job >= sa.n_jobs) return;
@@ -333,7 +341,8 @@ __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(con
   const int wv = __builtin_amdgcn_readfirstlane(wave);
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
   const int lrow = lane >> 3;
-  const half_t* wrow = W + ((size_t)t.c * N + t.n0 + lrow) * Kc;
+  const size_t w_ld = w_blk ? 32 : Kc;   // elements between consecutive weight rows
+  const half_t* wrow = W + (size_t)t.c * N * Kc + (size_t)(t.n0 + lrow) * w_ld;
   const int p = t.m0 + fr;
   const half_t* brow[COLS / 8];
 #pragma unroll
@@ -348,7 +357,7 @@ __global__ __launch_bounds__(256, SkRing<COLS>::OCC) void skinny_base_kernel(con
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[rb][v] = 0.f;
   const int iters = Kc / 64;
-  skinny_stream<COLS>(wrow, (size_t)8 * Kc, brow, smem + wv * RG::RING, smem_lds + wv * RG::RING, lane,
+  skinny_stream<COLS>(wrow, 8 * w_ld, w_blk ? (size_t)w_blk : 32, brow, smem + wv * RG::RING, smem_lds + wv * RG::RING, lane,
                 wv * iters / SK_WAVES, (wv + 1) * iters / SK_WAVES, acc);
   __syncthreads();  // every ring has been consumed: its space becomes red
   float16v hb;
@@ -604,9 +613,12 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
   dim3 block(256);
   SideArgs sa{};
   sa.x_div = x_div > 1 ? x_div : 1;
+  // the re-tiled copy of W1 when the caller keeps one, else the canonical array
+  const half_t* w1 = w.packed ? (const half_t*)((const char*)w.packed + cmoe_packed(dm).w1) : (const half_t*)w.w1_base;
+  const long w_blk = w.packed ? (long)dm.d_ff * 32 : 0;
   if (t1 == nullptr) {
-    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, x, perm,
-                       (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
+    hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, x, perm, w1, offsets,
+                       dm.d_ff, dm.d, hb, nx, dm.G, w_blk, sa);
     return hipGetLastError();
   }
   sa.x = x;
@@ -623,8 +635,8 @@ hipError_t launch_skinny_hb(const cmoe_dims& dm, const cmoe_weights& w, const ha
   sa.n_exp = dm.G * dm.K;
   sa.n_jobs = T * dm.k;
   sa.n_side = (sa.n_jobs + 7) & ~7;
-  hipLaunchKernelGGL((skinny_base_kernel<SIDE_T1, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, x, perm,
-                     (const half_t*)w.w1_base, offsets, dm.d_ff, dm.d, hb, nx, dm.G, sa);
+  hipLaunchKernelGGL((skinny_base_kernel<SIDE_T1, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, x, perm, w1,
+                     offsets, dm.d_ff, dm.d, hb, nx, dm.G, w_blk, sa);
   return hipGetLastError();
 }
 
@@ -655,9 +667,11 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   dim3 block(256);
   SideArgs sa{};
   sa.x_div = 1;
+  const half_t* w2 = w.packed ? (const half_t*)((const char*)w.packed + cmoe_packed(dm).w2) : (const half_t*)w.w2_base;
+  const long w_blk = w.packed ? (long)dm.d * 32 : 0;
   if (ures == nullptr) {
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, SK_COLS>), dim3(n_stream), block, 0, st, a, (const int*)nullptr,
-                       (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
+                       w2, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, w_blk, sa);
     return hipGetLastError();
   }
   sa.perm = perm;
@@ -677,7 +691,7 @@ hipError_t launch_skinny_down(const cmoe_dims& dm, const cmoe_weights& w, const 
   sa.n_jobs = T * ((dm.d + 2047) / 2048);
   sa.n_side = (sa.n_jobs + 7) & ~7;
   hipLaunchKernelGGL((skinny_base_kernel<SIDE_URES, SK_COLS>), dim3(n_stream + sa.n_side), block, 0, st, a, (const int*)nullptr,
-                     (const half_t*)w.w2_base, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, sa);
+                     w2, offsets, dm.d, dm.d_ff, y_base_sorted, nx, dm.G, w_blk, sa);
   return hipGetLastError();
 }
 
@@ -692,10 +706,10 @@ hipError_t launch_skinny_rows(const half_t* X, const half_t* W, const int* offse
   if (max_rows > 16) {
     const int passes = (max_rows + 31) / 32;
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, 32>), dim3((unsigned)nx * n_groups * passes), dim3(256), 0, st, X,
-                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, 0L, sa);
   } else {
     hipLaunchKernelGGL((skinny_base_kernel<SIDE_NONE, 16>), dim3((unsigned)nx * n_groups), dim3(256), 0, st, X,
-                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, sa);
+                       (const int*)nullptr, W, offsets, N, Kc, out, nx, n_groups, 0L, sa);
   }
   return hipGetLastError();
 }

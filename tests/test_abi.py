@@ -211,4 +211,14 @@ def test_pack_weights_rejects_bad_arguments_without_touching_the_gpu():
     bad.packed = 0x1008
     assert L.cmoe_ffn_forward(h, C.byref(bad), fake, 8, fake, fake, fake, fake, fake, fake, fake, 1 << 40,
                               None) == B.ERR_INVALID_ARG
+    # bases: the canonical arrays or the packed copy; with neither, or with only one of the two
+    # canonical arrays and no packed copy, the call is refused before any GPU work
+    nob = B.Weights(*([fake] * 13))
+    nob.w1_base = None
+    assert L.cmoe_ffn_forward(h, C.byref(nob), fake, 8, fake, fake, fake, fake, fake, fake, fake, 16,
+                              None) == B.ERR_INVALID_ARG
+    nob.w2_base = None
+    nob.packed = fake                  # packed copy alone: accepted (here it fails later, on the workspace size)
+    assert L.cmoe_ffn_forward(h, C.byref(nob), fake, 8, fake, fake, fake, fake, fake, fake, fake, 16,
+                              None) == B.ERR_WORKSPACE
     L.cmoe_destroy(h)

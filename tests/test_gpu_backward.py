@@ -21,7 +21,7 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
 
-def _run(cfg, w=None, dy_scale=1.0, pack=True):
+def _run(cfg, w=None, dy_scale=1.0, pack=True, drop_canonical=False):
     import torch
     import paper_2510_02345_amd as cm
     print(f"case {cfg}", flush=True)
@@ -31,6 +31,8 @@ def _run(cfg, w=None, dy_scale=1.0, pack=True):
     cid, eidx, gate, _, _ = orc.route(w["x"], w["router_cluster"], w["router_expert"], cfg.K, cfg.k, w["cluster_bias"])
     ref = orc.backward_naive(w, w["x"], dy, eidx, gate, cfg.K, cfg.q)
     layer = cm.Layer(cfg.d, cfg.d_ff, cfg.G, cfg.K, cfg.r, cfg.k, cfg.q, w, cfg.T, pack=pack)
+    if drop_canonical:
+        layer.drop_canonical_bases()
     out = layer.backward(_dev(w["x"]), _dev(dy), _dev(eidx.astype(np.int32)), _dev(gate.astype(np.float32)))
     torch.cuda.synchronize()
     res = {}
@@ -80,6 +82,13 @@ def test_backward_config1():
 
 def test_backward_canonical_bases_without_the_packed_copy():
     _run(SMALL[0], pack=False)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[8]], ids=lambda c: c.name)
+def test_backward_packed_copy_as_the_only_resident_bases(cfg):
+    # w1_base / w2_base freed and passed as NULL after packing: the transposed operands and the
+    # forward base product of the backward pass are all built from the packed buffer
+    _run(cfg, drop_canonical=True)
 
 
 def test_backward_live_residual_and_gate_path():

@@ -41,13 +41,15 @@ def _check_y(y, y_ref, what):
     return m
 
 
-def _stepwise(cfg, w=None, pack=True):
+def _stepwise(cfg, w=None, pack=True, drop_canonical=False):
     """Each entry point on its own against the oracle, then cmoe_forward."""
-    print(f"case {cfg} pack={pack}", flush=True)
+    print(f"case {cfg} pack={pack} drop_canonical={drop_canonical}", flush=True)
     w = w if w is not None else ci.generate(cfg)
     ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
     rw = orc.ffn_rewrite(w, w["x"], ref["perm"], ref["offsets"], ref["expert_idx"], ref["gate"], cfg.K, cfg.q)
     layer = _layer(cfg, w, pack=pack)
+    if drop_canonical:
+        layer.drop_canonical_bases()
     x = _dev(w["x"])
 
     cid, eidx, gate = layer.route(x)
@@ -143,10 +145,39 @@ def test_pre_activations_far_outside_the_gelu_polynomial_range(cfg):
     _stepwise(cfg, w=w)
 
 
-@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[9], SMALL[12]], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[9], SMALL[12], SMALL[7], SMALL[13]], ids=lambda c: c.name)
 def test_canonical_bases_without_the_packed_copy(cfg):
-    # the layer reads the caller's row-major bases when no packed copy is given
+    # the layer reads the caller's row-major bases when no packed copy is given (both paths)
     _stepwise(cfg, pack=False)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[7], SMALL[8], SMALL[12], SMALL[13]], ids=lambda c: c.name)
+def test_packed_copy_as_the_only_resident_bases(cfg):
+    # after packing, w1_base / w2_base are freed and passed as NULL: both paths (and every
+    # entry point) read the bases from the packed buffer alone
+    _stepwise(cfg, drop_canonical=True)
+
+
+def test_resident_weight_bytes_with_one_copy_of_the_bases():
+    # C1: bases once (packed) + INT4 factors + FP16 panels + routers
+    cfg = ci.config(1)
+    w = ci.generate(cfg)
+    layer = _layer(cfg, w)
+    both = layer.resident_weight_bytes()
+    layer.drop_canonical_bases()
+    one = layer.resident_weight_bytes()
+    bases = 2 * 2 * cfg.G * cfg.d * cfg.d_ff
+    assert both - one == bases
+    E, L = cfg.G * cfg.K, cfg.d + cfg.d_ff
+    factors = 2 * E * cfg.r * (L // 2 + 2 * (L // cfg.q))
+    panels = 4 * cfg.G * 32 * ((cfg.K * cfg.r + 31) // 32) * L
+    routers = 2 * (cfg.G + E) * cfg.d
+    assert abs(one - (bases + factors + panels + routers)) <= 4096
+    ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    out = layer.forward(_dev(w["x"]))
+    _sync()
+    _check_y(out["y"].cpu().numpy(), ref["y"], "forward, packed bases only")
+    layer.close()
 
 
 def test_packed_and_canonical_bases_give_identical_outputs():
@@ -154,6 +185,17 @@ def test_packed_and_canonical_bases_give_identical_outputs():
     # same order, bit-identical y
     import torch
     cfg = ci.config(1)
+    w = ci.generate(cfg)
+    x = _dev(w["x"])
+    ys = []
+    for pack in (True, False):
+        layer = _layer(cfg, w, pack=pack)
+        ys.append(layer.forward(x)["y"].clone())
+        _sync()
+        layer.close()
+    assert torch.equal(ys[0], ys[1])
+    # the same on the weight-streaming path
+    cfg = SMALL[7]
     w = ci.generate(cfg)
     x = _dev(w["x"])
     ys = []
