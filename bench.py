@@ -341,16 +341,21 @@ def main():
     if not args.no_calibration:
         import paper_2510_02345_amd as cm
         tf, ghz = cm.calibrate_mfma()
+        tf0, ghz0 = cm.calibrate_mfma(zero_operands=True)
         rf = line["roofline"]
         line["mfma_sustained"] = {
             "value": round(tf, 1), "unit": "TFLOP/s", "shader_clock_GHz": round(ghz, 3),
             "frac_of_peak": round(tf / PEAK_F16_TFLOPS, 4),
+            "zero_operands": {"value": round(tf0, 1), "shader_clock_GHz": round(ghz0, 3),
+                              "frac_of_peak": round(tf0 / PEAK_F16_TFLOPS, 4)},
             "dominant_kernel_vs_sustained": round(rf["achieved"] / tf, 4) if rf["bound"] == "mfma" else None,
             "note": "cmoe_calibrate_mfma in this run: the grouped products' inner schedule (16 x 16 x 32 FP16 MFMAs, "
-                    "fragments of random mantissas read from LDS, two wavefront sets) with no global traffic and "
-                    "every matrix-core issue slot used on all 256 CUs; the rate is what the power management "
-                    "sustains, the ceiling of any FP16 product on this box. roofline.frac stays against the "
-                    "published 2.5 PFLOP/s"}
+                    "fragments read from LDS, two wavefront sets) with no global traffic and every matrix-core issue "
+                    "slot used on all 256 CUs. value: operands of random mantissas (what weights and activations "
+                    "look like); zero_operands: the same instructions on all-zero operands. The difference is the "
+                    "board's power management, which lowers the clock with the switching activity of the data; "
+                    "value is the ceiling of any FP16 product on real data on this box. roofline.frac stays against "
+                    "the published 2.5 PFLOP/s"}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, res["inputs"], min(args.cpu_sample, cfg.T))
     del res

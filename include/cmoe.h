@@ -321,9 +321,11 @@ const char *cmoe_timing_name(int32_t slot);
  * 8 * iters * 32 * 16384; the rate over the call's duration is what the power management lets
  * the matrix cores sustain on this machine.  ticks [2] u64 (device, zeroed by the caller): sums
  * over the workgroups of shader-clock cycles and of constant-rate (100 MHz) ticks spent in the
- * loop; sink [n_workgroups * 512] f32 (device) receives the accumulators.  Not for production
- * use. */
-int cmoe_calibrate_mfma(int32_t n_workgroups, int32_t iters, uint64_t *ticks, float *sink, void *stream);
+ * loop; sink [n_workgroups * 512] f32 (device) receives the accumulators.  zero_operands != 0
+ * runs the same loop on operands that are all 0.0 (the rate without the data-dependent part of
+ * the power draw).  Not for production use. */
+int cmoe_calibrate_mfma(int32_t n_workgroups, int32_t iters, int32_t zero_operands, uint64_t *ticks, float *sink,
+                        void *stream);
 
 #ifdef __cplusplus
 }

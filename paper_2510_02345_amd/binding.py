@@ -102,7 +102,7 @@ def lib():
     L.cmoe_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32), i32]
     L.cmoe_timing_name.argtypes = [i32]
     L.cmoe_timing_name.restype = C.c_char_p
-    L.cmoe_calibrate_mfma.argtypes = [i32, i32, vp, vp, vp]
+    L.cmoe_calibrate_mfma.argtypes = [i32, i32, i32, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("cmoe_workspace_bytes", "cmoe_status_string", "cmoe_timing_name",
                         "cmoe_compress_workspace_bytes", "cmoe_workspace_bytes_multi",
@@ -180,19 +180,21 @@ def reconstruction_error(W, base, u_q, u_s, v_q, v_s, G: int, K: int, r: int, q:
     return err
 
 
-def calibrate_mfma(n_workgroups: int = 256, iters: int = 40000, device="cuda:0"):
+def calibrate_mfma(n_workgroups: int = 256, iters: int = 40000, device="cuda:0", zero_operands: bool = False):
     """cmoe_calibrate_mfma between two events: (TFLOP/s sustained by the matrix cores with every
     issue slot used and no memory traffic, shader clock in GHz during the loop)."""
     import torch
     ticks = torch.zeros((2,), dtype=torch.int64, device=device)
     sink = torch.empty((n_workgroups * 512,), dtype=torch.float32, device=device)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    _chk(lib().cmoe_calibrate_mfma(n_workgroups, max(iters // 20, 1), _ptr(ticks), _ptr(sink), _cur_stream()),
+    _chk(lib().cmoe_calibrate_mfma(n_workgroups, max(iters // 20, 1), int(zero_operands), _ptr(ticks), _ptr(sink),
+                                   _cur_stream()),
          "cmoe_calibrate_mfma")        # warm-up
     torch.cuda.synchronize()
     ticks.zero_()
     e0.record()
-    _chk(lib().cmoe_calibrate_mfma(n_workgroups, iters, _ptr(ticks), _ptr(sink), _cur_stream()), "cmoe_calibrate_mfma")
+    _chk(lib().cmoe_calibrate_mfma(n_workgroups, iters, int(zero_operands), _ptr(ticks), _ptr(sink), _cur_stream()),
+         "cmoe_calibrate_mfma")
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)

@@ -6,12 +6,16 @@
 // unit.  Every matrix-core issue slot is used (1024 cycles per iteration and SIMD for 64
 // instructions of 16 cycles, the 8 x 4 accumulator blocks of a 128 x 64 wavefront tile
 // twice), so the rate that comes out is set by the clock the power
-// management grants under this load and nothing else.
+// management grants under this load and nothing else.  With zero_operands every operand is
+// 0.0: same instructions, same issue rate, far less switching in the multipliers - the
+// difference between the two rates is the share of the published peak that the power limit,
+// not the kernel, takes away on real data.
 #include "cmoe_internal.h"
 
 namespace {
 
-__global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsigned long long* __restrict__ ticks,
+__global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, int zero_operands,
+                                                                unsigned long long* __restrict__ ticks,
                                                                 float* __restrict__ sink) {
   __shared__ __attribute__((aligned(1024))) char smem[2 * 32768];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -22,7 +26,8 @@ __global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsig
     x *= 2246822519u;
     x ^= x >> 13;
     // unit-scale values with random mantissas (sum of two uniforms)
-    ((half_t*)smem)[i] = (half_t)((((x & 0xffff) / 65536.f - 0.5f) + (((x >> 16) & 0xffff) / 65536.f - 0.5f)) * 1.7f);
+    const float v = (((x & 0xffff) / 65536.f - 0.5f) + (((x >> 16) & 0xffff) / 65536.f - 0.5f)) * 1.7f;
+    ((half_t*)smem)[i] = zero_operands ? (half_t)0.f : (half_t)v;
   }
   __syncthreads();
   int off[12];
@@ -76,10 +81,11 @@ __global__ __launch_bounds__(512, 1) void calibrate_mfma_kernel(int iters, unsig
 
 }  // namespace
 
-extern "C" int cmoe_calibrate_mfma(int32_t n_workgroups, int32_t iters, uint64_t* ticks, float* sink, void* stream) {
+extern "C" int cmoe_calibrate_mfma(int32_t n_workgroups, int32_t iters, int32_t zero_operands, uint64_t* ticks,
+                                   float* sink, void* stream) {
   if (n_workgroups <= 0 || n_workgroups > 4096 || iters <= 0 || ticks == nullptr || sink == nullptr)
     return CMOE_ERR_INVALID_ARG;
   hipLaunchKernelGGL(calibrate_mfma_kernel, dim3((unsigned)n_workgroups), dim3(512), 0, (hipStream_t)stream, iters,
-                     (unsigned long long*)ticks, sink);
+                     zero_operands != 0 ? 1 : 0, (unsigned long long*)ticks, sink);
   return hipGetLastError() == hipSuccess ? CMOE_OK : CMOE_ERR_HIP;
 }

@@ -473,6 +473,7 @@ namespace {
 // first expert alone when K * K keys do not fit the 64 bins.
 //   rowmap[i] = cluster-sorted row of refined row i,  perm2[i] = its token.
 constexpr int PS_THREADS = 1024;
+constexpr int PS_KEEP = 8;   // rows per thread whose token and key stay in registers
 __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __restrict__ perm,
                                                               const int* __restrict__ offsets,
                                                               const int* __restrict__ expert_idx, int K, int k,
@@ -485,15 +486,29 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
   const int c = blockIdx.x;
   const int lo = offsets[c], n = offsets[c + 1] - lo;
   if (n <= 0) return;
-  auto key_of = [&](int i) {
-    const int* e = expert_idx + (size_t)perm[lo + i] * k;
+  auto key_of_tok = [&](int tok) {
+    const int* e = expert_idx + (size_t)tok * k;
     // expert slots outside the cluster (inconsistent caller input) are clamped into it
     const int j0 = min(max(e[0] - c * K, 0), K - 1);
     return two_keys ? j0 * K + min(max(e[1] - c * K, 0), K - 1) : j0;
   };
+  // The first PS_KEEP rows of a thread (row tid + j * PS_THREADS) are read once, all loads in
+  // flight together, and kept in registers for both passes; clusters with more rows take
+  // the rest from memory in each pass.
+  int tokr[PS_KEEP], keyr[PS_KEEP];
+#pragma unroll
+  for (int j = 0; j < PS_KEEP; ++j) {
+    const int i = tid + j * PS_THREADS;
+    tokr[j] = i < n ? perm[lo + i] : 0;
+  }
+#pragma unroll
+  for (int j = 0; j < PS_KEEP; ++j) keyr[j] = tid + j * PS_THREADS < n ? key_of_tok(tokr[j]) : 0;
   if (tid < 64) binbase[tid] = 0;
   __syncthreads();
-  for (int i = tid; i < n; i += PS_THREADS) atomicAdd(&binbase[key_of(i)], 1);
+#pragma unroll
+  for (int j = 0; j < PS_KEEP; ++j)
+    if (tid + j * PS_THREADS < n) atomicAdd(&binbase[keyr[j]], 1);
+  for (int i = tid + PS_KEEP * PS_THREADS; i < n; i += PS_THREADS) atomicAdd(&binbase[key_of_tok(perm[lo + i])], 1);
   __syncthreads();
   if (wave == 0) {   // exclusive scan of the 64 bin counts
     const int cnt = binbase[lane];
@@ -506,10 +521,8 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
     binbase[lane] = incl - cnt;
   }
   __syncthreads();
-  for (int i0 = 0; i0 < n; i0 += PS_THREADS) {   // chunks in order keep the sort stable
-    const int i = i0 + tid;
-    const bool in = i < n;
-    const int key = in ? key_of(i) : 0;
+  // one chunk of PS_THREADS rows; chunks in order keep the sort stable
+  auto chunk = [&](int i, bool in, int key, int tok) {
     // lanes of this wavefront holding the same key
     unsigned long long same = __ballot(in);
 #pragma unroll
@@ -517,7 +530,7 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
       const unsigned long long m = __ballot((key >> b) & 1);
       same &= ((key >> b) & 1) ? m : ~m;
     }
-    for (int q = lane; q < 64; q += 64) wcount[wave][q] = 0;
+    wcount[wave][lane] = 0;
     __syncthreads();
     const int below = __popcll(same & ((1ull << lane) - 1ull));
     if (in && below == 0) wcount[wave][key] = __popcll(same);
@@ -527,7 +540,7 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
       for (int w = 0; w < wave; ++w) before += wcount[w][key];
       const int pos = lo + binbase[key] + before + below;
       rowmap[pos] = lo + i;
-      perm2[pos] = perm[lo + i];
+      perm2[pos] = tok;
     }
     __syncthreads();
     if (tid < 64) {
@@ -537,6 +550,18 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
       binbase[tid] += add;
     }
     __syncthreads();
+  };
+#pragma unroll
+  for (int j = 0; j < PS_KEEP; ++j) {
+    if (j * PS_THREADS >= n) break;   // uniform over the workgroup
+    const int i = tid + j * PS_THREADS;
+    chunk(i, i < n, keyr[j], tokr[j]);
+  }
+  for (int i0 = PS_KEEP * PS_THREADS; i0 < n; i0 += PS_THREADS) {
+    const int i = i0 + tid;
+    const bool in = i < n;
+    const int tok = in ? perm[lo + i] : 0;
+    chunk(i, in, in ? key_of_tok(tok) : 0, tok);
   }
 }
 }  // namespace
