@@ -14,11 +14,12 @@ __device__ __forceinline__ float16v mfma16(half8 a, half8 b, float16v c) {
 // to 1.95e-4 absolute, 4e-5 RMS under a unit Gaussian: below the FP16 rounding of the
 // result).  Beyond the range Phi is held at its value at the end of it, and the factor u at
 // -3.75 on the negative side, so the error does not grow with |u|: relative 8.8e-5 for
-// large positive u, -3.3e-4 absolute (instead of -0) for large negative u.  Eleven
-// full-rate FP32 operations per element.
+// large positive u, -3.3e-4 absolute (instead of -0) for large negative u; NaN in, NaN out.
+// Twelve full-rate FP32 operations per element.
 __device__ __forceinline__ float gelu_erf(float u) {
   const float uc = __builtin_amdgcn_fmed3f(u, -3.75f, 3.75f);
-  const float um = fmaxf(u, -3.75f);
+  // max(u, -3.75) as a select, so that a NaN pre-activation stays a NaN in the result
+  const float um = u < -3.75f ? -3.75f : u;
   const float t = uc * uc;
   float p = fmaf(t, 3.878059656e-08f, -2.362032659e-06f);
   p = fmaf(t, p, 6.212595828e-05f);

@@ -145,6 +145,28 @@ def test_pre_activations_far_outside_the_gelu_polynomial_range(cfg):
     _stepwise(cfg, w=w)
 
 
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[7]], ids=lambda c: c.name)
+def test_nan_in_a_base_weight_reaches_exactly_the_outputs_it_feeds(cfg):
+    # one NaN in row 5 of W1_base of cluster 0: hidden unit 5 of every token of that cluster is
+    # NaN before and after the activation, so all of those tokens' outputs are NaN and no
+    # other token's (the activation must not turn a NaN into a number)
+    w = ci.generate(cfg)
+    w1 = w["w1_base"].copy()
+    w1[0, 5, 7] = np.nan
+    w = dict(w, w1_base=w1)
+    with np.errstate(invalid="ignore"):
+        ref = orc.forward_naive(w, w["x"], cfg.K, cfg.k, cfg.q)
+    hit = ref["cluster_id"] == 0
+    assert hit.any() and not hit.all()
+    assert np.all(np.isnan(ref["y"][hit])) and np.all(np.isfinite(ref["y"][~hit]))
+    layer = _layer(cfg, w)
+    y = layer.forward(_dev(w["x"]))["y"].cpu().numpy()
+    _sync()
+    assert np.all(np.isnan(y[hit]))
+    _check_y(y[~hit], ref["y"][~hit], "tokens of the other clusters")
+    layer.close()
+
+
 @pytest.mark.parametrize("cfg", [SMALL[0], SMALL[9], SMALL[12], SMALL[7], SMALL[13]], ids=lambda c: c.name)
 def test_canonical_bases_without_the_packed_copy(cfg):
     # the layer reads the caller's row-major bases when no packed copy is given (both paths)
