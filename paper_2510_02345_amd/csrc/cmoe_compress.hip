@@ -23,28 +23,43 @@ constexpr int CP_LMAX = 48;   // widest sketch
 // One 64 x 64 tile of cluster c: the base tile (Eq. 6: FP32 sum of the K experts in index
 // order, divided by K, rounded to FP16), then for each expert e of the cluster
 // D = f16(W_e - base), DT = D^T, and the tile's share of sum D^2, sum D base, sum base^2,
-// sum W_e^2 (FP32, fixed order) -> part[e][tile][4].  The experts' tiles are read twice,
-// the second time from cache.
+// sum W_e^2 (FP32, fixed order), one partial per wavefront -> part[e][tile][wave][4].  The
+// tiles of the first CR_KEEP experts stay in registers between the two passes; those of
+// further experts are read a second time (from cache).  The transposing LDS tile is double
+// buffered: one barrier per expert.
+constexpr int CR_KEEP = 8;
 __global__ __launch_bounds__(256) void cmp_residual_kernel(const half_t* __restrict__ W, int K, int out_d, int in_d,
                                                            half_t* __restrict__ base, half_t* __restrict__ D,
                                                            half_t* __restrict__ DT, float* __restrict__ part) {
-  __shared__ half_t tile[64][72];
-  __shared__ float red[4][4];
+  __shared__ half_t tile[2][64][72];
   const int c = blockIdx.z;
   const int o0 = blockIdx.y * 64, i0 = blockIdx.x * 64;
   const int tid = threadIdx.x;
   const size_t me = (size_t)out_d * in_d;
   const size_t tix = (size_t)blockIdx.y * gridDim.x + blockIdx.x, nt = (size_t)gridDim.x * gridDim.y;
+  const int row0 = tid >> 3, ch = tid & 7;   // rows row0 and row0 + 32, 8 columns per thread
   size_t off[2];
   float bsum[2][8];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int row = (tid >> 3) + 32 * u, ch = tid & 7;   // 8 columns per thread
-    off[u] = (size_t)(o0 + row) * in_d + i0 + ch * 8;
+    off[u] = (size_t)(o0 + row0 + 32 * u) * in_d + i0 + ch * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) bsum[u][i] = 0.f;
   }
-  for (int j = 0; j < K; ++j)
+  half8 keep[CR_KEEP][2];
+#pragma unroll
+  for (int j = 0; j < CR_KEEP; ++j)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      keep[j][u] = j < K ? *(const half8*)(W + ((size_t)c * K + j) * me + off[u]) : half8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < CR_KEEP; ++j)
+    if (j < K)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bsum[u][i] += (float)keep[j][u][i];
+  for (int j = CR_KEEP; j < K; ++j)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const half8 w8 = *(const half8*)(W + ((size_t)c * K + j) * me + off[u]);
@@ -59,58 +74,75 @@ __global__ __launch_bounds__(256) void cmp_residual_kernel(const half_t* __restr
     for (int i = 0; i < 8; ++i) b8[u][i] = (half_t)(bsum[u][i] / kf);
     *(half8*)(base + (size_t)c * me + off[u]) = b8[u];
   }
-  for (int j = 0; j < K; ++j) {
-    const int e = c * K + j;
+  auto one = [&](int j, const half8 (&w)[2]) {
+    const int e = c * K + j, buf = j & 1;
     float s_dd = 0.f, s_db = 0.f, s_bb = 0.f, s_ww = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const int row = (tid >> 3) + 32 * u, ch = tid & 7;
-      const half8 w8 = *(const half8*)(W + (size_t)e * me + off[u]);
       half8 d8;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float w = (float)w8[i], b = (float)b8[u][i];
-        d8[i] = (half_t)(w - b);
+        const float wv = (float)w[u][i], b = (float)b8[u][i];
+        d8[i] = (half_t)(wv - b);
         const float dv = (float)d8[i];
         s_dd = fmaf(dv, dv, s_dd);
         s_db = fmaf(dv, b, s_db);
         s_bb = fmaf(b, b, s_bb);
-        s_ww = fmaf(w, w, s_ww);
+        s_ww = fmaf(wv, wv, s_ww);
       }
       *(half8*)(D + (size_t)e * me + off[u]) = d8;
-      *(half8*)(&tile[row][ch * 8]) = d8;
+      *(half8*)(&tile[buf][row0 + 32 * u][ch * 8]) = d8;
     }
+    // this barrier also separates the reads of tile[buf] two experts ago from these writes
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-      const int irow = (tid >> 3) + 32 * u, ch = tid & 7;   // row of the transposed tile
+      const int irow = row0 + 32 * u;   // row of the transposed tile
       half8 t8;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) t8[i] = tile[ch * 8 + i][irow];
+      for (int i = 0; i < 8; ++i) t8[i] = tile[buf][ch * 8 + i][irow];
       *(half8*)(DT + (size_t)e * me + (size_t)(i0 + irow) * out_d + o0 + ch * 8) = t8;
     }
-    // workgroup sums in a fixed order: lanes by halving, then the four wavefronts
+    // wavefront sums in a fixed order (lanes by halving); the four wavefronts' partials are
+    // added, in order, by cmp_stats_kernel
     float v[4] = {s_dd, s_db, s_bb, s_ww};
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int o2 = 32; o2 > 0; o2 >>= 1) v[a] += __shfl_xor(v[a], o2, 64);
-    if ((tid & 63) == 0)
+    if ((tid & 63) < 4) {
+      const int a = tid & 3;
+      part[(((size_t)e * nt + tix) * 4 + (tid >> 6)) * 4 + a] = a == 0 ? v[0] : a == 1 ? v[1] : a == 2 ? v[2] : v[3];
+    }
+  };
 #pragma unroll
-      for (int a = 0; a < 4; ++a) red[tid >> 6][a] = v[a];
-    __syncthreads();   // also: every thread has read the transposed tile
-    if (tid < 4) part[((size_t)e * nt + tix) * 4 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
-    __syncthreads();
+  for (int j = 0; j < CR_KEEP; ++j)
+    if (j < K) one(j, keep[j]);
+  for (int j = CR_KEEP; j < K; ++j) {
+    half8 w[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) w[u] = *(const half8*)(W + ((size_t)c * K + j) * me + off[u]);
+    one(j, w);
   }
 }
 
-// stats[e][a] = sum over tiles of part[e][tile][a] (FP64, fixed order), a = dd, db, bb, ww.
+// stats[e][a] = sum over the n_tiles (tile, wavefront) partials part[e][.][a] (FP64, fixed
+// order), a = dd, db, bb, ww.
 __global__ __launch_bounds__(256) void cmp_stats_kernel(const float* __restrict__ part, int n_tiles,
                                                         double* __restrict__ stats) {
   __shared__ double red[256];
   const int e = blockIdx.x, a = threadIdx.x & 3, lane4 = threadIdx.x >> 2;   // 64 strided readers per quantity
+  const float* src = part + (size_t)e * n_tiles * 4 + a;
   double s = 0.0;
-  for (int t = lane4; t < n_tiles; t += 64) s += (double)part[((size_t)e * n_tiles + t) * 4 + a];
+  int t = lane4;
+  for (; t + 7 * 64 < n_tiles; t += 8 * 64) {   // eight loads in flight, added in index order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(t + 64 * u) * 4];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (double)v[u];
+  }
+  for (; t < n_tiles; t += 64) s += (double)src[(size_t)t * 4];
   red[threadIdx.x] = s;
   __syncthreads();
   if (threadIdx.x < 4) {
@@ -162,22 +194,37 @@ __global__ __launch_bounds__(256) void cmp_gram_kernel(const half_t* __restrict_
   }
 }
 
-// ---------------------------------------------------------------- small dense steps, one wavefront per expert
+// ---------------------------------------------------------------- small dense steps, one workgroup per expert
 // Sums the Gram partials (FP64).  MODE 0: coef = inverse of the Cholesky factor of
 // (Gram + shift I), so that coef X has orthonormal rows.  MODE 1: Jacobi eigenvectors of
 // the Gram matrix; coef rows = the r eigenvectors of largest eigenvalue (transposed), and
-// lam[e] = the sum of those eigenvalues.
+// lam[e] = the sum of those eigenvalues.  The Jacobi sweeps use the round-robin ordering:
+// a sweep is l - 1 rounds of l / 2 rotations on disjoint index pairs, which commute, so a
+// round applies all of them at once, A <- J^T A J and V <- V J, every element by one thread.
+constexpr int CS_THREADS = 256;
+constexpr int CS_PER = (CP_LMAX * CP_LMAX + CS_THREADS - 1) / CS_THREADS;   // elements of an l x l matrix per thread
 template <int MODE>
-__global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__ gpart, int n_chunks, int l, int r,
-                                                       float* __restrict__ coef, double* __restrict__ lam) {
+__global__ __launch_bounds__(CS_THREADS) void cmp_small_kernel(const float* __restrict__ gpart, int n_chunks, int l,
+                                                               int r, float* __restrict__ coef,
+                                                               double* __restrict__ lam) {
   __shared__ double A[CP_LMAX][CP_LMAX + 1];
   __shared__ double V[CP_LMAX][CP_LMAX + 1];
   __shared__ double ev[CP_LMAX];
   __shared__ int order[CP_LMAX];
   const int e = blockIdx.x, t = threadIdx.x;
-  for (int idx = t; idx < l * l; idx += 64) {
+  for (int idx = t; idx < l * l; idx += CS_THREADS) {
+    const float* src = gpart + (size_t)e * n_chunks * l * l + idx;
     double s = 0.0;
-    for (int ch = 0; ch < n_chunks; ++ch) s += (double)gpart[((size_t)e * n_chunks + ch) * l * l + idx];
+    int ch = 0;
+    for (; ch + 4 <= n_chunks; ch += 4) {   // four loads in flight, summed in chunk order
+      const float v0 = src[(size_t)ch * l * l], v1 = src[(size_t)(ch + 1) * l * l];
+      const float v2 = src[(size_t)(ch + 2) * l * l], v3 = src[(size_t)(ch + 3) * l * l];
+      s += (double)v0;
+      s += (double)v1;
+      s += (double)v2;
+      s += (double)v3;
+    }
+    for (; ch < n_chunks; ++ch) s += (double)src[(size_t)ch * l * l];
     A[idx / l][idx % l] = s;
   }
   __syncthreads();
@@ -194,17 +241,19 @@ __global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__
       tau_s = 1e-5 * tr / l + 1e-290;
     }
     __syncthreads();
-    // Cholesky A = L L^T, column by column; lane i owns row i
+    // Cholesky A = L L^T, column by column; the trailing update spread over the workgroup
     for (int j = 0; j < l; ++j) {
       if (t == 0) A[j][j] = A[j][j] > tau_s ? sqrt(A[j][j]) : 1e150;
       __syncthreads();
       if (t > j && t < l) A[t][j] /= A[j][j];
       __syncthreads();
-      if (t > j && t < l)
-        for (int k2 = j + 1; k2 <= t; ++k2) A[t][k2] -= A[t][j] * A[k2][j];
+      for (int idx = t; idx < l * l; idx += CS_THREADS) {
+        const int i = idx / l, k2 = idx % l;
+        if (i > j && k2 > j && k2 <= i) A[i][k2] -= A[i][j] * A[k2][j];
+      }
       __syncthreads();
     }
-    // V = L^-1 by forward substitution, lane c owns column c
+    // V = L^-1 by forward substitution, thread c owns column c
     if (t < l) {
       for (int i = 0; i < l; ++i) {
         double s = (i == t) ? 1.0 : 0.0;
@@ -213,50 +262,92 @@ __global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__
       }
     }
     __syncthreads();
-    for (int idx = t; idx < l * CP_LMAX; idx += 64) {
+    for (int idx = t; idx < l * CP_LMAX; idx += CS_THREADS) {
       const int a = idx / CP_LMAX, b = idx % CP_LMAX;
       cf[idx] = b < l ? (float)V[a][b] : 0.f;
     }
   } else {
-    for (int idx = t; idx < l * l; idx += 64) V[idx / l][idx % l] = (idx / l == idx % l) ? 1.0 : 0.0;
+    // per index k of the current round: its partner and the coefficients of
+    // new column k = cc[k] * column k + ss[k] * column partner[k]
+    __shared__ int partner[CP_LMAX];
+    __shared__ double cc[CP_LMAX], ss[CP_LMAX];
+    __shared__ double red[2][CS_THREADS / 64];
+    for (int idx = t; idx < l * l; idx += CS_THREADS) V[idx / l][idx % l] = (idx / l == idx % l) ? 1.0 : 0.0;
     __syncthreads();
+    const int n2 = (l + 1) / 2 * 2, m = n2 - 1;   // an odd l plays with one idle index
     for (int sweep = 0; sweep < 12; ++sweep) {
       // converged when every off-diagonal element is negligible against the diagonal
-      // (every lane evaluates the same test on the same values)
       double offmax = 0.0, diagmax = 0.0;
-      for (int i = 0; i < l; ++i)
-        for (int j2 = 0; j2 < l; ++j2) {
-          const double a = fabs(A[i][j2]);
-          if (i == j2) diagmax = fmax(diagmax, a); else offmax = fmax(offmax, a);
+      for (int idx = t; idx < l * l; idx += CS_THREADS) {
+        const double a = fabs(A[idx / l][idx % l]);
+        if (idx / l == idx % l) diagmax = fmax(diagmax, a); else offmax = fmax(offmax, a);
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        offmax = fmax(offmax, __shfl_xor(offmax, off, 64));
+        diagmax = fmax(diagmax, __shfl_xor(diagmax, off, 64));
+      }
+      if ((t & 63) == 0) {
+        red[0][t >> 6] = offmax;
+        red[1][t >> 6] = diagmax;
+      }
+      __syncthreads();
+      offmax = 0.0;
+      diagmax = 0.0;
+      for (int w = 0; w < CS_THREADS / 64; ++w) {
+        offmax = fmax(offmax, red[0][w]);
+        diagmax = fmax(diagmax, red[1][w]);
+      }
+      __syncthreads();   // red is rewritten by the next sweep
+      if (offmax <= 1e-10 * diagmax) break;   // the same values in every thread
+      for (int rr = 0; rr < m; ++rr) {
+        if (t < n2 / 2) {
+          const int a = t == 0 ? m : (rr + t) % m, b = t == 0 ? rr : (rr - t + m) % m;
+          const int p = min(a, b), q2 = max(a, b);
+          if (q2 < l) {
+            const double apq = A[p][q2], app = A[p][p], aqq = A[q2][q2];
+            double c = 1.0, sn = 0.0;
+            if (fabs(apq) > 1e-300 && fabs(apq) > 1e-17 * sqrt(fabs(app * aqq))) {
+              const double theta = (aqq - app) / (2.0 * apq);
+              const double tt = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+              c = 1.0 / sqrt(tt * tt + 1.0);
+              sn = tt * c;
+            }
+            partner[p] = q2;
+            cc[p] = c;
+            ss[p] = -sn;
+            partner[q2] = p;
+            cc[q2] = c;
+            ss[q2] = sn;
+          } else if (p < l) {   // paired with the idle index
+            partner[p] = p;
+            cc[p] = 1.0;
+            ss[p] = 0.0;
+          }
         }
-      if (offmax <= 1e-10 * diagmax) break;
-      for (int p = 0; p < l - 1; ++p)
-        for (int q2 = p + 1; q2 < l; ++q2) {
-          const double apq = A[p][q2], app = A[p][p], aqq = A[q2][q2];
-          double c = 1.0, s = 0.0;
-          if (fabs(apq) > 1e-300 && fabs(apq) > 1e-17 * sqrt(fabs(app * aqq))) {
-            const double theta = (aqq - app) / (2.0 * apq);
-            const double tt = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-            c = 1.0 / sqrt(tt * tt + 1.0);
-            s = tt * c;
+        __syncthreads();
+        double an[CS_PER], vn[CS_PER];
+#pragma unroll
+        for (int u = 0; u < CS_PER; ++u) {
+          const int idx = t + u * CS_THREADS;
+          if (idx < l * l) {
+            const int i = idx / l, k2 = idx % l, pi = partner[i], pk = partner[k2];
+            const double ci = cc[i], si = ss[i], ck = cc[k2], sk = ss[k2];
+            an[u] = ci * (ck * A[i][k2] + sk * A[i][pk]) + si * (ck * A[pi][k2] + sk * A[pi][pk]);
+            vn[u] = ck * V[i][k2] + sk * V[i][pk];
           }
-          __syncthreads();
-          if (t < l) {   // columns p, q of A and V
-            const double akp = A[t][p], akq = A[t][q2];
-            A[t][p] = c * akp - s * akq;
-            A[t][q2] = s * akp + c * akq;
-            const double vkp = V[t][p], vkq = V[t][q2];
-            V[t][p] = c * vkp - s * vkq;
-            V[t][q2] = s * vkp + c * vkq;
-          }
-          __syncthreads();
-          if (t < l) {   // rows p, q of A
-            const double apk = A[p][t], aqk = A[q2][t];
-            A[p][t] = c * apk - s * aqk;
-            A[q2][t] = s * apk + c * aqk;
-          }
-          __syncthreads();
         }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < CS_PER; ++u) {
+          const int idx = t + u * CS_THREADS;
+          if (idx < l * l) {
+            A[idx / l][idx % l] = an[u];
+            V[idx / l][idx % l] = vn[u];
+          }
+        }
+        __syncthreads();
+      }
     }
     if (t < l) ev[t] = A[t][t];
     __syncthreads();
@@ -266,7 +357,7 @@ __global__ __launch_bounds__(64) void cmp_small_kernel(const float* __restrict__
       order[rank] = t;
     }
     __syncthreads();
-    for (int idx = t; idx < r * CP_LMAX; idx += 64) {
+    for (int idx = t; idx < r * CP_LMAX; idx += CS_THREADS) {
       const int rho = idx / CP_LMAX, b = idx % CP_LMAX;
       cf[idx] = b < l ? (float)V[b][order[rho]] : 0.f;
     }
@@ -348,52 +439,127 @@ __global__ void cmp_gate_kernel(const double* __restrict__ stats, const double* 
 }
 
 // ---------------------------------------------------------------- reconstruction error of a stored form
-// epart[e][tile] = sum over a 64 x 64 tile of (W - base - U V)^2 with U, V dequantised
+// epart[e][workgroup] = sum over its 64 x 256 elements of (W - base - U V)^2 with U, V dequantised
 // (Sec. 3.2's Frobenius error, for what the layer will actually compute); wpart = sum W^2.
 __device__ __forceinline__ float cmp_nib(const uint8_t* row, int n) {
   const unsigned b = row[n >> 1];
   return (float)((int)((n & 1 ? b >> 4 : b & 0xF) ^ 8) - 8);
 }
+// A workgroup takes 64 rows and CE_CT consecutive 64-column tiles of one expert: the U panel
+// of its rows is decoded once, the V panel per column tile, all global loads issued before
+// the first use; epart has one entry per workgroup.  A one-dimensional grid of
+// 8 * ceil(G * tiles / 8) * K workgroups.  The kernel is bound by the vector ALUs, not by
+// memory: rebuilding U V costs r FP32 FMAs per element (34 GFLOP for 64 experts of
+// 8192 x 2048 at r = 16, about 0.5 ms of issue) next to 2.4 GB of reads.
+constexpr int CE_CT = 4;
 __global__ __launch_bounds__(256) void cmp_error_kernel(const half_t* __restrict__ W, const half_t* __restrict__ base,
                                                         const uint8_t* __restrict__ u_q,
                                                         const half_t* __restrict__ u_s,
                                                         const uint8_t* __restrict__ v_q,
-                                                        const half_t* __restrict__ v_s, int K, int out_d, int in_d,
-                                                        int r, int q, float* __restrict__ epart) {
-  __shared__ float us[32][64];   // U[rho][o0 + 0..63]
-  __shared__ float vs[32][64];   // V[rho][i0 + 0..63]
+                                                        const half_t* __restrict__ v_s, int G, int K, int out_d, int in_d,
+                                                        int r, int q, int tiles_x, int tiles_y,
+                                                        float* __restrict__ epart) {
+  __shared__ float us[32][64];                               // U[rho][o0 + 0..63]
+  __shared__ __attribute__((aligned(16))) float vs[32][64];  // V[rho][i0 + 0..63]
   __shared__ float red[4][2];
-  const int e = blockIdx.z, c = e / K;
-  const int o0 = blockIdx.y * 64, i0 = blockIdx.x * 64, tid = threadIdx.x;
-  for (int idx = tid; idx < r * 64; idx += 256) {
-    const int rho = idx / 64, j = idx % 64;
-    const size_t row = (size_t)e * r + rho;
-    us[rho][j] = (float)u_s[row * (out_d / q) + (o0 + j) / q] * cmp_nib(u_q + row * (out_d / 2), o0 + j);
-    vs[rho][j] = (float)v_s[row * (in_d / q) + (i0 + j) / q] * cmp_nib(v_q + row * (in_d / 2), i0 + j);
-  }
-  __syncthreads();
+  // Workgroups are dealt round-robin to the 8 XCDs; the K experts of one (cluster, tile) take
+  // K consecutive workgroups of ONE XCD, so that the base tile they share is fetched from
+  // memory once and found in that XCD's L2 by the others.
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int tc = (local / K) * 8 + xcd, per_c = tiles_x * tiles_y;
+  if (tc >= G * per_c) return;
+  const int c = tc / per_c, e = c * K + local % K;
+  const int tile_y = (tc % per_c) / tiles_x, tile_x = (tc % per_c) % tiles_x;
+  const int o0 = tile_y * 64, tid = threadIdx.x;
+  const int row0 = tid >> 3, ch = tid & 7;
   const size_t me = (size_t)out_d * in_d;
-  float se = 0.f, sw = 0.f;
+  // Panels: thread tid < 8 r owns the 8 codes (one 32-bit word) of rank row tid / 8 at columns
+  // 8 (tid % 8) .. + 7 of a 64-column tile and their scale (one scale when q is a multiple of
+  // 8; other group lengths take the element-wise path).  Every global load of the workgroup -
+  // the U words, the V words of all column tiles, the W and base tiles - is issued up front.
+  const bool words = (q % 8) == 0;
+  const int prho = tid >> 3, pwd = tid & 7;
+  const bool powner = words && prho < r;
+  const size_t prow = (size_t)e * r + (powner ? prho : 0);
+  auto put = [&](float (*dst)[64], unsigned w, float sc) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    const int row = (tid >> 3) + 32 * u, ch = tid & 7;
-    const size_t off = (size_t)(o0 + row) * in_d + i0 + ch * 8;
-    const half8 w8 = *(const half8*)(W + (size_t)e * me + off);
-    const half8 b8 = *(const half8*)(base + (size_t)c * me + off);
-    float uv[8];
+    for (int b2 = 0; b2 < 4; ++b2) {
+      const unsigned byte = (w >> (8 * b2)) & 0xffu;
+      dst[prho][pwd * 8 + 2 * b2] = sc * (float)((int)((byte & 0xFu) ^ 8u) - 8);
+      dst[prho][pwd * 8 + 2 * b2 + 1] = sc * (float)((int)((byte >> 4) ^ 8u) - 8);
+    }
+  };
+  unsigned uw = 0u, vw[CE_CT];
+  float usc = 0.f, vsc[CE_CT];
+  half8 w8[CE_CT][2], b8[CE_CT][2];
+  if (powner) {
+    uw = *(const unsigned*)(u_q + prow * (out_d / 2) + (o0 + pwd * 8) / 2);
+    usc = (float)u_s[prow * (out_d / q) + (o0 + pwd * 8) / q];
+  }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) uv[i] = 0.f;
-    for (int rho = 0; rho < r; ++rho) {
-      const float uo = us[rho][row];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) uv[i] = fmaf(uo, vs[rho][ch * 8 + i], uv[i]);
+  for (int ct = 0; ct < CE_CT; ++ct) {
+    const int i0 = (tile_x * CE_CT + ct) * 64;
+    const bool in = i0 < in_d;
+    vw[ct] = 0u;
+    vsc[ct] = 0.f;
+    if (powner && in) {
+      vw[ct] = *(const unsigned*)(v_q + prow * (in_d / 2) + (i0 + pwd * 8) / 2);
+      vsc[ct] = (float)v_s[prow * (in_d / q) + (i0 + pwd * 8) / q];
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float w = (float)w8[i];
-      const float dv = w - (float)b8[i] - uv[i];
-      se = fmaf(dv, dv, se);
-      sw = fmaf(w, w, sw);
+    for (int u = 0; u < 2; ++u) {
+      const size_t off = (size_t)(o0 + row0 + 32 * u) * in_d + (in ? i0 : 0) + ch * 8;
+      w8[ct][u] = *(const half8*)(W + (size_t)e * me + off);
+      b8[ct][u] = *(const half8*)(base + (size_t)c * me + off);
+    }
+  }
+  if (words) {
+    if (powner) put(us, uw, usc);
+  } else {
+    for (int idx = tid; idx < r * 64; idx += 256) {
+      const int rho = idx / 64, j = idx % 64;
+      const size_t row = (size_t)e * r + rho;
+      us[rho][j] = (float)u_s[row * (out_d / q) + (o0 + j) / q] * cmp_nib(u_q + row * (out_d / 2), o0 + j);
+    }
+  }
+  float se = 0.f, sw = 0.f;
+#pragma unroll
+  for (int ct = 0; ct < CE_CT; ++ct) {
+    const int i0 = (tile_x * CE_CT + ct) * 64;
+    if (i0 >= in_d) break;   // uniform over the workgroup
+    if (ct > 0) __syncthreads();   // the previous column tile has been consumed
+    if (words) {
+      if (powner) put(vs, vw[ct], vsc[ct]);
+    } else {
+      for (int idx = tid; idx < r * 64; idx += 256) {
+        const int rho = idx / 64, j = idx % 64;
+        const size_t row = (size_t)e * r + rho;
+        vs[rho][j] = (float)v_s[row * (in_d / q) + (i0 + j) / q] * cmp_nib(v_q + row * (in_d / 2), i0 + j);
+      }
+    }
+    __syncthreads();   // us (first tile) and vs are complete
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = row0 + 32 * u;
+      float uv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) uv[i] = 0.f;
+      for (int rho = 0; rho < r; ++rho) {
+        const float uo = us[rho][row];
+        const float4v va = *(const float4v*)&vs[rho][ch * 8], vb = *(const float4v*)&vs[rho][ch * 8 + 4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          uv[i] = fmaf(uo, va[i], uv[i]);
+          uv[4 + i] = fmaf(uo, vb[i], uv[4 + i]);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float w = (float)w8[ct][u][i];
+        const float dv = w - (float)b8[ct][u][i] - uv[i];
+        se = fmaf(dv, dv, se);
+        sw = fmaf(w, w, sw);
+      }
     }
   }
   float v[2] = {se, sw};
@@ -406,10 +572,8 @@ __global__ __launch_bounds__(256) void cmp_error_kernel(const half_t* __restrict
     red[tid >> 6][1] = v[1];
   }
   __syncthreads();
-  if (tid < 2) {
-    const size_t t = (size_t)blockIdx.y * gridDim.x + blockIdx.x, nt = (size_t)gridDim.x * gridDim.y;
-    epart[((size_t)e * nt + t) * 2 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
-  }
+  if (tid < 2)
+    epart[((size_t)e * per_c + tc % per_c) * 2 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
 }
 // err[e * stride] = sqrt(sum epart[..][0]) / sqrt(sum epart[..][1]), FP64, fixed order
 __global__ __launch_bounds__(64) void cmp_error_finish_kernel(const float* __restrict__ epart, int n_tiles, int stride,
@@ -446,7 +610,7 @@ CompressLayout compress_layout(const cmoe_compress_config& c) {
   L.XA = take(E * c.sketch * nmax * 2);
   L.XB = take(E * c.sketch * nmax * 2);
   L.offsets = take((E + 1) * 4);
-  L.part = take(E * tiles * 4 * 4);
+  L.part = take(E * tiles * 4 * 4 * 4);   // four quantities x four wavefront partials per tile
   L.stats = take(E * 4 * 8);
   L.gpart = take(E * ((nmax + 511) / 512) * c.sketch * c.sketch * 4);
   L.coef = take(E * CP_LMAX * CP_LMAX * 4);
@@ -481,7 +645,7 @@ int orth_rows(const cmoe_compress_config& c, int E, int n, const half_t* Xin, ha
               const CompressLayout& L, hipStream_t st) {
   const int l = c.sketch, nch = (n + 511) / 512;
   hipLaunchKernelGGL(cmp_gram_kernel, dim3(nch, E), dim3(256), 0, st, Xin, l, n, (float*)(ws + L.gpart));
-  hipLaunchKernelGGL(cmp_small_kernel<0>, dim3(E), dim3(64), 0, st, (const float*)(ws + L.gpart), nch, l, c.r,
+  hipLaunchKernelGGL(cmp_small_kernel<0>, dim3(E), dim3(CS_THREADS), 0, st, (const float*)(ws + L.gpart), nch, l, c.r,
                      (float*)(ws + L.coef), (double*)(ws + L.lam));
   hipLaunchKernelGGL(cmp_apply_kernel<half_t>, dim3((n + 255) / 256, E), dim3(256), 0, st,
                      (const float*)(ws + L.coef), Xin, l, l, n, Xout);
@@ -520,10 +684,10 @@ extern "C" int cmoe_reconstruction_error(const cmoe_compress_config* cfg, const 
   if (workspace_bytes < L.total) return CMOE_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  const int E = cfg->G * cfg->K, tx = cfg->in_dim / 64, ty = cfg->out_dim / 64;
-  hipLaunchKernelGGL(cmp_error_kernel, dim3(tx, ty, E), dim3(256), 0, st, (const half_t*)W, (const half_t*)base, u_q,
-                     (const half_t*)u_s, v_q, (const half_t*)v_s, cfg->K, cfg->out_dim, cfg->in_dim, cfg->r,
-                     cfg->q_group, (float*)(ws + L.epart));
+  const int E = cfg->G * cfg->K, tx = (cfg->in_dim / 64 + CE_CT - 1) / CE_CT, ty = cfg->out_dim / 64;
+  hipLaunchKernelGGL(cmp_error_kernel, dim3((unsigned)((cfg->G * tx * ty + 7) / 8 * 8 * cfg->K)), dim3(256), 0, st,
+                     (const half_t*)W, (const half_t*)base, u_q, (const half_t*)u_s, v_q, (const half_t*)v_s, cfg->G,
+                     cfg->K, cfg->out_dim, cfg->in_dim, cfg->r, cfg->q_group, tx, ty, (float*)(ws + L.epart));
   hipLaunchKernelGGL(cmp_error_finish_kernel, dim3(E), dim3(64), 0, st, (const float*)(ws + L.epart), tx * ty, 1, err);
   CP_CHECK();
   return CMOE_OK;
@@ -558,7 +722,7 @@ extern "C" int cmoe_compress(const cmoe_compress_config* cfg, const cmoe_f16* W,
   // Eq. 6 and the residuals (and their transposes) against the stored base
   hipLaunchKernelGGL(cmp_residual_kernel, dim3(tx, ty, c.G), dim3(256), 0, st, (const half_t*)W, c.K, out_d, in_d,
                      (half_t*)base, D, DT, (float*)(ws + L.part));
-  hipLaunchKernelGGL(cmp_stats_kernel, dim3(E), dim3(256), 0, st, (const float*)(ws + L.part), tx * ty, stats);
+  hipLaunchKernelGGL(cmp_stats_kernel, dim3(E), dim3(256), 0, st, (const float*)(ws + L.part), tx * ty * 4, stats);
   hipLaunchKernelGGL(cmp_offsets_kernel, dim3((E + 256) / 256), dim3(256), 0, st, E, l, offs);
   hipLaunchKernelGGL(cmp_tile_rows_kernel, dim3((in_d / 8 + 255) / 256, E * l), dim3(256), 0, st, (const half_t*)omega,
                      l, in_d, XA);
@@ -582,7 +746,7 @@ extern "C" int cmoe_compress(const cmoe_compress_config* cfg, const cmoe_f16* W,
   if (launch_skinny_rows(XB, DT, offs, E, in_d, out_d, l, XA, st) != hipSuccess) return CMOE_ERR_HIP;
   const int nch = (in_d + 511) / 512;
   hipLaunchKernelGGL(cmp_gram_kernel, dim3(nch, E), dim3(256), 0, st, XA, l, in_d, (float*)(ws + L.gpart));
-  hipLaunchKernelGGL(cmp_small_kernel<1>, dim3(E), dim3(64), 0, st, (const float*)(ws + L.gpart), nch, l, c.r, coef,
+  hipLaunchKernelGGL(cmp_small_kernel<1>, dim3(E), dim3(CS_THREADS), 0, st, (const float*)(ws + L.gpart), nch, l, c.r, coef,
                      lam);
   hipLaunchKernelGGL(cmp_apply_kernel<float>, dim3((out_d + 255) / 256, E), dim3(256), 0, st, (const float*)coef, XB,
                      l, c.r, out_d, UF);
@@ -596,10 +760,11 @@ extern "C" int cmoe_compress(const cmoe_compress_config* cfg, const cmoe_f16* W,
                      (long)E * c.r, out_d, c.q_group, (const int*)gate, c.r, u_q, (half_t*)u_s);
   hipLaunchKernelGGL(cmp_quantize_kernel, dim3((unsigned)((vg + 255) / 256)), dim3(256), 0, st, (const float*)VF,
                      (long)E * c.r, in_d, c.q_group, (const int*)gate, c.r, v_q, (half_t*)v_s);
-  hipLaunchKernelGGL(cmp_error_kernel, dim3(tx, ty, E), dim3(256), 0, st, (const half_t*)W, (const half_t*)base, u_q,
-                     (const half_t*)u_s, v_q, (const half_t*)v_s, c.K, out_d, in_d, c.r, c.q_group,
-                     (float*)(ws + L.epart));
-  hipLaunchKernelGGL(cmp_error_finish_kernel, dim3(E), dim3(64), 0, st, (const float*)(ws + L.epart), tx * ty, 4,
+  const int etx = (tx + CE_CT - 1) / CE_CT;
+  hipLaunchKernelGGL(cmp_error_kernel, dim3((unsigned)((c.G * etx * ty + 7) / 8 * 8 * c.K)), dim3(256), 0, st,
+                     (const half_t*)W, (const half_t*)base, u_q, (const half_t*)u_s, v_q, (const half_t*)v_s, c.G, c.K,
+                     out_d, in_d, c.r, c.q_group, etx, ty, (float*)(ws + L.epart));
+  hipLaunchKernelGGL(cmp_error_finish_kernel, dim3(E), dim3(64), 0, st, (const float*)(ws + L.epart), etx * ty, 4,
                      report);
   CP_CHECK();
   return CMOE_OK;
