@@ -814,28 +814,29 @@ struct EpiFusedUp {
 
 // ---------------------------------------------------------------- s partial reduction
 // s_down[perm[p]][w] = sum over row tiles of spart[tile][p][w], in a fixed order: a block
-// owns 64 consecutive outputs, its NW wavefronts each sum every NW-th tile, and the NW
-// sums are added in wavefront order.
+// owns 256 consecutive outputs (four per lane, k * r is a multiple of 4 so they belong to one
+// token), its NW wavefronts each sum every NW-th tile, and the NW sums are added in
+// wavefront order.
 template <int NW, class ST>
 __global__ __launch_bounds__(64 * NW) void sreduce_kernel(const ST* __restrict__ spart,
                                                           const int* __restrict__ perm, int T, int kr, int n_tiles,
                                                           float* __restrict__ s_down) {
-  __shared__ float part[NW][64];
+  __shared__ float4v part[NW][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const size_t total = (size_t)T * kr;
-  const size_t idx = (size_t)blockIdx.x * 64 + lane;
-  float sum = 0.f;
+  const size_t idx = ((size_t)blockIdx.x * 64 + lane) * 4;
+  float4v sum = {0.f, 0.f, 0.f, 0.f};
   if (idx < total) {
 #pragma unroll 8
-    for (int nt = wave; nt < n_tiles; nt += NW) sum += (float)spart[(size_t)nt * total + idx];
+    for (int nt = wave; nt < n_tiles; nt += NW) sum += *(const float4v*)(spart + (size_t)nt * total + idx);
   }
   part[wave][lane] = sum;
   __syncthreads();
   if (wave == 0 && idx < total) {
-    float s2 = 0.f;
+    float4v s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < NW; ++w) s2 += part[w][lane];
-    s_down[(size_t)perm[idx / kr] * kr + idx % kr] = s2;
+    *(float4v*)(s_down + (size_t)perm[idx / kr] * kr + idx % kr) = s2;
   }
 }
 
@@ -1058,7 +1059,7 @@ hipError_t launch_sreduce(const cmoe_dims& dm, int T, const int* perm, const flo
                           float* s_down, hipStream_t st) {
   int kr = dm.k * dm.r;
   size_t n = (size_t)T * kr;
-  const dim3 grid((unsigned)((n + 63) / 64));
+  const dim3 grid((unsigned)((n + 255) / 256));
   if (n_parts > 128)
     hipLaunchKernelGGL((sreduce_kernel<16, float>), grid, dim3(1024), 0, st, spart, perm, T, kr, n_parts, s_down);
   else
