@@ -99,6 +99,10 @@ CASES = [
     ("wide_in", 1, 3, 128, 320, 20, 0.2, 0.02, 16, 24, 64),
     ("r32", 2, 2, 192, 256, 40, 0.3, 0.01, 32, 40, 32),
     ("noise_only", 1, 4, 128, 128, 4, 0.0, 0.05, 4, 12, 8),
+    # an odd number of sketch rows (the round-robin Jacobi then has an idle index every round)
+    ("odd_sketch", 1, 3, 128, 192, 10, 0.3, 0.01, 8, 13, 32),
+    # the widest sketch
+    ("sketch48", 1, 2, 128, 128, 30, 0.3, 0.01, 32, 48, 32),
 ]
 
 
