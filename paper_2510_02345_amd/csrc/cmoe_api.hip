@@ -26,7 +26,7 @@ cmoe_ws_layout cmoe_layout(const cmoe_dims& dm, int T) {
   L.u1t = take(sizeof(half_t) * dm.G * dm.d_ff * dm.KRp);
   L.v2p = take(sizeof(half_t) * dm.G * dm.KRp * dm.d_ff);
   L.u2t = take(sizeof(half_t) * dm.G * dm.d * dm.KRp);
-  L.t1ext = take(sizeof(half_t) * Tz * dm.k * dm.KRp);
+  L.t1ext = take(sizeof(half_t) * Tz * dm.k * dm.r);
   L.a = take(sizeof(half_t) * Tz * dm.d_ff);
   L.ures = take(T <= SKINNY_T ? sizeof(float) * Tz * dm.d : 0);
   L.stats_part = take(sizeof(float) * stats_partial_slots(dm, T) * dm.K * dm.d);

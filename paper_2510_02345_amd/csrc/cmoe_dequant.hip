@@ -10,12 +10,8 @@ namespace {
 __device__ __forceinline__ float nib_lo(unsigned b) { return (float)((int)(b << 28) >> 28); }
 __device__ __forceinline__ float nib_hi(unsigned b) { return (float)((int)(b << 24) >> 28); }
 
-// Row-preserving panel: out[c][kk][pos(n)] = factor[c*K + kk/r][kk%r][n], rows kk >= K*r
-// zero.  With PERMUTE16, positions inside every aligned group of 16 are reordered as
-// n = 8a + 4h + i  ->  8h + 4a + i, which is the order in which one lane of a 32x32
-// accumulator block holds its rows (used for the V2 panel, see the fused up-projection).
+// Row-preserving panel: out[c][kk][n] = factor[c*K + kk/r][kk%r][n], rows kk >= K*r zero.
 // Block (bx, kk, c) of a grid ((L / 8 + 255) / 256, KRp, G).
-template <bool PERMUTE16>
 __device__ __forceinline__ void dequant_rows(int bx, int kk, int c, const uint8_t* __restrict__ qv,
                                              const half_t* __restrict__ sv, int L, int q, int K, int r, int KRp,
                                              const int* __restrict__ offsets, half_t* __restrict__ out) {
@@ -25,31 +21,14 @@ __device__ __forceinline__ void dequant_rows(int bx, int kk, int c, const uint8_
   half8 o = {0, 0, 0, 0, 0, 0, 0, 0};
   if (kk < K * r) {
     const size_t row = (size_t)(c * K) * r + kk;  // (expert, rho) flattened: e*r + rho
-    if (!PERMUTE16) {
-      // q is a multiple of 8, so the 8 aligned elements share one scale
-      unsigned bytes = *(const unsigned*)(qv + row * (L / 2) + n8 / 2);
-      float sc = (float)sv[row * (L / q) + n8 / q];
+    // q is a multiple of 8, so the 8 aligned elements share one scale
+    unsigned bytes = *(const unsigned*)(qv + row * (L / 2) + n8 / 2);
+    float sc = (float)sv[row * (L / q) + n8 / q];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        unsigned b = (bytes >> (8 * i)) & 0xffu;
-        o[2 * i] = (half_t)(sc * nib_lo(b));
-        o[2 * i + 1] = (half_t)(sc * nib_hi(b));
-      }
-    } else {
-      // output positions n8..n8+7 of the permuted row = h fixed, a in {0,1}, i in 0..3
-      int g16 = n8 & ~15, h = (n8 >> 3) & 1;
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        int n = g16 + 8 * a + 4 * h;  // 4 consecutive source elements = 2 bytes
-        unsigned bytes = *(const unsigned short*)(qv + row * (L / 2) + n / 2);
-        float sc = (float)sv[row * (L / q) + n / q];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          unsigned b = (bytes >> (8 * (i >> 1))) & 0xffu;
-          float code = (i & 1) ? nib_hi(b) : nib_lo(b);
-          o[4 * a + i] = (half_t)(sc * code);
-        }
-      }
+    for (int i = 0; i < 4; ++i) {
+      unsigned b = (bytes >> (8 * i)) & 0xffu;
+      o[2 * i] = (half_t)(sc * nib_lo(b));
+      o[2 * i + 1] = (half_t)(sc * nib_hi(b));
     }
   }
   *(half8*)(out + ((size_t)c * KRp + kk) * L + n8) = o;
@@ -102,7 +81,7 @@ struct DequantJob {
   const uint8_t* qv;
   const half_t* sv;
   half_t* out;
-  int L, kind;          // kind 0: rows, 1: rows with the 16-group permutation, 2: transposed
+  int L, kind;          // kind 0: rows, 2: transposed
   unsigned nx, first;   // blocks per (kk, c) or per c; first linear block of the job
 };
 struct DequantJobs {
@@ -122,8 +101,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(DequantJobs jobs, int q, i
                       tile);
   } else {
     const int bx = (int)(local % jb.nx), kk = (int)((local / jb.nx) % KRp), c = (int)(local / jb.nx / KRp);
-    if (jb.kind == 1) dequant_rows<true>(bx, kk, c, jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out);
-    else dequant_rows<false>(bx, kk, c, jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out);
+    dequant_rows(bx, kk, c, jb.qv, jb.sv, jb.L, q, K, r, KRp, offsets, jb.out);
   }
 }
 

@@ -179,10 +179,14 @@ struct FusedUp {
                                                     const Need& nd, int k, int q, UF uf, VF vf, float (&o)[8],
                                                     float4v (&sacc)[KMAX][NSP]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = 0.f;
-#pragma unroll
     for (int j = 0; j < KMAX; ++j) {
-      if (j >= k) continue;
+      if (j >= k) {
+        if (j == 0) {   // k >= 1 always; keeps o defined for the compiler
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = 0.f;
+        }
+        continue;
+      }
       const int ej = t.e[j];
       float4v h0 = hb0, h1 = hb1;
       for (unsigned m = nd.chunks[j]; m != 0u; m &= m - 1u) {
@@ -200,7 +204,7 @@ struct FusedUp {
       half8 ab;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        o[i] = fmaf(t.g[j], a[i], o[i]);
+        o[i] = j == 0 ? t.g[0] * a[i] : fmaf(t.g[j], a[i], o[i]);
         ab[i] = (half_t)a[i];
       }
       const int p0 = (ej * R) >> 4;   // first pass of the expert's rank rows

@@ -58,9 +58,10 @@ struct cmoe_ws_layout {
   size_t sort_i32;    // int32 [2][T]          expert-pair order inside clusters: rowmap, perm2
   size_t v1cat;       // f16 [G][KRp][d]       dequantised V1, rows kk = j*r + rho
   size_t u1t;         // f16 [G][d_ff][KRp]    dequantised U1, transposed
-  size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2, columns permuted inside 16-groups
+  size_t v2p;         // f16 [G][KRp][d_ff]    dequantised V2
   size_t u2t;         // f16 [G][d][KRp]       dequantised U2, transposed
-  size_t t1ext;       // f16 [T][k][KRp]       V1 x, one-hot expanded over the cluster's experts
+  size_t t1ext;       // f16 [T][k][r]         t1_j = V1 x of the selected experts, sorted rows (expanded
+                      //                       one-hot over the cluster's rank rows only in registers)
   size_t a;           // f16 [T][d_ff]         gated hidden activations, cluster-sorted rows; stored as
                       //                       [d_ff/32][T][32] on the matrix-core path
   size_t ures;        // f32 [T][d]            residual-down term, sorted rows (weight-streaming path only)
