@@ -164,12 +164,14 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const half_t* __restrict__ 
     dot[j] = 0.f;
   }
   for (int col = threadIdx.x * 4; col < d_ff; col += 1024) {
-    const half4 hv = *(const half4*)(hb + t * d_ff + col), dv = *(const half4*)(dab + t * d_ff + col);
+    const half4 hv = __builtin_nontemporal_load((const half4*)(hb + t * d_ff + col));
+    const half4 dv = __builtin_nontemporal_load((const half4*)(dab + t * d_ff + col));
     float dhs[4] = {0.f, 0.f, 0.f, 0.f}, ags[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) {
       if (j >= k) break;
-      const half4 r1 = *(const half4*)(rh + prow[j] * d_ff + col), r2 = *(const half4*)(rda + prow[j] * d_ff + col);
+      const half4 r1 = __builtin_nontemporal_load((const half4*)(rh + prow[j] * d_ff + col));
+      const half4 r2 = __builtin_nontemporal_load((const half4*)(rda + prow[j] * d_ff + col));
       half4 ao, ho;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -183,8 +185,8 @@ __global__ __launch_bounds__(256) void bw_act_kernel(const half_t* __restrict__ 
         dhs[i] += dh;
         ags[i] += g[j] * a;
       }
-      *(half4*)(a16 + prow[j] * d_ff + col) = ao;
-      *(half4*)(dh16 + prow[j] * d_ff + col) = ho;
+      __builtin_nontemporal_store(ao, (half4*)(a16 + prow[j] * d_ff + col));
+      __builtin_nontemporal_store(ho, (half4*)(dh16 + prow[j] * d_ff + col));
     }
     *(half4*)(dhsum16 + t * d_ff + col) = half4{(half_t)dhs[0], (half_t)dhs[1], (half_t)dhs[2], (half_t)dhs[3]};
     *(half4*)(ag16 + t * d_ff + col) = half4{(half_t)ags[0], (half_t)ags[1], (half_t)ags[2], (half_t)ags[3]};
@@ -369,8 +371,8 @@ __global__ __launch_bounds__(256) void bw_rankexpand_kernel(const half_t* __rest
     for (int u = 0; u < 4; ++u) {
       if (pb + u >= p1) break;
       if constexpr (sizeof(OutT) == 2)
-        *(half4*)(out + row[u] * L + col) =
-            half4{(half_t)acc[u][0], (half_t)acc[u][1], (half_t)acc[u][2], (half_t)acc[u][3]};
+        __builtin_nontemporal_store(half4{(half_t)acc[u][0], (half_t)acc[u][1], (half_t)acc[u][2], (half_t)acc[u][3]},
+                                    (half4*)(out + row[u] * L + col));
       else
         *(float4v*)(out + row[u] * L + col) = float4v{acc[u][0], acc[u][1], acc[u][2], acc[u][3]};
     }
