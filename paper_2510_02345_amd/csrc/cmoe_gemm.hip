@@ -20,8 +20,8 @@ namespace {
 // Tile of one workgroup: BN weight rows x BM tokens, WAVES_N x WAVES_M wavefronts, each
 // owning (BN/WAVES_N) x (BM/WAVES_M) outputs as 16x16 accumulator blocks.  Operand tiles
 // move global -> LDS with direct-to-LDS loads (no register staging) into NS stages of 32
-// contraction elements; rows are 64 B, their four 16-B chunks XOR-swizzled with
-// (row >> 2) & 3 so that the 16 lanes the LDS serves per cycle hit 64 distinct banks.  The
+// contraction elements; rows are 64 B, their four 16-B chunks XOR-swizzled with swz(row)
+// so that the 16 lanes the LDS serves per cycle hit 64 distinct banks.  The
 // weight rows of a tile are stored in MFMA order: tile row rho holds weight row pi_row(rho).
 template <int BN_, int BM_, int WAVES_N_, int WAVES_M_, int NS_, int OCC_, bool PINGPONG_, int XSM_, int XSN_>
 struct Tile {

@@ -568,7 +568,7 @@ __global__ __launch_bounds__(PS_THREADS) void pair_sort_kernel(const int* __rest
 
 // Refines the cluster-sorted order: inside every cluster, rows are ordered by (first
 // selected expert, second selected expert, original order).  Cluster boundaries (offsets)
-// do not move.  Rows of a 32-token block then mostly share their experts, so the fused
+// do not move.  Rows of a 16-token block then mostly share their experts, so the fused
 // up-projection skips most rank chunks.
 hipError_t launch_pair_sort(const cmoe_dims& dm, const int* perm, const int* offsets, const int* expert_idx, int T,
                             int* rowmap, int* perm2, hipStream_t st) {
